@@ -1,0 +1,174 @@
+"""CPU oracle for the dedup dispatch/combine path -- TEST INFRASTRUCTURE ONLY.
+
+A ctypes front end to ``hmo.c`` (plain single-threaded C, written from the paper:
+HierMoE Eq.(7) and Sections II-A/B, III-A, IV).  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; the product path never does and
+shares no code with it.  Arrays are numpy, on the host.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hmo.c")
+_LIB = os.path.join(_HERE, "libhmo.so")
+
+LEVEL_NONE, LEVEL_GPU, LEVEL_NODE = 0, 1, 2
+BAD_ID = -7
+
+# No -ffast-math, no contraction: the float adds and the single float multiply must be IEEE.
+CFLAGS = ["-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC"]
+
+
+def build(force: bool = False) -> str:
+    """Compile hmo.c with gcc into libhmo.so next to it."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.hmo_f64_to_bf16.restype = ctypes.c_uint16
+        _lib.hmo_f64_to_bf16.argtypes = [ctypes.c_double]
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _c(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+@dataclass
+class Plan:
+    level: int
+    num_dest: int
+    dest_count: np.ndarray    # [num_dest] int32
+    dest_offset: np.ndarray   # [num_dest+1] int32
+    row_token: np.ndarray     # [total_rows] int32
+    slot_row: np.ndarray      # [T,K] int32
+    slot_keep: np.ndarray     # [T,K] uint8
+    row_weight: np.ndarray    # [total_rows] float32
+    rank_mask: np.ndarray     # [T] uint64
+    node_mask: np.ndarray     # [T] uint32
+    status: int
+
+    @property
+    def total_rows(self) -> int:
+        return int(self.dest_offset[-1])
+
+
+def plan(topk_ids, topk_weights, expert_to_rank, nodes: int, ranks_per_node: int, level: int) -> Plan:
+    lib = _load()
+    ids = _c(topk_ids, np.int32)
+    w = _c(topk_weights, np.float32)
+    e2r = _c(expert_to_rank, np.int32)
+    T, K = ids.shape
+    E = e2r.shape[0]
+    G = nodes * ranks_per_node
+    Dn = nodes if level == LEVEL_NODE else G
+    dest_count = np.zeros(max(Dn, 1), np.int32)
+    dest_offset = np.zeros(max(Dn, 1) + 1, np.int32)
+    row_token = np.full(max(T * K, 1), -1, np.int32)
+    slot_row = np.full((T, K), -1, np.int32)
+    slot_keep = np.zeros((T, K), np.uint8)
+    row_weight = np.zeros(max(T * K, 1), np.float32)
+    rank_mask = np.zeros(max(T, 1), np.uint64)
+    node_mask = np.zeros(max(T, 1), np.uint32)
+    status = np.zeros(1, np.int32)
+    rc = lib.hmo_plan(_p(ids), _p(w), _p(e2r), ctypes.c_int32(T), ctypes.c_int32(K), ctypes.c_int32(E),
+                      ctypes.c_int32(nodes), ctypes.c_int32(ranks_per_node), ctypes.c_int32(level),
+                      _p(dest_count), _p(dest_offset), _p(row_token), _p(slot_row), _p(slot_keep),
+                      _p(row_weight), _p(rank_mask), _p(node_mask), _p(status))
+    if rc != 0:
+        raise ValueError("hmo_plan: argument error %d" % rc)
+    total = int(dest_offset[Dn])
+    return Plan(level, Dn, dest_count[:Dn], dest_offset[:Dn + 1], row_token[:total].copy(), slot_row, slot_keep,
+                row_weight[:total].copy(), rank_mask[:T], node_mask[:T], int(status[0]))
+
+
+def dispatch_pack(x_rows: np.ndarray, row_token: np.ndarray) -> np.ndarray:
+    """packed[row] = x[row_token[row]]; x is [T, ...] of any fixed-size dtype, rows are copied as bytes."""
+    lib = _load()
+    x = np.ascontiguousarray(x_rows)
+    rt = _c(row_token, np.int32)
+    T = x.shape[0]
+    row_bytes = x.strides[0] if x.ndim > 1 else x.itemsize
+    out = np.empty((rt.shape[0],) + x.shape[1:], dtype=x.dtype)
+    rc = lib.hmo_dispatch_pack(_p(x), ctypes.c_int64(T), ctypes.c_int64(row_bytes), _p(rt),
+                               ctypes.c_int64(rt.shape[0]), _p(out))
+    if rc != 0:
+        raise ValueError("hmo_dispatch_pack: argument error %d" % rc)
+    return out
+
+
+def combine(y_bf16: np.ndarray, topk_weights, slot_row) -> np.ndarray:
+    """out[t] = bf16(sum_k w[t,k] * Y[slot_row[t,k]]) in binary64; y and out are uint16 bf16 encodings."""
+    lib = _load()
+    y = _c(y_bf16, np.uint16)
+    w = _c(topk_weights, np.float32)
+    sr = _c(slot_row, np.int32)
+    T, K = sr.shape
+    H = y.shape[1]
+    out = np.empty((T, H), np.uint16)
+    rc = lib.hmo_combine(_p(y), ctypes.c_int64(y.shape[0]), _p(w), _p(sr), ctypes.c_int64(T), ctypes.c_int32(K),
+                         ctypes.c_int64(H), _p(out))
+    if rc != 0:
+        raise ValueError("hmo_combine: argument error %d" % rc)
+    return out
+
+
+def combine_transpose(gout: np.ndarray, row_token, row_weight) -> np.ndarray:
+    """gy[row] = row_weight[row] * gout[row_token[row]] (fp32)."""
+    lib = _load()
+    g = _c(gout, np.float32)
+    rt = _c(row_token, np.int32)
+    rw = _c(row_weight, np.float32)
+    T, H = g.shape
+    gy = np.empty((rt.shape[0], H), np.float32)
+    rc = lib.hmo_combine_transpose(_p(g), ctypes.c_int64(T), ctypes.c_int64(H), _p(rt), _p(rw),
+                                   ctypes.c_int64(rt.shape[0]), _p(gy))
+    if rc != 0:
+        raise ValueError("hmo_combine_transpose: argument error %d" % rc)
+    return gy
+
+
+def expert_load(topk_ids, expert_to_rank, nodes: int, ranks_per_node: int):
+    """(load_expert[E], load_rank[G], load_node[nodes], status)."""
+    lib = _load()
+    ids = _c(topk_ids, np.int32)
+    e2r = _c(expert_to_rank, np.int32)
+    T, K = ids.shape
+    E = e2r.shape[0]
+    G = nodes * ranks_per_node
+    le = np.zeros(E, np.int32)
+    lr = np.zeros(G, np.int32)
+    ln = np.zeros(nodes, np.int32)
+    status = np.zeros(1, np.int32)
+    rc = lib.hmo_expert_load(_p(ids), _p(e2r), ctypes.c_int32(T), ctypes.c_int32(K), ctypes.c_int32(E),
+                             ctypes.c_int32(nodes), ctypes.c_int32(ranks_per_node), _p(le), _p(lr), _p(ln),
+                             _p(status))
+    if rc != 0:
+        raise ValueError("hmo_expert_load: argument error %d" % rc)
+    return le, lr, ln, int(status[0])
+
+
+def f64_to_bf16(v: float) -> int:
+    return int(_load().hmo_f64_to_bf16(float(v)))

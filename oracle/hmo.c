@@ -1,0 +1,284 @@
+/*
+ * hmo.c -- CPU oracle for hierarchical token deduplication (dispatch plan, pack, combine).
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, single-threaded C; no SIMD, no threads, no blocking
+ * or fusion.  It exists so the HIP path can be checked against something written directly
+ * from the paper; it shares no code with that path and the product never calls it.
+ *
+ * What the paper fixes (HierMoE, Section III-C, Eq.(7)): an expert group's routing mask is the
+ * OR of its experts' masks, so a token is sent to a group at most once, and the duplicate-free
+ * count of a group is the number of tokens whose group mask is set.  Groups are the G ranks
+ * ("HD1", one group per GPU) or the U[1] nodes ("HD2" inter-node hop), Section III-A/III-B.
+ * What the paper leaves open (row order, which duplicate survives, combine formula) is fixed
+ * by the readings listed next to each function.
+ *
+ * All pointers are host pointers.  Every function returns 0 on success, a negative value on
+ * an argument error (nothing written).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { HMO_LEVEL_NONE = 0, HMO_LEVEL_GPU = 1, HMO_LEVEL_NODE = 2 };
+enum { HMO_OK = 0, HMO_ERR_ARG = -1, HMO_BAD_ID = -7 };
+
+/* Destination of one slot at a level, or -1 when the expert id or its rank is out of range.
+ * Rank of an expert: expert_to_rank (contiguous blocks in Eq.(7); an arbitrary map here so that
+ * an expert swap of Section IV is an exchange of two entries).  Node of a rank: rank / R, ranks
+ * of one node being contiguous (Section III-B, the index illustration of Fig.6). */
+static int slot_rank(const int32_t *expert_to_rank, int32_t E, int32_t G, int32_t id)
+{
+    if (id < 0 || id >= E) return -1;
+    int32_t g = expert_to_rank[id];
+    if (g < 0 || g >= G) return -1;
+    return g;
+}
+
+static int slot_dest(int rank, int32_t ranks_per_node, int32_t level)
+{
+    if (rank < 0) return -1;
+    return level == HMO_LEVEL_NODE ? rank / ranks_per_node : rank;
+}
+
+/*
+ * hmo_plan -- Eq.(7) turned into per-destination send lists for one rank's T tokens.
+ *
+ *  step 1  d(t,k)      destination of slot (t,k) at the level (rank for none/gpu, node for node).
+ *  step 2  slot_keep   none: every valid slot.  gpu/node: a slot is kept iff no earlier slot
+ *                      k' < k of the same token has the same destination -- the OR of Eq.(7)
+ *                      leaves one copy per (token, group); "earlier slot wins" is this build's
+ *                      reading (the paper only defines the OR).
+ *  step 3  dest_count  p[j] = number of kept slots with destination j (second line of Eq.(7));
+ *                      dest_offset = its exclusive prefix sum, dest_offset[Dn] = total rows.
+ *  step 4  rows        kept slots are numbered inside their destination in ascending flat slot
+ *                      index t*K+k (so: ascending token; at level none ties inside a token by k).
+ *                      row_token[row] = t.  slot_row[t,k] = the row that carries token t to
+ *                      d(t,k), for kept and non-kept slots alike; -1 for invalid slots.
+ *  step 5  row_weight  fp32 sum, in ascending k, of the router weights of the slots a row serves.
+ *  step 6  masks       rank_mask[t] = OR_k 1<<rank, node_mask[t] = OR_k 1<<node (level-free).
+ *
+ * Invalid slots (expert id outside [0,E), rank outside [0,G)) are dropped everywhere and
+ * *status is set to HMO_BAD_ID.  rank_mask / node_mask may be NULL.
+ * Buffers: dest_count[Dn], dest_offset[Dn+1], row_token/row_weight[>= T*K], slot_row/slot_keep[T*K].
+ */
+int hmo_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+             int32_t T, int32_t K, int32_t E, int32_t nodes, int32_t ranks_per_node, int32_t level,
+             int32_t *dest_count, int32_t *dest_offset, int32_t *row_token, int32_t *slot_row,
+             uint8_t *slot_keep, float *row_weight, uint64_t *rank_mask, uint32_t *node_mask,
+             int32_t *status)
+{
+    if (!topk_ids || !topk_weights || !expert_to_rank || !dest_count || !dest_offset || !row_token ||
+        !slot_row || !slot_keep || !row_weight || !status)
+        return HMO_ERR_ARG;
+    if (T < 0 || K <= 0 || E <= 0 || nodes <= 0 || ranks_per_node <= 0) return HMO_ERR_ARG;
+    if (level != HMO_LEVEL_NONE && level != HMO_LEVEL_GPU && level != HMO_LEVEL_NODE) return HMO_ERR_ARG;
+    const int32_t G = nodes * ranks_per_node;
+    if (G > 64 || nodes > 32) return HMO_ERR_ARG;
+    const int32_t Dn = (level == HMO_LEVEL_NODE) ? nodes : G;
+
+    *status = HMO_OK;
+    int *dest = (int *)malloc(sizeof(int) * (size_t)(T > 0 ? T : 1) * (size_t)K);
+    if (!dest) return HMO_ERR_ARG;
+
+    /* steps 1, 2, 6 */
+    for (int32_t t = 0; t < T; ++t) {
+        uint64_t rm = 0;
+        uint32_t nm = 0;
+        for (int32_t k = 0; k < K; ++k) {
+            const size_t s = (size_t)t * K + k;
+            const int rank = slot_rank(expert_to_rank, E, G, topk_ids[s]);
+            dest[s] = slot_dest(rank, ranks_per_node, level);
+            if (rank < 0) {
+                *status = HMO_BAD_ID;
+                slot_keep[s] = 0;
+                continue;
+            }
+            rm |= (uint64_t)1 << rank;
+            nm |= (uint32_t)1 << (rank / ranks_per_node);
+            int keep = 1;
+            if (level != HMO_LEVEL_NONE)
+                for (int32_t k1 = 0; k1 < k; ++k1)
+                    if (dest[(size_t)t * K + k1] == dest[s]) keep = 0;
+            slot_keep[s] = (uint8_t)keep;
+        }
+        if (rank_mask) rank_mask[t] = rm;
+        if (node_mask) node_mask[t] = nm;
+    }
+
+    /* step 3 */
+    for (int32_t d = 0; d < Dn; ++d) dest_count[d] = 0;
+    for (size_t s = 0; s < (size_t)T * K; ++s)
+        if (slot_keep[s]) dest_count[dest[s]] += 1;
+    dest_offset[0] = 0;
+    for (int32_t d = 0; d < Dn; ++d) dest_offset[d + 1] = dest_offset[d] + dest_count[d];
+
+    /* step 4 */
+    int32_t cursor[64];
+    int32_t row_of[64];
+    for (int32_t d = 0; d < Dn; ++d) cursor[d] = dest_offset[d];
+    for (int32_t t = 0; t < T; ++t) {
+        for (int32_t d = 0; d < Dn; ++d) row_of[d] = -1;
+        for (int32_t k = 0; k < K; ++k) {
+            const size_t s = (size_t)t * K + k;
+            if (dest[s] < 0) { slot_row[s] = -1; continue; }
+            if (slot_keep[s]) {
+                const int32_t row = cursor[dest[s]]++;
+                row_token[row] = t;
+                row_of[dest[s]] = row;      /* at level none a later slot overwrites: each slot has its own row */
+                slot_row[s] = row;
+            } else {
+                slot_row[s] = row_of[dest[s]];
+            }
+        }
+    }
+
+    /* step 5 */
+    const int32_t total = dest_offset[Dn];
+    uint8_t *seen = (uint8_t *)calloc((size_t)(total > 0 ? total : 1), 1);
+    if (!seen) { free(dest); return HMO_ERR_ARG; }
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t k = 0; k < K; ++k) {
+            const size_t s = (size_t)t * K + k;
+            const int32_t row = slot_row[s];
+            if (row < 0) continue;
+            if (!seen[row]) { row_weight[row] = topk_weights[s]; seen[row] = 1; }
+            else            { row_weight[row] = row_weight[row] + topk_weights[s]; }
+        }
+    free(seen);
+    free(dest);
+    return HMO_OK;
+}
+
+/*
+ * hmo_dispatch_pack -- the deduplicated send buffer (Section III-A, the Fig.5 example): one copy
+ * of token row_token[row] per packed row; destination d owns rows [dest_offset[d], dest_offset[d+1]).
+ * Rows are `row_bytes` opaque bytes (bf16: 2*H).
+ */
+int hmo_dispatch_pack(const void *x, int64_t T, int64_t row_bytes, const int32_t *row_token,
+                      int64_t n_rows, void *packed)
+{
+    if (!x || !row_token || !packed || T < 0 || row_bytes <= 0 || n_rows < 0) return HMO_ERR_ARG;
+    const unsigned char *src = (const unsigned char *)x;
+    unsigned char *dst = (unsigned char *)packed;
+    for (int64_t row = 0; row < n_rows; ++row) {
+        const int32_t t = row_token[row];
+        if (t < 0 || t >= T) return HMO_ERR_ARG;
+        for (int64_t b = 0; b < row_bytes; ++b) dst[row * row_bytes + b] = src[(int64_t)t * row_bytes + b];
+    }
+    return HMO_OK;
+}
+
+/* bf16 encoding -> double (exact). */
+static double bf16_to_f64(uint16_t b)
+{
+    uint32_t u = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/*
+ * Round a finite double to the nearest bf16 (8 exponent bits, 7 stored fraction bits), ties to
+ * even, in ONE rounding: scale so that one bf16 ulp becomes 1.0, round to an integer with the
+ * default rounding mode (nearest even), scale back.  Every intermediate is exact in binary64.
+ */
+static uint16_t f64_to_bf16_rne(double v)
+{
+    if (v != v) return 0x7FC0;
+    if (v == 0.0) return signbit(v) ? 0x8000 : 0x0000;
+    int e;
+    (void)frexp(fabs(v), &e);          /* |v| = m * 2^e, m in [0.5,1)  ->  |v| in [2^(e-1), 2^e) */
+    int ulp_exp = (e - 1) - 7;         /* ulp of a bf16 normal in that binade                      */
+    if (ulp_exp < -133) ulp_exp = -133; /* subnormal spacing 2^-126 * 2^-7                          */
+    const double q = nearbyint(ldexp(v, -ulp_exp));
+    const double r = ldexp(q, ulp_exp);
+    if (fabs(r) >= ldexp(1.0, 128)) return signbit(v) ? 0xFF80 : 0x7F80;
+    const float f = (float)r;          /* exact: r has at most 8 significant bits */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(u >> 16);
+}
+
+/*
+ * hmo_combine -- the weighted merge of expert outputs (Section II-A/II-B: the layer output of a
+ * token is the gate-weighted sum of its K experts' outputs; "AlltoAll Combine" brings them back).
+ * Y has the packed layout, one row per (token, destination); slot (t,k) reads row slot_row[t,k]:
+ *     out[t][j] = bf16( sum_k  w[t,k] * Y[slot_row[t,k]][j] ),   sum in binary64, ascending k,
+ * rounded once to bf16.  Slots with slot_row < 0 (dropped) contribute nothing.
+ */
+int hmo_combine(const uint16_t *y, int64_t y_rows, const float *topk_weights, const int32_t *slot_row,
+                int64_t T, int32_t K, int64_t H, uint16_t *out)
+{
+    if (!y || !topk_weights || !slot_row || !out || T < 0 || K <= 0 || H <= 0) return HMO_ERR_ARG;
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t j = 0; j < H; ++j) {
+            double acc = 0.0;
+            for (int32_t k = 0; k < K; ++k) {
+                const int64_t row = slot_row[t * K + k];
+                if (row < 0) continue;
+                if (row >= y_rows) return HMO_ERR_ARG;
+                acc += (double)topk_weights[t * K + k] * bf16_to_f64(y[row * H + j]);
+            }
+            out[t * H + j] = f64_to_bf16_rne(acc);
+        }
+    return HMO_OK;
+}
+
+/*
+ * hmo_combine_transpose -- adjoint of hmo_combine with respect to Y: the gradient of packed row
+ * `row` is the row's aggregated router weight times the output gradient of its token,
+ *     gy[row][j] = row_weight[row] * gout[row_token[row]][j]     (one binary32 multiply).
+ */
+int hmo_combine_transpose(const float *gout, int64_t T, int64_t H, const int32_t *row_token,
+                          const float *row_weight, int64_t n_rows, float *gy)
+{
+    if (!gout || !row_token || !row_weight || !gy || T < 0 || H <= 0 || n_rows < 0) return HMO_ERR_ARG;
+    for (int64_t row = 0; row < n_rows; ++row) {
+        const int32_t t = row_token[row];
+        if (t < 0 || t >= T) return HMO_ERR_ARG;
+        for (int64_t j = 0; j < H; ++j) {
+            volatile float p = row_weight[row] * gout[(int64_t)t * H + j];
+            gy[row * H + j] = p;
+        }
+    }
+    return HMO_OK;
+}
+
+/*
+ * hmo_expert_load -- the counts an expert-swap planner consumes (Section IV): the raw number of
+ * slots per expert (what duplicate-unaware planners count) and the duplicate-free number of tokens
+ * per rank, p^(1,G), and per node, p^(1,U[1]), of Eq.(7).  Written from the set definition: a
+ * token counts once for a group if any of its valid slots lands in the group.
+ */
+int hmo_expert_load(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                    int32_t nodes, int32_t ranks_per_node, int32_t *load_expert, int32_t *load_rank,
+                    int32_t *load_node, int32_t *status)
+{
+    if (!topk_ids || !expert_to_rank || !load_expert || !load_rank || !load_node || !status) return HMO_ERR_ARG;
+    if (T < 0 || K <= 0 || E <= 0 || nodes <= 0 || ranks_per_node <= 0) return HMO_ERR_ARG;
+    const int32_t G = nodes * ranks_per_node;
+    if (G > 64 || nodes > 32) return HMO_ERR_ARG;
+    *status = HMO_OK;
+    for (int32_t e = 0; e < E; ++e) load_expert[e] = 0;
+    for (int32_t g = 0; g < G; ++g) load_rank[g] = 0;
+    for (int32_t n = 0; n < nodes; ++n) load_node[n] = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        int in_rank[64] = {0};
+        int in_node[32] = {0};
+        for (int32_t k = 0; k < K; ++k) {
+            const int32_t id = topk_ids[(size_t)t * K + k];
+            const int rank = slot_rank(expert_to_rank, E, G, id);
+            if (rank < 0) { *status = HMO_BAD_ID; continue; }
+            load_expert[id] += 1;
+            in_rank[rank] = 1;
+            in_node[rank / ranks_per_node] = 1;
+        }
+        for (int32_t g = 0; g < G; ++g) load_rank[g] += in_rank[g];
+        for (int32_t n = 0; n < nodes; ++n) load_node[n] += in_node[n];
+    }
+    return HMO_OK;
+}
+
+/* Exposed so tests can pin the rounding routine by itself. */
+uint16_t hmo_f64_to_bf16(double v) { return f64_to_bf16_rne(v); }

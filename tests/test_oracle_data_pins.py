@@ -1,0 +1,169 @@
+"""Pins for the oracle's data functions: bf16 rounding, dispatch pack, combine, transpose.
+
+CPU only.  The references here are exact rational arithmetic (fractions), numpy library
+routines for the special cases that reduce to them (plain MoE permute and weighted sum at
+dedup level none), algebraic identities (round trip, adjoint) and the closed form of the
+scaled-expert model.
+"""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from helpers import GPU, NODE, NONE, bf16_ulp_distance, exact_round_to_bf16
+from paper_2508_09591_amd import workloads as W
+
+
+# ---- rounding binary64 -> bf16 --------------------------------------------------------------
+def test_bf16_rounding_is_identity_on_bf16_values(oracle):
+    for enc in list(range(0, 0x7F80, 97)) + [0x0001, 0x007F, 0x0080, 0x7F7F]:
+        for sign in (0, 0x8000):
+            v = float(W.bf16_bits_to_f64(np.array([enc | sign], np.uint16))[0])
+            assert oracle.f64_to_bf16(v) == (enc | sign)
+
+
+def test_bf16_rounding_against_exact_rationals(oracle):
+    rng = np.random.default_rng(0)
+    vals = list(rng.standard_normal(400) * np.exp(rng.uniform(-90, 90, 400)))
+    # exact midpoints between neighbouring bf16 values (ties) and their two double neighbours
+    for enc in (0x3F80, 0x3F81, 0x4000, 0x0001, 0x007F, 0x0080, 0x7F7E, 0x3EFF, 0x0000):
+        lo = float(W.bf16_bits_to_f64(np.array([enc], np.uint16))[0])
+        hi = float(W.bf16_bits_to_f64(np.array([enc + 1], np.uint16))[0])
+        mid = (lo + hi) / 2                       # exact in binary64
+        vals += [mid, np.nextafter(mid, 0.0), np.nextafter(mid, np.inf), -mid]
+    # a double that rounds differently when it is first rounded to binary32 (double rounding)
+    vals.append(1.0 + 2.0 ** -8 + 2.0 ** -40)      # just above the tie 1 + 2^-8 -> must round up
+    vals.append(1.0 + 2.0 ** -8 - 2.0 ** -40)      # just below -> must round down
+    vals += [3.4e38, -3.4e38, 3.3895e38, 1e-45, 4.6e-41, 9.2e-41, 0.0, -0.0]
+    for v in vals:
+        v = float(v)
+        got = oracle.f64_to_bf16(v)
+        if v == 0.0:                      # a rational has no signed zero
+            assert got == (0x8000 if np.signbit(v) else 0), v
+        else:
+            assert got == exact_round_to_bf16(Fraction(v)), v
+    assert oracle.f64_to_bf16(1.0 + 2.0 ** -8 + 2.0 ** -40) == 0x3F81
+    assert oracle.f64_to_bf16(1.0 + 2.0 ** -8 - 2.0 ** -40) == 0x3F80
+    assert oracle.f64_to_bf16(1.0 + 2.0 ** -8) == 0x3F80           # tie -> even
+    assert oracle.f64_to_bf16(1.0 + 3 * 2.0 ** -8) == 0x3F82       # tie -> even (up)
+
+
+# ---- dispatch pack ----------------------------------------------------------------------------
+@pytest.mark.parametrize("name,level", [("tiny", NONE), ("tiny", GPU), ("tiny", NODE), ("qwen3", GPU), ("qwen3", NODE)])
+def test_dispatch_pack_rows(oracle, name, level):
+    wl = W.WORKLOADS[name]
+    T = min(wl.T, 1024)
+    r = W.make_routing(wl, T=T)
+    x = W.make_activations(wl, T=T, H=min(wl.H, 512))
+    p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+    packed = oracle.dispatch_pack(x, p.row_token)
+    assert packed.shape == (p.total_rows, x.shape[1])
+    # every slot finds its token's row in the destination's buffer
+    assert np.array_equal(packed[p.slot_row.reshape(-1)], np.repeat(x, wl.K, axis=0))
+    # every packed row is reached by some slot: nothing else was written
+    assert np.array_equal(np.unique(p.slot_row), np.arange(p.total_rows))
+    if level == NONE:
+        # the standard MoE permute: rows sorted by destination, stable
+        d = r.expert_to_rank[r.topk_ids].reshape(-1)
+        order = np.argsort(d, kind="stable")
+        assert np.array_equal(packed, x[order // wl.K])
+
+
+# ---- combine ------------------------------------------------------------------------------------
+def test_combine_exact_rational_small(oracle):
+    rng = np.random.default_rng(3)
+    T, K, H, E = 5, 3, 7, 6
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)
+    w = rng.random((T, K), dtype=np.float32)
+    e2r = np.array([0, 0, 1, 1, 2, 3], np.int32)
+    for level in (NONE, GPU, NODE):
+        p = oracle.plan(ids, w, e2r, 2, 2, level)
+        y = W.f32_to_bf16_bits(rng.standard_normal((p.total_rows, H)).astype(np.float32) * 3)
+        out = oracle.combine(y, w, p.slot_row)
+        yf = W.bf16_bits_to_f64(y)
+        for t in range(T):
+            for j in range(H):
+                q = sum(Fraction(float(w[t, k])) * Fraction(float(yf[p.slot_row[t, k], j])) for k in range(K))
+                assert int(out[t, j]) == exact_round_to_bf16(q), (level, t, j)
+
+
+def test_combine_level_none_is_plain_moe_weighted_sum(oracle):
+    wl = W.WORKLOADS["tiny"]
+    r = W.make_routing(wl, T=256)
+    rng = np.random.default_rng(9)
+    p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, NONE)
+    y = W.f32_to_bf16_bits(rng.standard_normal((p.total_rows, 64)).astype(np.float32))
+    out = oracle.combine(y, r.topk_weights, p.slot_row)
+    # out[t] = sum_k w[t,k] * y_slot[t,k]  (library einsum in fp64), rounded once
+    y_slot = W.bf16_bits_to_f64(y)[p.slot_row]                           # [T,K,H]
+    ref = np.einsum("tk,tkh->th", r.topk_weights.astype(np.float64), y_slot)
+    ref_bits = np.array([[exact_round_to_bf16(Fraction(float(v))) for v in row] for row in ref[:16]], np.uint16)
+    # einsum's fp64 summation order may differ in the last bit of the double: allow 1 ulp there
+    assert bf16_ulp_distance(out[:16], ref_bits).max() <= 1
+    assert np.abs(W.bf16_bits_to_f64(out) - ref).max() <= 2.0 ** -8 * np.abs(ref).max()
+
+
+@pytest.mark.parametrize("name", ["tiny", "dsv3"])
+def test_identity_expert_round_trip_is_bit_exact(oracle, name):
+    wl = W.WORKLOADS[name]
+    T, H = 512, 128
+    r = W.make_routing(wl, T=T)
+    x = W.make_activations(wl, T=T, H=H)
+    assert np.abs(r.topk_weights.astype(np.float64).sum(1) - 1).max() < 4 * 2.0 ** -24
+    for level in (NONE, GPU, NODE):
+        p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        packed = oracle.dispatch_pack(x, p.row_token)
+        out = oracle.combine(packed, r.topk_weights, p.slot_row)
+        assert np.array_equal(out, x), level
+
+
+def test_scaled_experts_closed_form_all_levels(oracle):
+    """Expert e returns c[e] * x.  A row that serves several experts of one destination carries
+    their weight-normalised mixture, so the layer output is (sum_k w_k c[e_k]) * x at every level."""
+    wl = W.WORKLOADS["qwen3"]
+    T, H = 384, 96
+    r = W.make_routing(wl, T=T)
+    x = W.make_activations(wl, T=T, H=H)
+    c = W.make_expert_scales(wl)
+    xf = W.bf16_bits_to_f64(x)
+    coef = (r.topk_weights.astype(np.float64) * c[r.topk_ids].astype(np.float64)).sum(1)
+    expect = coef[:, None] * xf
+    for level in (NONE, GPU, NODE):
+        p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        packed = oracle.dispatch_pack(x, p.row_token)
+        num = np.zeros(p.total_rows)
+        np.add.at(num, p.slot_row.reshape(-1), (r.topk_weights * c[r.topk_ids]).astype(np.float64).reshape(-1))
+        s = num / p.row_weight.astype(np.float64)
+        y = W.f32_to_bf16_bits((s[:, None] * W.bf16_bits_to_f64(packed)).astype(np.float32))
+        out = W.bf16_bits_to_f64(oracle.combine(y, r.topk_weights, p.slot_row))
+        # Y is rounded to bf16 once (rel 2^-9), the output once more (rel 2^-9)
+        assert np.all(np.abs(out - expect) <= 2.0 ** -7 * np.abs(expect) + 1e-30), level
+
+
+# ---- transpose ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("level", [NONE, GPU, NODE])
+def test_transpose_is_adjoint_and_one_multiply(oracle, level):
+    wl = W.WORKLOADS["stress"]
+    T, H = 300, 40
+    r = W.make_routing(wl, T=T)
+    rng = np.random.default_rng(17)
+    p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+    gout = W.make_output_grads(wl, T=T, H=H)
+    gy = oracle.combine_transpose(gout, p.row_token, p.row_weight)
+    # one IEEE binary32 multiply per element
+    assert np.array_equal(gy, p.row_weight[:, None] * gout[p.row_token])
+    # <combine(Y), g> == <Y, combine^T(g)> with the linear (unrounded) combine in fp64
+    y = rng.standard_normal((p.total_rows, H))
+    lin = np.zeros((T, H))
+    for k in range(wl.K):
+        lin += r.topk_weights[:, k].astype(np.float64)[:, None] * y[p.slot_row[:, k]]
+    lhs = float((lin * gout.astype(np.float64)).sum())
+    # exact adjoint uses the exact per-row weight sums; row_weight is their fp32 rounding
+    rhs = float((y * gy.astype(np.float64)).sum())
+    scale = float(np.abs(lin * gout).sum())
+    assert abs(lhs - rhs) <= 4e-7 * scale
+    # with the exact (fp64) row weights the identity holds to rounding of the dot products
+    rw64 = np.zeros(p.total_rows)
+    np.add.at(rw64, p.slot_row.reshape(-1), r.topk_weights.astype(np.float64).reshape(-1))
+    rhs64 = float((y * (rw64[:, None] * gout.astype(np.float64)[p.row_token])).sum())
+    assert abs(lhs - rhs64) <= 1e-12 * scale
