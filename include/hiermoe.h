@@ -1,0 +1,168 @@
+/*
+ * hiermoe.h -- C ABI of the MI355X (gfx950) dedup dispatch / combine library, libhiermoe.so.
+ *
+ * The library implements one expert-parallel rank's side of the hierarchical token
+ * deduplication of HierMoE (arxiv 2508.09591): from the rank's top-K routing it builds, per
+ * destination group (a GPU for HD1, a node for the inter-node hop of HD2; Section III-A), the
+ * send list in which every token appears at most once (the group-OR of Eq.(7)), packs the bf16
+ * token rows into per-destination send buffers, and merges expert outputs coming back in that
+ * layout with the router weights ("AlltoAll Combine", Section II-B).  Destinations are index
+ * partitions of one buffer; the exchange itself is not part of the library.
+ *
+ * Conventions
+ *   - Unless marked "host", every pointer is a DEVICE pointer into memory the caller owns.
+ *     The library never allocates or frees device memory.
+ *   - Every call only enqueues work on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and returns; only hm_plan_status synchronises.
+ *   - The return value reports host-checkable argument errors, detected before anything is
+ *     launched (so nothing was written), or a HIP launch failure.  Data errors found by the
+ *     kernels (an expert id outside [0,E), a rank outside [0,G), a row index outside the
+ *     caller's buffer) never fault: the offending slot / row is skipped and the code is stored
+ *     in the plan's device status word, which hm_plan_status returns.
+ *   - Row and token indices are int32; byte offsets inside the kernels are 64-bit.
+ *   - Limits: nodes*ranks_per_node <= 64, nodes <= 32 (bit masks), 1 <= K <= 64,
+ *     T*K <= 2^31-1.
+ *   - Re-entrant per (plan buffers, workspace, stream); no global state.
+ */
+#ifndef HIERMOE_H
+#define HIERMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HM_OK = 0,
+  HM_ERR_NULL = -1,      /* a required pointer is NULL                                   */
+  HM_ERR_SHAPE = -2,     /* T < 0, K/E/H out of range, T*K overflows int32                */
+  HM_ERR_TOPOLOGY = -3,  /* nodes or ranks_per_node < 1, more than 64 ranks or 32 nodes   */
+  HM_ERR_LEVEL = -4,     /* dedup level is not one of hm_dedup_level                      */
+  HM_ERR_WORKSPACE = -5, /* workspace smaller than hm_plan_workspace_bytes                */
+  HM_ERR_CAPACITY = -6,  /* a row index does not fit the caller's row buffers (device)    */
+  HM_ERR_BAD_ID = -7,    /* expert id or rank out of range (device-detected)              */
+  HM_ERR_HIP = -8        /* a HIP runtime call failed                                     */
+} hm_status;
+
+/* Where duplicates are removed (Section III-A): nowhere (plain per-rank MoE permute, the H1
+ * baseline), per destination GPU (HD1), or per destination node (first hop of HD2). */
+typedef enum { HM_DEDUP_NONE = 0, HM_DEDUP_GPU = 1, HM_DEDUP_NODE = 2 } hm_dedup_level;
+
+/* Two-level hierarchy: rank g belongs to node g / ranks_per_node (contiguous, Section III-B). */
+typedef struct {
+  int32_t nodes;
+  int32_t ranks_per_node;
+} hm_topology;
+
+/*
+ * Plan buffers, allocated by the caller, filled by hm_plan.  `num_dest` (host) is written by
+ * hm_plan: nodes at level node, nodes*ranks_per_node otherwise.  `row_capacity` (host, input)
+ * is the number of rows row_token / row_weight can hold; T*min(K,num_dest) always suffices.
+ *
+ *   dest_count [num_dest]     rows destined to each group = the duplicate-free count p of Eq.(7)
+ *   dest_offset[num_dest+1]   exclusive prefix sum; destination d owns packed rows
+ *                             [dest_offset[d], dest_offset[d+1]); the last entry is total_rows
+ *   row_token  [row_capacity] packed row -> source token.  Inside a destination rows ascend by
+ *                             flat slot index t*K+k of the kept slot (i.e. by token).
+ *   slot_row   [T*K]          slot (t,k) -> the packed row carrying token t to the slot's
+ *                             destination (same row for all slots of t with that destination);
+ *                             -1 for a dropped (invalid) slot
+ *   slot_keep  [T*K]          1 for the first slot of a token with a given destination (the one
+ *                             that owns the row), else 0; at level none every valid slot is 1
+ *   row_weight [row_capacity] fp32 sum, in ascending k, of the router weights of the slots a row
+ *                             serves
+ *   rank_mask  [T]  optional  bit g set iff some valid slot of the token maps to rank g
+ *   node_mask  [T]  optional  bit n set iff some valid slot maps to node n
+ *   status     [1]            0, or the last HM_ERR_BAD_ID / HM_ERR_CAPACITY a kernel stored
+ */
+typedef struct {
+  int32_t num_dest;
+  int64_t row_capacity;
+  int32_t *dest_count;
+  int32_t *dest_offset;
+  int32_t *row_token;
+  int32_t *slot_row;
+  uint8_t *slot_keep;
+  float *row_weight;
+  uint64_t *rank_mask;
+  uint32_t *node_mask;
+  int32_t *status;
+} hm_plan_out;
+
+/* Bytes of device scratch hm_plan needs for these sizes (0 on invalid arguments). */
+size_t hm_plan_workspace_bytes(int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level);
+
+/*
+ * hm_plan -- Eq.(7) as send lists.  For slot (t,k): rank = expert_to_rank[topk_ids[t,k]], the
+ * destination is the rank (levels none, gpu) or rank / ranks_per_node (level node).  At levels
+ * gpu and node a token keeps one row per destination (the OR over the group's experts); the
+ * lowest k owns it.  Fills every field of *out described above and clears / sets *out->status.
+ *   topk_ids [T*K] int32, topk_weights [T*K] fp32, expert_to_rank [E] int32 (any map E -> ranks;
+ *   an expert swap of Section IV is an exchange of two entries).  workspace: device scratch of
+ *   at least hm_plan_workspace_bytes, 16-byte aligned, private to this call until it completes.
+ * Invalid slots are dropped (slot_row = -1, slot_keep = 0) and flagged HM_ERR_BAD_ID; rows beyond
+ * row_capacity are not written and flagged HM_ERR_CAPACITY (counts and offsets stay exact).
+ */
+hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+                  int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
+                  hm_plan_out *out /* host struct */, void *workspace, size_t workspace_bytes,
+                  void *hip_stream);
+
+/*
+ * hm_plan_status -- waits for `hip_stream`, then returns the plan's device status word and
+ * stores total_rows (= dest_offset[num_dest]) into *total_rows (host, may be NULL).
+ */
+hm_status hm_plan_status(const hm_plan_out *plan /* host struct */, int64_t *total_rows /* host */,
+                         void *hip_stream);
+
+/*
+ * hm_dispatch_pack -- the deduplicated send buffers (Section III-A, Fig.5): for every kept slot,
+ * packed[slot_row[t,k], :] = x[t, :], a bit copy of H bf16 values.  x [T,H] bf16 row-major,
+ * packed [packed_rows,H] bf16; rows outside [0,packed_rows) are skipped and flagged
+ * HM_ERR_CAPACITY.  Uses plan->slot_row, slot_keep, status.  Fast path needs H % 8 == 0 and
+ * 16-byte aligned x / packed; any other H or alignment takes a slower element-wise kernel.
+ */
+hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
+                           void *packed_bf16, int64_t packed_rows, void *hip_stream);
+
+/*
+ * hm_combine -- weighted merge of expert outputs returned in the packed layout (Section II-A:
+ * the layer output is the gate-weighted sum of the selected experts' outputs):
+ *     out[t,:] = bf16( sum_k topk_weights[t,k] * y[slot_row[t,k], :] ),  fp32 accumulation.
+ * Slots that share a row are merged first (their weights are added in fp32, ascending k) so each
+ * distinct row is read once.  y [y_rows,H] bf16, out [T,H] bf16.  Dropped slots and rows outside
+ * [0,y_rows) contribute nothing (the latter flagged HM_ERR_CAPACITY).  Uses plan->slot_row, status.
+ */
+hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
+                     int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream);
+
+/*
+ * hm_combine_transpose -- adjoint of hm_combine with respect to y (the gradient that travels
+ * back through the dispatch layout): for every kept slot,
+ *     gy[row,:] = row_weight[row] * gout[t,:],   row = slot_row[t,k]   (one fp32 multiply).
+ * gout [T,H] fp32, gy [gy_rows,H] fp32.  Uses plan->slot_row, slot_keep, row_weight, status.
+ */
+hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
+                               float *gy, int64_t gy_rows, void *hip_stream);
+
+/*
+ * hm_expert_load -- the counts the expert-swap planner of Section IV consumes:
+ *   load_expert[E]   slots per expert (duplicate-unaware, what SmartMoE-style planners count)
+ *   load_rank [G]    tokens per rank after deduplication  = p^(1,G)    of Eq.(7)
+ *   load_node [nodes] tokens per node after deduplication = p^(1,U[1]) of Eq.(7)
+ * Invalid slots are not counted; if `status` (device int32[1], may be NULL) is given it is
+ * cleared and set to HM_ERR_BAD_ID when one is met.
+ */
+hm_status hm_expert_load(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                         hm_topology topo, int32_t *load_expert, int32_t *load_rank, int32_t *load_node,
+                         int32_t *status, void *hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char *hm_status_string(hm_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HIERMOE_H */

@@ -112,6 +112,8 @@ def dispatch_pack(x_rows: np.ndarray, row_token: np.ndarray) -> np.ndarray:
     T = x.shape[0]
     row_bytes = x.strides[0] if x.ndim > 1 else x.itemsize
     out = np.empty((rt.shape[0],) + x.shape[1:], dtype=x.dtype)
+    if out.size == 0:
+        return out
     rc = lib.hmo_dispatch_pack(_p(x), ctypes.c_int64(T), ctypes.c_int64(row_bytes), _p(rt),
                                ctypes.c_int64(rt.shape[0]), _p(out))
     if rc != 0:
@@ -128,6 +130,10 @@ def combine(y_bf16: np.ndarray, topk_weights, slot_row) -> np.ndarray:
     T, K = sr.shape
     H = y.shape[1]
     out = np.empty((T, H), np.uint16)
+    if out.size == 0:
+        return out
+    if y.shape[0] == 0:
+        y = np.zeros((1, H), np.uint16)      # never read: every slot_row is negative
     rc = lib.hmo_combine(_p(y), ctypes.c_int64(y.shape[0]), _p(w), _p(sr), ctypes.c_int64(T), ctypes.c_int32(K),
                          ctypes.c_int64(H), _p(out))
     if rc != 0:
@@ -143,6 +149,8 @@ def combine_transpose(gout: np.ndarray, row_token, row_weight) -> np.ndarray:
     rw = _c(row_weight, np.float32)
     T, H = g.shape
     gy = np.empty((rt.shape[0], H), np.float32)
+    if gy.size == 0:
+        return gy
     rc = lib.hmo_combine_transpose(_p(g), ctypes.c_int64(T), ctypes.c_int64(H), _p(rt), _p(rw),
                                    ctypes.c_int64(rt.shape[0]), _p(gy))
     if rc != 0:

@@ -1,0 +1,215 @@
+"""Thin ctypes binding over libhiermoe.so: argument marshalling only.
+
+Function names and arguments mirror ``include/hiermoe.h``.  Tensors are torch tensors on the
+GPU (torch supplies device memory and the current stream, nothing else); every step of the path
+runs in the library's HIP kernels.  There is no CPU fallback: if the library is missing or a
+tensor is not on the GPU the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch  # must be imported before the library so both share one HIP runtime
+
+HM_DEDUP_NONE, HM_DEDUP_GPU, HM_DEDUP_NODE = 0, 1, 2
+HM_OK = 0
+HM_ERR_NULL, HM_ERR_SHAPE, HM_ERR_TOPOLOGY, HM_ERR_LEVEL = -1, -2, -3, -4
+HM_ERR_WORKSPACE, HM_ERR_CAPACITY, HM_ERR_BAD_ID, HM_ERR_HIP = -5, -6, -7, -8
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhiermoe.so")
+
+EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_pack", "hm_combine",
+           "hm_combine_transpose", "hm_expert_load", "hm_status_string")
+
+
+class hm_topology(ctypes.Structure):
+    _fields_ = [("nodes", ctypes.c_int32), ("ranks_per_node", ctypes.c_int32)]
+
+
+class hm_plan_out(ctypes.Structure):
+    _fields_ = [("num_dest", ctypes.c_int32), ("row_capacity", ctypes.c_int64),
+                ("dest_count", ctypes.c_void_p), ("dest_offset", ctypes.c_void_p),
+                ("row_token", ctypes.c_void_p), ("slot_row", ctypes.c_void_p),
+                ("slot_keep", ctypes.c_void_p), ("row_weight", ctypes.c_void_p),
+                ("rank_mask", ctypes.c_void_p), ("node_mask", ctypes.c_void_p),
+                ("status", ctypes.c_void_p)]
+
+
+class HierMoEError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (fn, status_string(code), code))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError("libhiermoe.so is not built (run __graft_entry__.build()); "
+                               "there is no fallback path")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        L.hm_plan_workspace_bytes.restype = ctypes.c_size_t
+        L.hm_plan_workspace_bytes.argtypes = [i32, i32, i32, hm_topology, ctypes.c_int]
+        L.hm_plan.restype = ctypes.c_int
+        L.hm_plan.argtypes = [vp, vp, vp, i32, i32, i32, hm_topology, ctypes.c_int,
+                              ctypes.POINTER(hm_plan_out), vp, ctypes.c_size_t, vp]
+        L.hm_plan_status.restype = ctypes.c_int
+        L.hm_plan_status.argtypes = [ctypes.POINTER(hm_plan_out), ctypes.POINTER(i64), vp]
+        L.hm_dispatch_pack.restype = ctypes.c_int
+        L.hm_dispatch_pack.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
+        L.hm_combine.restype = ctypes.c_int
+        L.hm_combine.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
+        L.hm_combine_transpose.restype = ctypes.c_int
+        L.hm_combine_transpose.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
+        L.hm_expert_load.restype = ctypes.c_int
+        L.hm_expert_load.argtypes = [vp, vp, i32, i32, i32, hm_topology, vp, vp, vp, vp, vp]
+        L.hm_status_string.restype = ctypes.c_char_p
+        L.hm_status_string.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().hm_status_string(int(code)).decode()
+
+
+def _dev(t: Optional[torch.Tensor], dtype: torch.dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("%s must be a GPU tensor (no CPU path exists)" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise TypeError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream or None
+
+
+def _check(fn: str, rc: int):
+    if rc != HM_OK:
+        raise HierMoEError(fn, rc)
+
+
+@dataclass
+class Plan:
+    """Device buffers of one plan plus the host struct the C calls take."""
+    T: int
+    K: int
+    level: int
+    num_dest: int
+    row_capacity: int
+    dest_count: torch.Tensor
+    dest_offset: torch.Tensor
+    row_token: torch.Tensor
+    slot_row: torch.Tensor
+    slot_keep: torch.Tensor
+    row_weight: torch.Tensor
+    rank_mask: Optional[torch.Tensor]
+    node_mask: Optional[torch.Tensor]
+    status: torch.Tensor
+    workspace: torch.Tensor
+    c: hm_plan_out
+
+    def ref(self):
+        return ctypes.byref(self.c)
+
+
+def hm_plan_workspace_bytes(T: int, K: int, E: int, nodes: int, ranks_per_node: int, level: int) -> int:
+    return int(lib().hm_plan_workspace_bytes(T, K, E, hm_topology(nodes, ranks_per_node), level))
+
+
+def alloc_plan(T: int, K: int, E: int, nodes: int, ranks_per_node: int, level: int, device="cuda",
+               row_capacity: Optional[int] = None, masks: bool = True) -> Plan:
+    """Allocate (uninitialised) plan buffers; row_capacity defaults to the worst case."""
+    G = nodes * ranks_per_node
+    Dn = nodes if level == HM_DEDUP_NODE else G
+    if row_capacity is None:
+        row_capacity = T * (K if level == HM_DEDUP_NONE else min(K, Dn))
+    e = lambda n, dt: torch.empty(max(int(n), 1), dtype=dt, device=device)
+    ws_bytes = hm_plan_workspace_bytes(T, K, E, nodes, ranks_per_node, level)
+    bufs = dict(dest_count=e(Dn, torch.int32), dest_offset=e(Dn + 1, torch.int32),
+                row_token=e(row_capacity, torch.int32), slot_row=e(T * K, torch.int32),
+                slot_keep=e(T * K, torch.uint8), row_weight=e(row_capacity, torch.float32),
+                rank_mask=e(T, torch.int64) if masks else None,
+                node_mask=e(T, torch.int32) if masks else None,
+                status=e(1, torch.int32), workspace=e(max(ws_bytes, 16) // 4 + 4, torch.int32))
+    c = hm_plan_out()
+    c.num_dest = Dn
+    c.row_capacity = int(row_capacity)
+    for name in ("dest_count", "dest_offset", "row_token", "slot_row", "slot_keep", "row_weight",
+                 "rank_mask", "node_mask", "status"):
+        t = bufs[name]
+        setattr(c, name, t.data_ptr() if t is not None else None)
+    return Plan(T=T, K=K, level=level, num_dest=Dn, row_capacity=int(row_capacity), c=c, **bufs)
+
+
+def hm_plan(topk_ids: torch.Tensor, topk_weights: torch.Tensor, expert_to_rank: torch.Tensor,
+            nodes: int, ranks_per_node: int, level: int, plan: Optional[Plan] = None, stream=None) -> Plan:
+    T, K = topk_ids.shape
+    E = expert_to_rank.shape[0]
+    if plan is None:
+        plan = alloc_plan(T, K, E, nodes, ranks_per_node, level, device=topk_ids.device)
+    rc = lib().hm_plan(_dev(topk_ids, torch.int32, "topk_ids"), _dev(topk_weights, torch.float32, "topk_weights"),
+                       _dev(expert_to_rank, torch.int32, "expert_to_rank"), T, K, E,
+                       hm_topology(nodes, ranks_per_node), level, plan.ref(),
+                       plan.workspace.data_ptr(), plan.workspace.numel() * 4, _stream(stream))
+    _check("hm_plan", rc)
+    plan.num_dest = int(plan.c.num_dest)
+    return plan
+
+
+def hm_plan_status(plan: Plan, stream=None):
+    """(status code, total_rows); synchronises the stream."""
+    total = ctypes.c_int64(0)
+    rc = lib().hm_plan_status(plan.ref(), ctypes.byref(total), _stream(stream))
+    return int(rc), int(total.value)
+
+
+def hm_dispatch_pack(x: torch.Tensor, plan: Plan, packed: torch.Tensor, stream=None) -> torch.Tensor:
+    T, H = x.shape
+    rc = lib().hm_dispatch_pack(_dev(x, torch.bfloat16, "x"), T, plan.K, H, plan.ref(),
+                                _dev(packed, torch.bfloat16, "packed"), packed.shape[0], _stream(stream))
+    _check("hm_dispatch_pack", rc)
+    return packed
+
+
+def hm_combine(y: torch.Tensor, topk_weights: torch.Tensor, plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
+    T, H = out.shape
+    rc = lib().hm_combine(_dev(y, torch.bfloat16, "y"), y.shape[0], _dev(topk_weights, torch.float32, "topk_weights"),
+                          T, plan.K, H, plan.ref(), _dev(out, torch.bfloat16, "out"), _stream(stream))
+    _check("hm_combine", rc)
+    return out
+
+
+def hm_combine_transpose(gout: torch.Tensor, plan: Plan, gy: torch.Tensor, stream=None) -> torch.Tensor:
+    T, H = gout.shape
+    rc = lib().hm_combine_transpose(_dev(gout, torch.float32, "gout"), T, plan.K, H, plan.ref(),
+                                    _dev(gy, torch.float32, "gy"), gy.shape[0], _stream(stream))
+    _check("hm_combine_transpose", rc)
+    return gy
+
+
+def hm_expert_load(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, nodes: int, ranks_per_node: int,
+                   load_expert: torch.Tensor, load_rank: torch.Tensor, load_node: torch.Tensor,
+                   status: Optional[torch.Tensor] = None, stream=None):
+    T, K = topk_ids.shape
+    E = expert_to_rank.shape[0]
+    rc = lib().hm_expert_load(_dev(topk_ids, torch.int32, "topk_ids"), _dev(expert_to_rank, torch.int32, "expert_to_rank"),
+                              T, K, E, hm_topology(nodes, ranks_per_node), _dev(load_expert, torch.int32, "load_expert"),
+                              _dev(load_rank, torch.int32, "load_rank"), _dev(load_node, torch.int32, "load_node"),
+                              _dev(status, torch.int32, "status"), _stream(stream))
+    _check("hm_expert_load", rc)
+    return load_expert, load_rank, load_node

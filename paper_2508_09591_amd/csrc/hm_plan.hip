@@ -1,0 +1,292 @@
+// hm_plan: routing -> deduplicated, stable per-destination send lists (HierMoE Eq.(7)).
+//
+// One lane owns one routing slot s = t*K + k; a wave owns 64 consecutive slots, a workgroup 1024.
+// Rows of a destination are numbered in ascending slot order, so a lane's row is
+//     dest_offset[d] + (kept slots of d in earlier workgroups) + (in earlier waves of this
+//     workgroup) + (in lower lanes of this wave),
+// and the last term is a popcount over a wavefront ballot.  No atomics decide positions, so the
+// plan is deterministic and stable.  Two launches:
+//   plan_count_kernel  per-workgroup, per-destination counts of kept slots -> workspace
+//   plan_write_kernel  every workgroup re-reads the (small) count matrix to get its own base
+//                      rows and the destination totals, then writes the index maps.
+#include "hm_device.h"
+
+namespace hm {
+
+constexpr int kPlanThreads = 1024;
+constexpr int kPlanWaves = kPlanThreads / kWave;
+
+struct PlanParams {
+  const int32_t *ids;
+  const float *weights;
+  const int32_t *expert_to_rank;
+  int32_t T, K, E, G, R, Dn, level;
+  int32_t nslots, nblocks;
+  int64_t row_capacity;
+  int32_t *counts;  // workspace [nblocks][Dn]
+  int32_t *dest_count, *dest_offset, *row_token, *slot_row;
+  uint8_t *slot_keep;
+  float *row_weight;
+  uint64_t *rank_mask;
+  uint32_t *node_mask;
+  int32_t *status;
+};
+
+__device__ __forceinline__ int dest_of_rank(const PlanParams &p, int rank) {
+  return p.level == HM_DEDUP_NODE ? rank / p.R : rank;
+}
+
+// Destination of slot (t,k) (-1: invalid slot) and whether the slot owns the row of its
+// (token, destination) pair: always at level none, else iff no earlier slot of the token has the
+// same destination -- the OR over a group's experts in Eq.(7) leaves one copy per group.
+__device__ __forceinline__ int slot_destination(const PlanParams &p, int t, int k, int &rank, bool &keep) {
+  const int32_t *tok = p.ids + (int64_t)t * p.K;
+  rank = rank_of(p.expert_to_rank, p.E, p.G, tok[k]);
+  keep = false;
+  if (rank < 0) return -1;
+  const int dest = dest_of_rank(p, rank);
+  keep = true;
+  if (p.level != HM_DEDUP_NONE) {
+    for (int k1 = 0; k1 < k; ++k1) {
+      const int r1 = rank_of(p.expert_to_rank, p.E, p.G, tok[k1]);
+      if (r1 >= 0 && dest_of_rank(p, r1) == dest) {
+        keep = false;
+        break;
+      }
+    }
+  }
+  return dest;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanParams p) {
+  __shared__ int32_t wave_cnt[kPlanWaves][kWave];
+  const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
+  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
+  int dest = -1;
+  if (s < p.nslots) {
+    const int t = (int)(s / p.K), k = (int)(s - (int64_t)t * p.K);
+    int rank;
+    bool keep;
+    const int d = slot_destination(p, t, k, rank, keep);
+    if (keep) dest = d;
+  }
+  int mine = 0;  // lane d ends up with the wave's count for destination d
+  for (int d = 0; d < p.Dn; ++d) {
+    const uint64_t b = __ballot(dest == d);
+    if (lane == d) mine = __popcll(b);
+  }
+  wave_cnt[wv][lane] = mine;
+  __syncthreads();
+  if ((int)threadIdx.x < p.Dn) {
+    int sum = 0;
+    for (int w = 0; w < kPlanWaves; ++w) sum += wave_cnt[w][threadIdx.x];
+    p.counts[(int64_t)blockIdx.x * p.Dn + threadIdx.x] = sum;
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) *p.status = 0;
+}
+
+__global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) {
+  __shared__ int32_t part_tot[kPlanWaves][kWave];
+  __shared__ int32_t part_pre[kPlanWaves][kWave];
+  __shared__ int32_t block_base[kWave];             // first row of this workgroup per destination
+  __shared__ uint64_t ballots[kPlanWaves][kWave];   // [wave][destination] -> lanes that keep a slot
+  __shared__ int32_t wave_base[kPlanWaves][kWave];  // kept slots in earlier waves of the workgroup
+  const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
+
+  // Column sums of the count matrix: over all workgroups (destination total) and over the
+  // earlier ones (this workgroup's base).  Wave wv takes rows wv, wv+16, ...
+  {
+    int tot = 0, pre = 0;
+    if (lane < p.Dn) {
+      for (int b = wv; b < p.nblocks; b += kPlanWaves) {
+        const int c = p.counts[(int64_t)b * p.Dn + lane];
+        tot += c;
+        if (b < (int)blockIdx.x) pre += c;
+      }
+    }
+    part_tot[wv][lane] = tot;
+    part_pre[wv][lane] = pre;
+  }
+
+  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
+  const bool live = s < p.nslots;
+  int t = 0, k = 0, rank = -1, dest = -1;
+  bool keep = false;
+  if (live) {
+    t = (int)(s / p.K);
+    k = (int)(s - (int64_t)t * p.K);
+    dest = slot_destination(p, t, k, rank, keep);
+  }
+  const int kept_dest = keep ? dest : -1;
+  for (int d = 0; d < p.Dn; ++d) {
+    const uint64_t b = __ballot(kept_dest == d);
+    if (lane == d) ballots[wv][d] = b;
+  }
+  __syncthreads();
+
+  if (lane < p.Dn) {
+    int a = 0;
+    for (int w = 0; w < wv; ++w) a += __popcll(ballots[w][lane]);
+    wave_base[wv][lane] = a;
+  }
+  if (wv == 0) {
+    int tot = 0, pre = 0;
+    if (lane < p.Dn)
+      for (int w = 0; w < kPlanWaves; ++w) {
+        tot += part_tot[w][lane];
+        pre += part_pre[w][lane];
+      }
+    int incl = tot;  // inclusive scan over destinations (lanes >= Dn hold 0)
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int v = __shfl_up(incl, off, kWave);
+      if (lane >= off) incl += v;
+    }
+    const int offset = incl - tot;
+    block_base[lane] = offset + pre;
+    if (blockIdx.x == 0 && lane < p.Dn) {
+      p.dest_count[lane] = tot;
+      p.dest_offset[lane] = offset;
+      if (lane == p.Dn - 1) p.dest_offset[p.Dn] = incl;
+    }
+  }
+  __syncthreads();
+
+  if (!live) return;
+  if (rank < 0) {
+    p.slot_row[s] = -1;
+    p.slot_keep[s] = 0;
+    flag(p.status, HM_ERR_BAD_ID);
+  } else if (!keep) {
+    p.slot_keep[s] = 0;  // its slot_row is written by the slot that owns the row
+  } else {
+    const uint64_t b = ballots[wv][dest];
+    const int pos = __popcll(b & ((1ull << lane) - 1ull));
+    const int row = block_base[dest] + wave_base[wv][dest] + pos;
+    p.slot_keep[s] = 1;
+    p.slot_row[s] = row;
+    float wsum = p.weights[s];
+    if (p.level != HM_DEDUP_NONE) {
+      const int32_t *tok = p.ids + (int64_t)t * p.K;
+      for (int k2 = k + 1; k2 < p.K; ++k2) {
+        const int r2 = rank_of(p.expert_to_rank, p.E, p.G, tok[k2]);
+        if (r2 >= 0 && dest_of_rank(p, r2) == dest) {
+          p.slot_row[(int64_t)t * p.K + k2] = row;
+          wsum = wsum + p.weights[(int64_t)t * p.K + k2];  // ascending k, fp32
+        }
+      }
+    }
+    if (row < p.row_capacity) {
+      p.row_token[row] = t;
+      p.row_weight[row] = wsum;
+    } else {
+      flag(p.status, HM_ERR_CAPACITY);
+    }
+  }
+  if (k == 0 && (p.rank_mask || p.node_mask)) {
+    const int32_t *tok = p.ids + (int64_t)t * p.K;
+    uint64_t rm = 0;
+    uint32_t nm = 0;
+    for (int k2 = 0; k2 < p.K; ++k2) {
+      const int r2 = rank_of(p.expert_to_rank, p.E, p.G, tok[k2]);
+      if (r2 >= 0) {
+        rm |= 1ull << r2;
+        nm |= 1u << (r2 / p.R);
+      }
+    }
+    if (p.rank_mask) p.rank_mask[t] = rm;
+    if (p.node_mask) p.node_mask[t] = nm;
+  }
+}
+
+static inline int32_t plan_blocks(int64_t nslots) {
+  const int64_t b = (nslots + kPlanThreads - 1) / kPlanThreads;
+  return (int32_t)(b < 1 ? 1 : b);
+}
+
+}  // namespace hm
+
+extern "C" size_t hm_plan_workspace_bytes(int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level) {
+  if (E < 1 || hm_check_tk(T, K) != HM_OK || hm_check_topology(topo) != HM_OK) return 0;
+  if (level != HM_DEDUP_NONE && level != HM_DEDUP_GPU && level != HM_DEDUP_NODE) return 0;
+  const int Dn = level == HM_DEDUP_NODE ? topo.nodes : topo.nodes * topo.ranks_per_node;
+  return (size_t)hm::plan_blocks((int64_t)T * K) * (size_t)Dn * sizeof(int32_t);
+}
+
+extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+                             int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
+                             hm_plan_out *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  if (!out || !expert_to_rank || !workspace) return HM_ERR_NULL;
+  if (!out->dest_count || !out->dest_offset || !out->row_token || !out->slot_row || !out->slot_keep ||
+      !out->row_weight || !out->status)
+    return HM_ERR_NULL;
+  hm_status st = hm_check_tk(T, K);
+  if (st != HM_OK) return st;
+  if (E < 1 || out->row_capacity < 0) return HM_ERR_SHAPE;
+  if (T > 0 && (!topk_ids || !topk_weights)) return HM_ERR_NULL;
+  st = hm_check_topology(topo);
+  if (st != HM_OK) return st;
+  if (level != HM_DEDUP_NONE && level != HM_DEDUP_GPU && level != HM_DEDUP_NODE) return HM_ERR_LEVEL;
+  if (workspace_bytes < hm_plan_workspace_bytes(T, K, E, topo, level)) return HM_ERR_WORKSPACE;
+
+  hm::PlanParams p;
+  p.ids = topk_ids;
+  p.weights = topk_weights;
+  p.expert_to_rank = expert_to_rank;
+  p.T = T;
+  p.K = K;
+  p.E = E;
+  p.R = topo.ranks_per_node;
+  p.G = topo.nodes * topo.ranks_per_node;
+  p.Dn = level == HM_DEDUP_NODE ? topo.nodes : p.G;
+  p.level = (int32_t)level;
+  p.nslots = (int32_t)((int64_t)T * K);
+  p.nblocks = hm::plan_blocks(p.nslots);
+  p.row_capacity = out->row_capacity;
+  p.counts = (int32_t *)workspace;
+  p.dest_count = out->dest_count;
+  p.dest_offset = out->dest_offset;
+  p.row_token = out->row_token;
+  p.slot_row = out->slot_row;
+  p.slot_keep = out->slot_keep;
+  p.row_weight = out->row_weight;
+  p.rank_mask = out->rank_mask;
+  p.node_mask = out->node_mask;
+  p.status = out->status;
+  out->num_dest = p.Dn;
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(hm::plan_count_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
+  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  hipLaunchKernelGGL(hm::plan_write_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
+  return hm_launch_status();
+}
+
+extern "C" hm_status hm_plan_status(const hm_plan_out *plan, int64_t *total_rows, void *hip_stream) {
+  if (!plan || !plan->status || !plan->dest_offset) return HM_ERR_NULL;
+  if (plan->num_dest < 1 || plan->num_dest > 64) return HM_ERR_SHAPE;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  int32_t host[2] = {0, 0};
+  if (hipMemcpyAsync(&host[0], plan->status, sizeof(int32_t), hipMemcpyDeviceToHost, stream) != hipSuccess)
+    return HM_ERR_HIP;
+  if (hipMemcpyAsync(&host[1], plan->dest_offset + plan->num_dest, sizeof(int32_t), hipMemcpyDeviceToHost,
+                     stream) != hipSuccess)
+    return HM_ERR_HIP;
+  if (hipStreamSynchronize(stream) != hipSuccess) return HM_ERR_HIP;
+  if (total_rows) *total_rows = host[1];
+  return (hm_status)host[0];
+}
+
+extern "C" const char *hm_status_string(hm_status s) {
+  switch (s) {
+    case HM_OK: return "ok";
+    case HM_ERR_NULL: return "null pointer";
+    case HM_ERR_SHAPE: return "bad shape";
+    case HM_ERR_TOPOLOGY: return "bad topology (need 1..32 nodes, at most 64 ranks)";
+    case HM_ERR_LEVEL: return "bad dedup level";
+    case HM_ERR_WORKSPACE: return "workspace too small";
+    case HM_ERR_CAPACITY: return "row index beyond the caller's row buffers";
+    case HM_ERR_BAD_ID: return "expert id or rank out of range";
+    case HM_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}

