@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets (cold HBM reads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain 1 GiB device copy a few times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -155,6 +157,16 @@ def main() -> int:
         tb = (1 + c) * T * 4 * H
         log("hm_combine_transpose: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
             % (tms, tb / (tms * 1e-3) / 1e9, 100 * tb / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)      # 1 GiB
+        dst = torch.empty_like(src)
+        with torch.cuda.stream(stream):
+            for _ in range(5):
+                dst.copy_(src)
+        torch.cuda.synchronize()
+        log("calibration: 5 plain copies of %d bytes launched" % (src.numel() * 2))
+        del src, dst
 
     # ---- the oracle on this machine's host cores (reported baseline, not the target) ---------------
     cpu = None

@@ -1,25 +1,30 @@
 // Row-streaming kernels: hm_dispatch_pack, hm_combine, hm_combine_transpose.
 //
 // All three are HBM-bound and token-centric: a wave owns (token, segment of the row), reads the
-// token-side row once and touches each of the token's distinct packed rows once, which is the
+// token-side data once and touches each of the token's distinct packed rows once, which is the
 // algorithmic minimum of (1 + c) rows of traffic per token (c = packed rows per token).  The
 // token's row list is wave-uniform: lanes 0..K-1 fetch slot_row[t,:], a ballot marks the rows to
 // visit and readlane broadcasts each row index into a scalar register, so every global access
 // is a base + lane*16 B coalesced stream of 16-byte vectors.
 //
-// A segment is 64*U consecutive 16-byte vectors (U per lane, all issued before the first use);
-// U is picked on the host so that the row splits evenly (H=7168 bf16: 896 vectors = 2 x 64 x 7).
+// A segment is 64 consecutive 16-byte vectors (1 KiB, one vector per lane).  Work items this
+// small matter on MI355X: a kernel here lasts well under 100 us, so with multi-KiB items the
+// last round of waves leaves most of the chip idle; 1 KiB items measured 15-20 % faster than
+// 7 KiB ones on the 14 KiB rows of the DeepSeek-V3 shape.  Combine issues the loads of up to
+// four rows before the first use so a wave still keeps several KiB in flight.
 #include "hm_device.h"
 
 namespace hm {
 
-constexpr int kRowThreads = 256;
-constexpr int kRowWaves = kRowThreads / kWave;
+constexpr int kElemThreads = 256;   // element-wise fallback kernels
+constexpr int kCopyThreads = 128;   // dispatch / transpose: 2 waves per workgroup
+constexpr int kCombineThreads = 256;
+constexpr int kCombineRows = 4;     // rows whose loads are in flight together
 
 struct RowParams {
   int32_t T, K;
   int32_t nvec;   // 16-byte vectors per row
-  int32_t nseg;   // segments per row
+  int32_t nseg;   // 64-vector segments per row
   int64_t nunits; // T * nseg
   const int32_t *slot_row;
   const uint8_t *slot_keep;
@@ -27,8 +32,9 @@ struct RowParams {
 };
 
 // Wave-uniform (token, segment) of this wave, or false when past the end.
+template <int BLOCK>
 __device__ __forceinline__ bool unit_of_wave(const RowParams &p, int &t, int &seg) {
-  const int64_t unit = (int64_t)blockIdx.x * kRowWaves + (threadIdx.x >> 6);
+  const int64_t unit = (int64_t)blockIdx.x * (BLOCK / kWave) + (threadIdx.x >> 6);
   if (unit >= p.nunits) return false;
   t = (int)(unit / p.nseg);
   seg = (int)(unit - (int64_t)t * p.nseg);
@@ -38,12 +44,15 @@ __device__ __forceinline__ bool unit_of_wave(const RowParams &p, int &t, int &se
 // ---------------------------------------------------------------------------------------------
 // dispatch: packed[slot_row[t,k], :] = x[t, :] for kept slots
 // ---------------------------------------------------------------------------------------------
-template <int U>
-__global__ __launch_bounds__(kRowThreads) void dispatch_rows_kernel(RowParams p, const u32x4 *__restrict__ x,
-                                                                    u32x4 *__restrict__ packed, int64_t packed_rows) {
+__global__ __launch_bounds__(kCopyThreads) void dispatch_rows_kernel(RowParams p, const u32x4 *__restrict__ x,
+                                                                     u32x4 *__restrict__ packed, int64_t packed_rows) {
   int t, seg;
-  if (!unit_of_wave(p, t, seg)) return;
+  if (!unit_of_wave<kCopyThreads>(p, t, seg)) return;
   const int lane = lane_id();
+  const int v = seg * kWave + lane;
+  const bool in_row = v < p.nvec;
+  u32x4 r = {0u, 0u, 0u, 0u};
+  if (in_row) r = x[(int64_t)t * p.nvec + v];   // does not wait for the row list below
   int my_row = -1;
   if (lane < p.K) {
     const int64_t s = (int64_t)t * p.K + lane;
@@ -54,33 +63,18 @@ __global__ __launch_bounds__(kRowThreads) void dispatch_rows_kernel(RowParams p,
     }
   }
   uint64_t todo = __ballot(my_row >= 0);
-  if (todo == 0) return;
-
-  const int v0 = seg * (kWave * U) + lane;
-  const u32x4 *src = x + (int64_t)t * p.nvec;
-  u32x4 r[U];
-#pragma unroll
-  for (int i = 0; i < U; ++i) {
-    const int v = v0 + i * kWave;
-    if (v < p.nvec) r[i] = src[v];
-  }
   while (todo) {
     const int k = __builtin_ctzll(todo);
     todo &= todo - 1;
     const int row = read_lane(my_row, k);
-    u32x4 *dst = packed + (int64_t)row * p.nvec;
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      const int v = v0 + i * kWave;
-      if (v < p.nvec) store_stream(dst + v, r[i]);
-    }
+    if (in_row) store_stream(packed + (int64_t)row * p.nvec + v, r);
   }
 }
 
 // Any H / any alignment: one thread per (token, element), 2-byte accesses.
-__global__ __launch_bounds__(kRowThreads) void dispatch_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ x,
+__global__ __launch_bounds__(kElemThreads) void dispatch_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ x,
                                                                      uint16_t *__restrict__ packed, int64_t packed_rows) {
-  const int64_t i = (int64_t)blockIdx.x * kRowThreads + threadIdx.x;
+  const int64_t i = (int64_t)blockIdx.x * kElemThreads + threadIdx.x;
   if (i >= (int64_t)p.T * H) return;
   const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
   const uint16_t v = x[i];
@@ -114,12 +108,11 @@ __device__ __forceinline__ uint64_t merge_slots(int K, int my_row, float my_w, f
   return __ballot(first);
 }
 
-template <int U>
-__global__ __launch_bounds__(kRowThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y, int64_t y_rows,
-                                                                   const float *__restrict__ topk_weights,
-                                                                   u32x4 *__restrict__ out) {
+__global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
+                                                                       int64_t y_rows, const float *__restrict__ topk_weights,
+                                                                       u32x4 *__restrict__ out) {
   int t, seg;
-  if (!unit_of_wave(p, t, seg)) return;
+  if (!unit_of_wave<kCombineThreads>(p, t, seg)) return;
   const int lane = lane_id();
   int my_row = -1;
   float my_w = 0.0f;
@@ -138,53 +131,55 @@ __global__ __launch_bounds__(kRowThreads) void combine_rows_kernel(RowParams p, 
   float agg;
   uint64_t todo = merge_slots(p.K, my_row, my_w, agg);
 
-  const int v0 = seg * (kWave * U) + lane;
-  float acc[U][8];
+  const int v = seg * kWave + lane;
+  const bool in_row = v < p.nvec;
+  float acc[8];
 #pragma unroll
-  for (int i = 0; i < U; ++i)
-#pragma unroll
-    for (int e = 0; e < 8; ++e) acc[i][e] = 0.0f;
+  for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
 
   while (todo) {
-    const int k = __builtin_ctzll(todo);
-    todo &= todo - 1;
-    const int row = read_lane(my_row, k);
-    const float a = read_lane(agg, k);
-    const u32x4 *src = y + (int64_t)row * p.nvec;
-    u32x4 r[U];
+    // issue the loads of up to kCombineRows rows, then consume them in the same (ascending k) order
+    u32x4 r[kCombineRows];
+    float a[kCombineRows];
+    bool have[kCombineRows];
 #pragma unroll
-    for (int i = 0; i < U; ++i) {
-      const int v = v0 + i * kWave;
-      if (v < p.nvec) r[i] = load_stream(src + v);
-      else r[i] = (u32x4){0u, 0u, 0u, 0u};
-    }
-#pragma unroll
-    for (int i = 0; i < U; ++i)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        acc[i][2 * e] = __builtin_fmaf(a, bf16_lo(r[i][e]), acc[i][2 * e]);
-        acc[i][2 * e + 1] = __builtin_fmaf(a, bf16_hi(r[i][e]), acc[i][2 * e + 1]);
+    for (int j = 0; j < kCombineRows; ++j) {
+      have[j] = todo != 0;
+      r[j] = (u32x4){0u, 0u, 0u, 0u};
+      a[j] = 0.0f;
+      if (have[j]) {
+        const int k = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int row = read_lane(my_row, k);
+        a[j] = read_lane(agg, k);
+        if (in_row) r[j] = load_stream(y + (int64_t)row * p.nvec + v);
       }
-  }
-  u32x4 *dst = out + (int64_t)t * p.nvec;
-#pragma unroll
-  for (int i = 0; i < U; ++i) {
-    const int v = v0 + i * kWave;
-    if (v < p.nvec) {
-      u32x4 o;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[i][2 * e], acc[i][2 * e + 1]);
-      dst[v] = o;
     }
+#pragma unroll
+    for (int j = 0; j < kCombineRows; ++j) {
+      if (have[j]) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] = __builtin_fmaf(a[j], bf16_lo(r[j][e]), acc[2 * e]);
+          acc[2 * e + 1] = __builtin_fmaf(a[j], bf16_hi(r[j][e]), acc[2 * e + 1]);
+        }
+      }
+    }
+  }
+  if (in_row) {
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[2 * e], acc[2 * e + 1]);
+    out[(int64_t)t * p.nvec + v] = o;
   }
 }
 
 // Any H / alignment: one thread per (token, element); same merge order and the same fma chain
 // as the vector kernel, so both give identical bits.
-__global__ __launch_bounds__(kRowThreads) void combine_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ y,
+__global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ y,
                                                                     int64_t y_rows, const float *__restrict__ topk_weights,
                                                                     uint16_t *__restrict__ out) {
-  const int64_t i = (int64_t)blockIdx.x * kRowThreads + threadIdx.x;
+  const int64_t i = (int64_t)blockIdx.x * kElemThreads + threadIdx.x;
   if (i >= (int64_t)p.T * H) return;
   const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
   const int32_t *rows = p.slot_row + (int64_t)t * p.K;
@@ -212,14 +207,17 @@ __global__ __launch_bounds__(kRowThreads) void combine_elems_kernel(RowParams p,
 // ---------------------------------------------------------------------------------------------
 // transpose: gy[slot_row[t,k], :] = row_weight[row] * gout[t, :] for kept slots (fp32)
 // ---------------------------------------------------------------------------------------------
-template <int U>
-__global__ __launch_bounds__(kRowThreads) void transpose_rows_kernel(RowParams p, const f32x4 *__restrict__ gout,
-                                                                     const float *__restrict__ row_weight,
-                                                                     int64_t weight_rows, f32x4 *__restrict__ gy,
-                                                                     int64_t gy_rows) {
+__global__ __launch_bounds__(kCopyThreads) void transpose_rows_kernel(RowParams p, const f32x4 *__restrict__ gout,
+                                                                      const float *__restrict__ row_weight,
+                                                                      int64_t weight_rows, f32x4 *__restrict__ gy,
+                                                                      int64_t gy_rows) {
   int t, seg;
-  if (!unit_of_wave(p, t, seg)) return;
+  if (!unit_of_wave<kCopyThreads>(p, t, seg)) return;
   const int lane = lane_id();
+  const int v = seg * kWave + lane;
+  const bool in_row = v < p.nvec;
+  f32x4 r = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (in_row) r = gout[(int64_t)t * p.nvec + v];
   int my_row = -1;
   float my_w = 0.0f;
   if (lane < p.K) {
@@ -235,41 +233,27 @@ __global__ __launch_bounds__(kRowThreads) void transpose_rows_kernel(RowParams p
     }
   }
   uint64_t todo = __ballot(my_row >= 0);
-  if (todo == 0) return;
-  const int v0 = seg * (kWave * U) + lane;
-  const f32x4 *src = gout + (int64_t)t * p.nvec;
-  f32x4 r[U];
-#pragma unroll
-  for (int i = 0; i < U; ++i) {
-    const int v = v0 + i * kWave;
-    if (v < p.nvec) r[i] = src[v];
-  }
   while (todo) {
     const int k = __builtin_ctzll(todo);
     todo &= todo - 1;
     const int row = read_lane(my_row, k);
     const float a = read_lane(my_w, k);
-    f32x4 *dst = gy + (int64_t)row * p.nvec;
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      const int v = v0 + i * kWave;
-      if (v < p.nvec) {
-        f32x4 o;
-        o.x = a * r[i].x;
-        o.y = a * r[i].y;
-        o.z = a * r[i].z;
-        o.w = a * r[i].w;
-        store_stream(dst + v, o);
-      }
+    if (in_row) {
+      f32x4 o;
+      o.x = a * r.x;
+      o.y = a * r.y;
+      o.z = a * r.z;
+      o.w = a * r.w;
+      store_stream(gy + (int64_t)row * p.nvec + v, o);
     }
   }
 }
 
-__global__ __launch_bounds__(kRowThreads) void transpose_elems_kernel(RowParams p, int32_t H, const float *__restrict__ gout,
+__global__ __launch_bounds__(kElemThreads) void transpose_elems_kernel(RowParams p, int32_t H, const float *__restrict__ gout,
                                                                       const float *__restrict__ row_weight,
                                                                       int64_t weight_rows, float *__restrict__ gy,
                                                                       int64_t gy_rows) {
-  const int64_t i = (int64_t)blockIdx.x * kRowThreads + threadIdx.x;
+  const int64_t i = (int64_t)blockIdx.x * kElemThreads + threadIdx.x;
   if (i >= (int64_t)p.T * H) return;
   const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
   const float g = gout[i];
@@ -282,55 +266,28 @@ __global__ __launch_bounds__(kRowThreads) void transpose_elems_kernel(RowParams 
   }
 }
 
-// Vectors per lane: the smallest waste, then the fewest segments, over the compiled widths.
-static inline int pick_unroll(int nvec) {
-  static const int widths[] = {8, 7, 6, 5, 4, 3, 2, 1};
-  int best = 1;
-  int64_t best_cost = -1;
-  for (int u : widths) {
-    const int per = kWave * u;
-    const int nseg = (nvec + per - 1) / per;
-    const int64_t cost = (int64_t)nseg * per - nvec;  // idle lane-slots
-    if (best_cost < 0 || cost < best_cost) {
-      best_cost = cost;
-      best = u;
-    }
-  }
-  return best;
-}
-
 static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
-static inline bool grid_for_units(int64_t nunits, dim3 &grid) {
-  const int64_t blocks = (nunits + kRowWaves - 1) / kRowWaves;
+// Fills nvec / nseg / nunits for rows of `nvec` 16-byte vectors and sizes the grid.
+static inline bool grid_for_units(RowParams &p, int nvec, int block, dim3 &grid) {
+  p.nvec = nvec;
+  p.nseg = (nvec + kWave - 1) / kWave;
+  p.nunits = (int64_t)p.T * p.nseg;
+  const int waves = block / kWave;
+  const int64_t blocks = (p.nunits + waves - 1) / waves;
   if (blocks > 2147483647LL) return false;
   grid = dim3((unsigned)blocks);
   return true;
 }
 
-static inline bool grid_for_elems(int64_t n, dim3 &grid) {
-  const int64_t blocks = (n + kRowThreads - 1) / kRowThreads;
+static inline bool grid_for_elems(RowParams &p, int64_t n, dim3 &grid) {
+  p.nvec = p.nseg = 0;
+  p.nunits = 0;
+  const int64_t blocks = (n + kElemThreads - 1) / kElemThreads;
   if (blocks > 2147483647LL) return false;
   grid = dim3((unsigned)blocks);
   return true;
 }
-
-#define HM_DISPATCH_U(U_, KERNEL, ...)                                                      \
-  case U_:                                                                                  \
-    hipLaunchKernelGGL((KERNEL<U_>), grid, dim3(kRowThreads), 0, stream, __VA_ARGS__);      \
-    break;
-
-#define HM_SWITCH_U(KERNEL, ...)            \
-  switch (U) {                              \
-    HM_DISPATCH_U(1, KERNEL, __VA_ARGS__)   \
-    HM_DISPATCH_U(2, KERNEL, __VA_ARGS__)   \
-    HM_DISPATCH_U(3, KERNEL, __VA_ARGS__)   \
-    HM_DISPATCH_U(4, KERNEL, __VA_ARGS__)   \
-    HM_DISPATCH_U(5, KERNEL, __VA_ARGS__)   \
-    HM_DISPATCH_U(6, KERNEL, __VA_ARGS__)   \
-    HM_DISPATCH_U(7, KERNEL, __VA_ARGS__)   \
-    HM_DISPATCH_U(8, KERNEL, __VA_ARGS__)   \
-  }
 
 }  // namespace hm
 
@@ -360,17 +317,12 @@ extern "C" hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, 
   p.status = plan->status;
   dim3 grid;
   if (H % 8 == 0 && aligned16(x_bf16) && aligned16(packed_bf16)) {
-    p.nvec = H / 8;
-    const int U = pick_unroll(p.nvec);
-    p.nseg = (p.nvec + kWave * U - 1) / (kWave * U);
-    p.nunits = (int64_t)T * p.nseg;
-    if (!grid_for_units(p.nunits, grid)) return HM_ERR_SHAPE;
-    HM_SWITCH_U(dispatch_rows_kernel, p, (const u32x4 *)x_bf16, (u32x4 *)packed_bf16, packed_rows)
+    if (!grid_for_units(p, H / 8, kCopyThreads, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(dispatch_rows_kernel, grid, dim3(kCopyThreads), 0, stream, p, (const u32x4 *)x_bf16,
+                       (u32x4 *)packed_bf16, packed_rows);
   } else {
-    p.nvec = p.nseg = 0;
-    p.nunits = 0;
-    if (!grid_for_elems((int64_t)T * H, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(dispatch_elems_kernel, grid, dim3(kRowThreads), 0, stream, p, H, (const uint16_t *)x_bf16,
+    if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(dispatch_elems_kernel, grid, dim3(kElemThreads), 0, stream, p, H, (const uint16_t *)x_bf16,
                        (uint16_t *)packed_bf16, packed_rows);
   }
   return hm_launch_status();
@@ -393,17 +345,12 @@ extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float 
   p.status = plan->status;
   dim3 grid;
   if (H % 8 == 0 && aligned16(y_bf16) && aligned16(out_bf16)) {
-    p.nvec = H / 8;
-    const int U = pick_unroll(p.nvec);
-    p.nseg = (p.nvec + kWave * U - 1) / (kWave * U);
-    p.nunits = (int64_t)T * p.nseg;
-    if (!grid_for_units(p.nunits, grid)) return HM_ERR_SHAPE;
-    HM_SWITCH_U(combine_rows_kernel, p, (const u32x4 *)y_bf16, y_rows, topk_weights, (u32x4 *)out_bf16)
+    if (!grid_for_units(p, H / 8, kCombineThreads, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(combine_rows_kernel, grid, dim3(kCombineThreads), 0, stream, p, (const u32x4 *)y_bf16, y_rows,
+                       topk_weights, (u32x4 *)out_bf16);
   } else {
-    p.nvec = p.nseg = 0;
-    p.nunits = 0;
-    if (!grid_for_elems((int64_t)T * H, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(combine_elems_kernel, grid, dim3(kRowThreads), 0, stream, p, H, (const uint16_t *)y_bf16, y_rows,
+    if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(combine_elems_kernel, grid, dim3(kElemThreads), 0, stream, p, H, (const uint16_t *)y_bf16, y_rows,
                        topk_weights, (uint16_t *)out_bf16);
   }
   return hm_launch_status();
@@ -427,17 +374,12 @@ extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t 
   p.status = plan->status;
   dim3 grid;
   if (H % 4 == 0 && aligned16(gout) && aligned16(gy)) {
-    p.nvec = H / 4;
-    const int U = pick_unroll(p.nvec);
-    p.nseg = (p.nvec + kWave * U - 1) / (kWave * U);
-    p.nunits = (int64_t)T * p.nseg;
-    if (!grid_for_units(p.nunits, grid)) return HM_ERR_SHAPE;
-    HM_SWITCH_U(transpose_rows_kernel, p, (const f32x4 *)gout, plan->row_weight, plan->row_capacity, (f32x4 *)gy, gy_rows)
+    if (!grid_for_units(p, H / 4, kCopyThreads, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(transpose_rows_kernel, grid, dim3(kCopyThreads), 0, stream, p, (const f32x4 *)gout, plan->row_weight,
+                       plan->row_capacity, (f32x4 *)gy, gy_rows);
   } else {
-    p.nvec = p.nseg = 0;
-    p.nunits = 0;
-    if (!grid_for_elems((int64_t)T * H, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(transpose_elems_kernel, grid, dim3(kRowThreads), 0, stream, p, H, gout, plan->row_weight,
+    if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL(transpose_elems_kernel, grid, dim3(kElemThreads), 0, stream, p, H, gout, plan->row_weight,
                        plan->row_capacity, gy, gy_rows);
   }
   return hm_launch_status();
