@@ -9,12 +9,17 @@
 //   plan_count_kernel  per-workgroup, per-destination counts of kept slots -> workspace
 //   plan_write_kernel  every workgroup re-reads the (small) count matrix to get its own base
 //                      rows and the destination totals, then writes the index maps.
+// Both first stage the rank and destination of their 1024 slots, plus a halo of K-1 slots on
+// either side (the rest of the first and last token), in LDS: each expert id is looked up once
+// and all "same destination as an earlier / later slot of my token" questions become LDS reads.
 #include "hm_device.h"
 
 namespace hm {
 
 constexpr int kPlanThreads = 1024;
 constexpr int kPlanWaves = kPlanThreads / kWave;
+constexpr int kPlanHalo = 63;                              // K - 1 <= 63
+constexpr int kPlanStaged = kPlanThreads + 2 * kPlanHalo;
 
 struct PlanParams {
   const int32_t *ids;
@@ -32,47 +37,65 @@ struct PlanParams {
   int32_t *status;
 };
 
-__device__ __forceinline__ int dest_of_rank(const PlanParams &p, int rank) {
-  return p.level == HM_DEDUP_NODE ? rank / p.R : rank;
-}
+// What one lane knows about its slot after staging.
+struct Slot {
+  bool live;   // inside the table
+  int t, k;    // token and position in the token
+  int tok0;    // LDS index of the token's slot 0
+  int rank;    // -1: invalid expert id or placement entry
+  int dest;    // destination at the chosen level, -1 if invalid
+  bool keep;   // owns the row of (token, dest)
+};
 
-// Destination of slot (t,k) (-1: invalid slot) and whether the slot owns the row of its
-// (token, destination) pair: always at level none, else iff no earlier slot of the token has the
-// same destination -- the OR over a group's experts in Eq.(7) leaves one copy per group.
-__device__ __forceinline__ int slot_destination(const PlanParams &p, int t, int k, int &rank, bool &keep) {
-  const int32_t *tok = p.ids + (int64_t)t * p.K;
-  rank = rank_of(p.expert_to_rank, p.E, p.G, tok[k]);
-  keep = false;
-  if (rank < 0) return -1;
-  const int dest = dest_of_rank(p, rank);
-  keep = true;
-  if (p.level != HM_DEDUP_NONE) {
-    for (int k1 = 0; k1 < k; ++k1) {
-      const int r1 = rank_of(p.expert_to_rank, p.E, p.G, tok[k1]);
-      if (r1 >= 0 && dest_of_rank(p, r1) == dest) {
-        keep = false;
-        break;
-      }
+// Stage rank / destination of slots [first - halo, first + 1024 + halo) and classify this lane's
+// slot.  A slot owns its (token, destination) row at level none always, else iff no earlier slot
+// of the token has the same destination: the OR over a group's experts in Eq.(7) leaves one copy
+// per group, and the lowest k keeps it.
+__device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *s_rank, int8_t *s_dest) {
+  const int halo = p.K - 1;
+  const int64_t first = (int64_t)blockIdx.x * kPlanThreads;
+  for (int i = threadIdx.x; i < kPlanThreads + 2 * halo; i += kPlanThreads) {
+    const int64_t s = first - halo + i;
+    int r = -1, d = -1;
+    if (s >= 0 && s < p.nslots) {
+      r = rank_of(p.expert_to_rank, p.E, p.G, p.ids[s]);
+      if (r >= 0) d = p.level == HM_DEDUP_NODE ? r / p.R : r;
     }
+    s_rank[i] = (int8_t)r;
+    s_dest[i] = (int8_t)d;
   }
-  return dest;
+  __syncthreads();
+  Slot me;
+  const int64_t s = first + threadIdx.x;
+  me.live = s < p.nslots;
+  me.t = me.k = me.tok0 = 0;
+  me.rank = me.dest = -1;
+  me.keep = false;
+  if (me.live) {
+    me.t = (int)(s / p.K);
+    me.k = (int)(s - (int64_t)me.t * p.K);
+    const int own = halo + (int)threadIdx.x;
+    me.tok0 = own - me.k;
+    me.rank = s_rank[own];
+    me.dest = s_dest[own];
+    me.keep = me.dest >= 0;
+    if (me.keep && p.level != HM_DEDUP_NONE)
+      for (int k1 = 0; k1 < me.k; ++k1)
+        if (s_dest[me.tok0 + k1] == me.dest) me.keep = false;
+  }
+  return me;
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanParams p) {
+  __shared__ int8_t s_rank[kPlanStaged];
+  __shared__ int8_t s_dest[kPlanStaged];
   __shared__ int32_t wave_cnt[kPlanWaves][kWave];
   const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
-  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
-  int dest = -1;
-  if (s < p.nslots) {
-    const int t = (int)(s / p.K), k = (int)(s - (int64_t)t * p.K);
-    int rank;
-    bool keep;
-    const int d = slot_destination(p, t, k, rank, keep);
-    if (keep) dest = d;
-  }
+  const Slot me = stage_and_classify(p, s_rank, s_dest);
+  const int kept_dest = me.keep ? me.dest : -1;
   int mine = 0;  // lane d ends up with the wave's count for destination d
   for (int d = 0; d < p.Dn; ++d) {
-    const uint64_t b = __ballot(dest == d);
+    const uint64_t b = __ballot(kept_dest == d);
     if (lane == d) mine = __popcll(b);
   }
   wave_cnt[wv][lane] = mine;
@@ -86,6 +109,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanParams p) 
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) {
+  __shared__ int8_t s_rank[kPlanStaged];
+  __shared__ int8_t s_dest[kPlanStaged];
   __shared__ int32_t part_tot[kPlanWaves][kWave];
   __shared__ int32_t part_pre[kPlanWaves][kWave];
   __shared__ int32_t block_base[kWave];             // first row of this workgroup per destination
@@ -108,16 +133,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
     part_pre[wv][lane] = pre;
   }
 
-  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
-  const bool live = s < p.nslots;
-  int t = 0, k = 0, rank = -1, dest = -1;
-  bool keep = false;
-  if (live) {
-    t = (int)(s / p.K);
-    k = (int)(s - (int64_t)t * p.K);
-    dest = slot_destination(p, t, k, rank, keep);
-  }
-  const int kept_dest = keep ? dest : -1;
+  const Slot me = stage_and_classify(p, s_rank, s_dest);   // contains a barrier
+  const int kept_dest = me.keep ? me.dest : -1;
   for (int d = 0; d < p.Dn; ++d) {
     const uint64_t b = __ballot(kept_dest == d);
     if (lane == d) ballots[wv][d] = b;
@@ -151,50 +168,49 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   }
   __syncthreads();
 
-  if (!live) return;
-  if (rank < 0) {
+  if (!me.live) return;
+  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
+  if (me.rank < 0) {
     p.slot_row[s] = -1;
     p.slot_keep[s] = 0;
     flag(p.status, HM_ERR_BAD_ID);
-  } else if (!keep) {
+  } else if (!me.keep) {
     p.slot_keep[s] = 0;  // its slot_row is written by the slot that owns the row
   } else {
-    const uint64_t b = ballots[wv][dest];
+    const uint64_t b = ballots[wv][me.dest];
     const int pos = __popcll(b & ((1ull << lane) - 1ull));
-    const int row = block_base[dest] + wave_base[wv][dest] + pos;
+    const int row = block_base[me.dest] + wave_base[wv][me.dest] + pos;
     p.slot_keep[s] = 1;
     p.slot_row[s] = row;
     float wsum = p.weights[s];
     if (p.level != HM_DEDUP_NONE) {
-      const int32_t *tok = p.ids + (int64_t)t * p.K;
-      for (int k2 = k + 1; k2 < p.K; ++k2) {
-        const int r2 = rank_of(p.expert_to_rank, p.E, p.G, tok[k2]);
-        if (r2 >= 0 && dest_of_rank(p, r2) == dest) {
-          p.slot_row[(int64_t)t * p.K + k2] = row;
-          wsum = wsum + p.weights[(int64_t)t * p.K + k2];  // ascending k, fp32
+      for (int k2 = me.k + 1; k2 < p.K; ++k2) {
+        if (s_dest[me.tok0 + k2] == me.dest) {
+          const int64_t s2 = s + (k2 - me.k);
+          p.slot_row[s2] = row;
+          wsum = wsum + p.weights[s2];  // ascending k, fp32
         }
       }
     }
     if (row < p.row_capacity) {
-      p.row_token[row] = t;
+      p.row_token[row] = me.t;
       p.row_weight[row] = wsum;
     } else {
       flag(p.status, HM_ERR_CAPACITY);
     }
   }
-  if (k == 0 && (p.rank_mask || p.node_mask)) {
-    const int32_t *tok = p.ids + (int64_t)t * p.K;
+  if (me.k == 0 && (p.rank_mask || p.node_mask)) {
     uint64_t rm = 0;
     uint32_t nm = 0;
     for (int k2 = 0; k2 < p.K; ++k2) {
-      const int r2 = rank_of(p.expert_to_rank, p.E, p.G, tok[k2]);
+      const int r2 = s_rank[me.tok0 + k2];
       if (r2 >= 0) {
         rm |= 1ull << r2;
         nm |= 1u << (r2 / p.R);
       }
     }
-    if (p.rank_mask) p.rank_mask[t] = rm;
-    if (p.node_mask) p.node_mask[t] = nm;
+    if (p.rank_mask) p.rank_mask[me.t] = rm;
+    if (p.node_mask) p.node_mask[me.t] = nm;
   }
 }
 

@@ -7,11 +7,14 @@
 // visit and readlane broadcasts each row index into a scalar register, so every global access
 // is a base + lane*16 B coalesced stream of 16-byte vectors.
 //
-// A segment is 64 consecutive 16-byte vectors (1 KiB, one vector per lane).  Work items this
-// small matter on MI355X: a kernel here lasts well under 100 us, so with multi-KiB items the
-// last round of waves leaves most of the chip idle; 1 KiB items measured 15-20 % faster than
-// 7 KiB ones on the 14 KiB rows of the DeepSeek-V3 shape.  Combine issues the loads of up to
-// four rows before the first use so a wave still keeps several KiB in flight.
+// Dispatch and transpose use segments of 64 consecutive 16-byte vectors (1 KiB, one vector per
+// lane).  Work items this small matter on MI355X: a kernel here lasts well under 100 us, so with
+// multi-KiB items the last round of waves leaves most of the chip idle; 1 KiB items measured
+// 15-20 % faster than 7 KiB ones on the 14 KiB rows of the DeepSeek-V3 shape.  Combine, which is
+// read-heavy, did best with 4 KiB segments (4 vectors per lane) and the loads of up to four rows
+// issued before the first use.  Every row-sized stream is read and written with non-temporal
+// accesses: rows are touched once per kernel, and output lines left dirty in the caches were
+// measured to slow the next kernel down by about 10 %.
 #include "hm_device.h"
 
 namespace hm {
@@ -19,12 +22,13 @@ namespace hm {
 constexpr int kElemThreads = 256;   // element-wise fallback kernels
 constexpr int kCopyThreads = 128;   // dispatch / transpose: 2 waves per workgroup
 constexpr int kCombineThreads = 256;
-constexpr int kCombineRows = 4;     // rows whose loads are in flight together
+constexpr int kCombineVecs = 4;     // combine: 16-byte vectors per lane (4 KiB segments)
+constexpr int kCombineRows = 4;     // combine: rows whose loads are in flight together
 
 struct RowParams {
   int32_t T, K;
   int32_t nvec;   // 16-byte vectors per row
-  int32_t nseg;   // 64-vector segments per row
+  int32_t nseg;   // segments per row
   int64_t nunits; // T * nseg
   const int32_t *slot_row;
   const uint8_t *slot_keep;
@@ -131,46 +135,58 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
   float agg;
   uint64_t todo = merge_slots(p.K, my_row, my_w, agg);
 
-  const int v = seg * kWave + lane;
-  const bool in_row = v < p.nvec;
-  float acc[8];
+  constexpr int U = kCombineVecs, R = kCombineRows;
+  const int v0 = seg * (kWave * U) + lane;   // this lane's vectors: v0, v0+64, ...
+  float acc[U][8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+  for (int i = 0; i < U; ++i)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[i][e] = 0.0f;
 
   while (todo) {
-    // issue the loads of up to kCombineRows rows, then consume them in the same (ascending k) order
-    u32x4 r[kCombineRows];
-    float a[kCombineRows];
-    bool have[kCombineRows];
+    // issue the loads of up to R rows, then consume them in the same (ascending k) order
+    u32x4 r[R][U];
+    float a[R];
+    bool have[R];
 #pragma unroll
-    for (int j = 0; j < kCombineRows; ++j) {
+    for (int j = 0; j < R; ++j) {
       have[j] = todo != 0;
-      r[j] = (u32x4){0u, 0u, 0u, 0u};
       a[j] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < U; ++i) r[j][i] = (u32x4){0u, 0u, 0u, 0u};
       if (have[j]) {
         const int k = __builtin_ctzll(todo);
         todo &= todo - 1;
         const int row = read_lane(my_row, k);
         a[j] = read_lane(agg, k);
-        if (in_row) r[j] = load_stream(y + (int64_t)row * p.nvec + v);
+        const u32x4 *src = y + (int64_t)row * p.nvec;
+#pragma unroll
+        for (int i = 0; i < U; ++i)
+          if (v0 + i * kWave < p.nvec) r[j][i] = load_stream(src + v0 + i * kWave);
       }
     }
 #pragma unroll
-    for (int j = 0; j < kCombineRows; ++j) {
+    for (int j = 0; j < R; ++j) {
       if (have[j]) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc[2 * e] = __builtin_fmaf(a[j], bf16_lo(r[j][e]), acc[2 * e]);
-          acc[2 * e + 1] = __builtin_fmaf(a[j], bf16_hi(r[j][e]), acc[2 * e + 1]);
-        }
+        for (int i = 0; i < U; ++i)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            acc[i][2 * e] = __builtin_fmaf(a[j], bf16_lo(r[j][i][e]), acc[i][2 * e]);
+            acc[i][2 * e + 1] = __builtin_fmaf(a[j], bf16_hi(r[j][i][e]), acc[i][2 * e + 1]);
+          }
       }
     }
   }
-  if (in_row) {
-    u32x4 o;
+  u32x4 *dst = out + (int64_t)t * p.nvec;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[2 * e], acc[2 * e + 1]);
-    out[(int64_t)t * p.nvec + v] = o;
+  for (int i = 0; i < U; ++i) {
+    if (v0 + i * kWave < p.nvec) {
+      u32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[i][2 * e], acc[i][2 * e + 1]);
+      store_stream(dst + v0 + i * kWave, o);
+    }
   }
 }
 
@@ -269,9 +285,9 @@ __global__ __launch_bounds__(kElemThreads) void transpose_elems_kernel(RowParams
 static inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 // Fills nvec / nseg / nunits for rows of `nvec` 16-byte vectors and sizes the grid.
-static inline bool grid_for_units(RowParams &p, int nvec, int block, dim3 &grid) {
+static inline bool grid_for_units(RowParams &p, int nvec, int vecs_per_lane, int block, dim3 &grid) {
   p.nvec = nvec;
-  p.nseg = (nvec + kWave - 1) / kWave;
+  p.nseg = (nvec + kWave * vecs_per_lane - 1) / (kWave * vecs_per_lane);
   p.nunits = (int64_t)p.T * p.nseg;
   const int waves = block / kWave;
   const int64_t blocks = (p.nunits + waves - 1) / waves;
@@ -317,7 +333,7 @@ extern "C" hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, 
   p.status = plan->status;
   dim3 grid;
   if (H % 8 == 0 && aligned16(x_bf16) && aligned16(packed_bf16)) {
-    if (!grid_for_units(p, H / 8, kCopyThreads, grid)) return HM_ERR_SHAPE;
+    if (!grid_for_units(p, H / 8, 1, kCopyThreads, grid)) return HM_ERR_SHAPE;
     hipLaunchKernelGGL(dispatch_rows_kernel, grid, dim3(kCopyThreads), 0, stream, p, (const u32x4 *)x_bf16,
                        (u32x4 *)packed_bf16, packed_rows);
   } else {
@@ -345,7 +361,7 @@ extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float 
   p.status = plan->status;
   dim3 grid;
   if (H % 8 == 0 && aligned16(y_bf16) && aligned16(out_bf16)) {
-    if (!grid_for_units(p, H / 8, kCombineThreads, grid)) return HM_ERR_SHAPE;
+    if (!grid_for_units(p, H / 8, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
     hipLaunchKernelGGL(combine_rows_kernel, grid, dim3(kCombineThreads), 0, stream, p, (const u32x4 *)y_bf16, y_rows,
                        topk_weights, (u32x4 *)out_bf16);
   } else {
@@ -374,7 +390,7 @@ extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t 
   p.status = plan->status;
   dim3 grid;
   if (H % 4 == 0 && aligned16(gout) && aligned16(gy)) {
-    if (!grid_for_units(p, H / 4, kCopyThreads, grid)) return HM_ERR_SHAPE;
+    if (!grid_for_units(p, H / 4, 1, kCopyThreads, grid)) return HM_ERR_SHAPE;
     hipLaunchKernelGGL(transpose_rows_kernel, grid, dim3(kCopyThreads), 0, stream, p, (const f32x4 *)gout, plan->row_weight,
                        plan->row_capacity, (f32x4 *)gy, gy_rows);
   } else {
