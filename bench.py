@@ -29,6 +29,21 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(workload: str, level: str, kernel: str):
+    """HBM bytes per launch from the committed rocprofv3 counter summaries (None if not measured)."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    for name in sorted(os.listdir(pdir)):
+        if not name.endswith(".txt"):
+            continue
+        for line in open(os.path.join(pdir, name)):
+            f = line.split()
+            if len(f) == 5 and f[0] == "traffic" and f[1:4] == [workload, level, kernel]:
+                return int(f[4])
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,7 +161,8 @@ def main() -> int:
     for n in ("hm_dispatch_pack", "hm_combine"):
         gbs = alg_bytes[n] / (avg_ms[n] * 1e-3) / 1e9
         kern[n] = {"avg_ms": round(avg_ms[n], 5), "min_ms": round(min_ms[n], 5), "alg_bytes": int(alg_bytes[n]),
-                   "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)}
+                   "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
+                   "traffic": measured_traffic(wl.name, level_name, n)}
     dominant = max(kern, key=lambda n: kern[n]["avg_ms"])
     pair_ms = avg_ms["hm_dispatch_pack"] + avg_ms["hm_combine"]
     pair_gbs = (alg_bytes["hm_dispatch_pack"] + alg_bytes["hm_combine"]) / (pair_ms * 1e-3) / 1e9
@@ -222,7 +238,8 @@ def main() -> int:
                    "rows_per_token": round(c, 4), "buffer_sets": nsets,
                    "combine_input": "same-step buffer (warm)" if args.warm_y else "identical buffer written %d steps earlier (cold)" % y_shift},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": kern[dominant]["achieved_GBps"],
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kern[dominant]["frac"], "traffic": None},
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kern[dominant]["frac"],
+                     "traffic": measured_traffic(wl.name, level_name, dominant)},
         "cpu_baseline": cpu,
         "kernels": kern,
         "pair": {"ms": round(pair_ms, 5), "achieved_GBps": round(pair_gbs, 1), "frac": round(pair_gbs / HBM_PEAK_GBS, 4),
