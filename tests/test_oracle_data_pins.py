@@ -87,6 +87,23 @@ def test_combine_exact_rational_small(oracle):
                 assert int(out[t, j]) == exact_round_to_bf16(q), (level, t, j)
 
 
+def test_combine_accumulates_beyond_binary32(oracle):
+    """Sums that sit 2^-30 above a bf16 rounding tie: a binary32 accumulator would land on the tie
+    and round to even (down); the binary64 sum rounded once must round up."""
+    ids = np.array([[0, 2]], np.int32)
+    e2r = np.array([0, 0, 1, 1], np.int32)
+    one = W.f32_to_bf16_bits(np.array([1.0], np.float32))[0]
+    for bump, want in ((2.0 ** -30, 0x3F81), (-2.0 ** -30, 0x3F80), (0.0, 0x3F80)):
+        w = np.array([[1.0, 2.0 ** -8 + bump]], np.float32)
+        assert float(w[0, 1]) == 2.0 ** -8 + bump                       # representable in binary32
+        p = oracle.plan(ids, w, e2r, 2, 1, GPU)
+        y = np.full((p.total_rows, 3), one, np.uint16)
+        out = oracle.combine(y, w, p.slot_row)
+        q = Fraction(1) + Fraction(float(w[0, 1]))
+        assert exact_round_to_bf16(q) == want
+        assert out.tolist() == [[want] * 3], (bump, out)
+
+
 def test_combine_level_none_is_plain_moe_weighted_sum(oracle):
     wl = W.WORKLOADS["tiny"]
     r = W.make_routing(wl, T=256)
