@@ -5,34 +5,40 @@
 // from ballots over the per-token bit masks (lane g accumulates the popcount for group g), so a
 // token is counted once per group however many of its experts live there.  A first tiny launch
 // clears the outputs, then integer atomics merge the workgroups, which keeps the result exact and
-// order-independent.  (One 1024-lane workgroup doing everything in a single launch was measured
-// at 56 us on T=8192, K=8 against 11 us for this pair of launches.)
+// order-independent.  The call is launch-latency bound (two launches, ~11 us on T=8192, K=8);
+// two single-launch designs were measured and dropped: one 1024-lane workgroup doing everything
+// (56 us) and 64 workgroups that each scan the whole table but own a slice of the outputs
+// (44 us) -- both serialise dependent id -> placement loads that the token-split version spreads
+// over the chip.
 #include "hm_device.h"
 
 namespace hm {
 
+struct LoadParams {
+  const int32_t *ids;
+  const int32_t *expert_to_rank;
+  int32_t T, K, E, G, R, N;
+  int32_t *load_expert, *load_rank, *load_node, *status;
+};
+
 constexpr int kLoadThreads = 256;
 constexpr int kLdsExperts = 8192;  // experts histogrammed in LDS; beyond that, global atomics
 
-__global__ __launch_bounds__(kLoadThreads) void load_clear_kernel(int32_t *load_expert, int E, int32_t *load_rank, int G,
-                                                                  int32_t *load_node, int N, int32_t *status) {
+__global__ __launch_bounds__(kLoadThreads) void load_clear_kernel(LoadParams p) {
   const int i = blockIdx.x * kLoadThreads + threadIdx.x;
-  if (i < E) load_expert[i] = 0;
-  if (i < G) load_rank[i] = 0;
-  if (i < N) load_node[i] = 0;
-  if (i == 0 && status) *status = 0;
+  if (i < p.E) p.load_expert[i] = 0;
+  if (i < p.G) p.load_rank[i] = 0;
+  if (i < p.N) p.load_node[i] = 0;
+  if (i == 0 && p.status) *p.status = 0;
 }
 
-__global__ __launch_bounds__(kLoadThreads) void load_count_kernel(const int32_t *__restrict__ ids,
-                                                                  const int32_t *__restrict__ expert_to_rank, int T, int K,
-                                                                  int E, int G, int R, int N, int32_t *load_expert,
-                                                                  int32_t *load_rank, int32_t *load_node, int32_t *status) {
+__global__ __launch_bounds__(kLoadThreads) void load_count_kernel(LoadParams p) {
   __shared__ int32_t hist[kLdsExperts];
   __shared__ int32_t rank_cnt[kWave];
   __shared__ int32_t node_cnt[kWave];
-  const bool lds_hist = E <= kLdsExperts;
+  const bool lds_hist = p.E <= kLdsExperts;
   if (lds_hist)
-    for (int e = threadIdx.x; e < E; e += kLoadThreads) hist[e] = 0;
+    for (int e = threadIdx.x; e < p.E; e += kLoadThreads) hist[e] = 0;
   if (threadIdx.x < kWave) {
     rank_cnt[threadIdx.x] = 0;
     node_cnt[threadIdx.x] = 0;
@@ -43,43 +49,43 @@ __global__ __launch_bounds__(kLoadThreads) void load_count_kernel(const int32_t 
   int my_rank_cnt = 0, my_node_cnt = 0;  // lane g: tokens of this wave's share that reach group g
   const int64_t stride = (int64_t)gridDim.x * kLoadThreads;
   // every lane of a wave runs the same number of rounds so the ballots stay convergent
-  const int64_t rounds = ((int64_t)T + stride - 1) / stride;
+  const int64_t rounds = ((int64_t)p.T + stride - 1) / stride;
   for (int64_t it = 0; it < rounds; ++it) {
     const int64_t t = it * stride + (int64_t)blockIdx.x * kLoadThreads + threadIdx.x;
     uint64_t rm = 0;
     uint32_t nm = 0;
-    if (t < T) {
-      const int32_t *tok = ids + t * K;
-      for (int k = 0; k < K; ++k) {
+    if (t < p.T) {
+      const int32_t *tok = p.ids + t * p.K;
+      for (int k = 0; k < p.K; ++k) {
         const int id = tok[k];
-        const int g = rank_of(expert_to_rank, E, G, id);
+        const int g = rank_of(p.expert_to_rank, p.E, p.G, id);
         if (g < 0) {
-          flag(status, HM_ERR_BAD_ID);
+          flag(p.status, HM_ERR_BAD_ID);
           continue;
         }
         if (lds_hist) atomicAdd(&hist[id], 1);
-        else atomicAdd(&load_expert[id], 1);
+        else atomicAdd(&p.load_expert[id], 1);
         rm |= 1ull << g;
-        nm |= 1u << (g / R);
+        nm |= 1u << (g / p.R);
       }
     }
-    for (int g = 0; g < G; ++g) {
-      const uint64_t b = __ballot((rm >> g) & 1ull);
-      if (lane == g) my_rank_cnt += __popcll(b);
+    for (int g = 0; g < p.G; ++g) {
+      const uint64_t bal = __ballot((rm >> g) & 1ull);
+      if (lane == g) my_rank_cnt += __popcll(bal);
     }
-    for (int n = 0; n < N; ++n) {
-      const uint64_t b = __ballot((nm >> n) & 1u);
-      if (lane == n) my_node_cnt += __popcll(b);
+    for (int n = 0; n < p.N; ++n) {
+      const uint64_t bal = __ballot((nm >> n) & 1u);
+      if (lane == n) my_node_cnt += __popcll(bal);
     }
   }
-  if (lane < G && my_rank_cnt) atomicAdd(&rank_cnt[lane], my_rank_cnt);
-  if (lane < N && my_node_cnt) atomicAdd(&node_cnt[lane], my_node_cnt);
+  if (lane < p.G && my_rank_cnt) atomicAdd(&rank_cnt[lane], my_rank_cnt);
+  if (lane < p.N && my_node_cnt) atomicAdd(&node_cnt[lane], my_node_cnt);
   __syncthreads();
   if (lds_hist)
-    for (int e = threadIdx.x; e < E; e += kLoadThreads)
-      if (hist[e]) atomicAdd(&load_expert[e], hist[e]);
-  if ((int)threadIdx.x < G && rank_cnt[threadIdx.x]) atomicAdd(&load_rank[threadIdx.x], rank_cnt[threadIdx.x]);
-  if ((int)threadIdx.x < N && node_cnt[threadIdx.x]) atomicAdd(&load_node[threadIdx.x], node_cnt[threadIdx.x]);
+    for (int e = threadIdx.x; e < p.E; e += kLoadThreads)
+      if (hist[e]) atomicAdd(&p.load_expert[e], hist[e]);
+  if ((int)threadIdx.x < p.G && rank_cnt[threadIdx.x]) atomicAdd(&p.load_rank[threadIdx.x], rank_cnt[threadIdx.x]);
+  if ((int)threadIdx.x < p.N && node_cnt[threadIdx.x]) atomicAdd(&p.load_node[threadIdx.x], node_cnt[threadIdx.x]);
 }
 
 }  // namespace hm
@@ -95,16 +101,26 @@ extern "C" hm_status hm_expert_load(const int32_t *topk_ids, const int32_t *expe
   if (T > 0 && !topk_ids) return HM_ERR_NULL;
   st = hm_check_topology(topo);
   if (st != HM_OK) return st;
-  const int G = topo.nodes * topo.ranks_per_node, N = topo.nodes;
   hipStream_t stream = (hipStream_t)hip_stream;
-  const int clear_blocks = ((E > kWave ? E : kWave) + kLoadThreads - 1) / kLoadThreads;
-  hipLaunchKernelGGL(load_clear_kernel, dim3(clear_blocks), dim3(kLoadThreads), 0, stream, load_expert, E, load_rank, G,
-                     load_node, N, status);
+  LoadParams p;
+  p.ids = topk_ids;
+  p.expert_to_rank = expert_to_rank;
+  p.T = T;
+  p.K = K;
+  p.E = E;
+  p.R = topo.ranks_per_node;
+  p.G = topo.nodes * topo.ranks_per_node;
+  p.N = topo.nodes;
+  p.load_expert = load_expert;
+  p.load_rank = load_rank;
+  p.load_node = load_node;
+  p.status = status;
+  const int most = E > kWave ? E : kWave;
+  hipLaunchKernelGGL(load_clear_kernel, dim3((most + kLoadThreads - 1) / kLoadThreads), dim3(kLoadThreads), 0, stream, p);
   if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   if (T == 0) return HM_OK;
   int64_t blocks = ((int64_t)T + kLoadThreads - 1) / kLoadThreads;
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(load_count_kernel, dim3((unsigned)blocks), dim3(kLoadThreads), 0, stream,
-                     topk_ids, expert_to_rank, T, K, E, G, topo.ranks_per_node, N, load_expert, load_rank, load_node, status);
+  hipLaunchKernelGGL(load_count_kernel, dim3((unsigned)blocks), dim3(kLoadThreads), 0, stream, p);
   return hm_launch_status();
 }

@@ -133,6 +133,19 @@ def test_full_size_stress_sampled(hw, oracle):
     gout = W.make_output_grads(wl)
     gout_d = hw.dev(gout)
     rng = np.random.default_rng(1234)
+    # T above the single-launch limit: the split (clear + atomics) path of hm_expert_load
+    le, lr, ln, st = oracle.expert_load(r.topk_ids, r.expert_to_rank, wl.nodes, wl.ranks_per_node)
+    le_d, lr_d, ln_d = (torch.full((m,), -1, dtype=torch.int32, device="cuda") for m in (wl.E, wl.G, wl.nodes))
+    st_d = torch.full((1,), 9, dtype=torch.int32, device="cuda")
+    B.hm_expert_load(hw.dev(r.topk_ids), hw.dev(r.expert_to_rank), wl.nodes, wl.ranks_per_node, le_d, lr_d, ln_d, st_d)
+    assert np.array_equal(le_d.cpu().numpy(), le) and np.array_equal(lr_d.cpu().numpy(), lr)
+    assert np.array_equal(ln_d.cpu().numpy(), ln) and int(st_d.item()) == 0
+    bad = r.topk_ids.copy()
+    bad[40000, 3] = wl.E + 5
+    le, lr, ln, st = oracle.expert_load(bad, r.expert_to_rank, wl.nodes, wl.ranks_per_node)
+    B.hm_expert_load(hw.dev(bad), hw.dev(r.expert_to_rank), wl.nodes, wl.ranks_per_node, le_d, lr_d, ln_d, st_d)
+    assert np.array_equal(le_d.cpu().numpy(), le) and np.array_equal(lr_d.cpu().numpy(), lr)
+    assert np.array_equal(ln_d.cpu().numpy(), ln) and int(st_d.item()) == st == B.HM_ERR_BAD_ID
     for level in wl.levels:
         ctx = "stress full level=%s" % LEVEL[level]
         print("case:", ctx, flush=True)
