@@ -20,6 +20,7 @@ _SRC = os.path.join(_HERE, "hmo.c")
 _LIB = os.path.join(_HERE, "libhmo.so")
 
 LEVEL_NONE, LEVEL_GPU, LEVEL_NODE = 0, 1, 2
+RECV_INTRA_NODE, RECV_LOCAL_EXPERTS = 0, 1
 BAD_ID = -7
 
 # No -ffast-math, no contraction: the float adds and the single float multiply must be IEEE.
@@ -176,6 +177,73 @@ def expert_load(topk_ids, expert_to_rank, nodes: int, ranks_per_node: int):
     if rc != 0:
         raise ValueError("hmo_expert_load: argument error %d" % rc)
     return le, lr, ln, int(status[0])
+
+
+def recv_dest_map(expert_to_rank, nodes: int, ranks_per_node: int, my_rank: int, stage: int):
+    """(dest_map[E], num_dest): destination of each expert as seen by `my_rank` at a receiver stage."""
+    lib = _load()
+    e2r = _c(expert_to_rank, np.int32)
+    E = e2r.shape[0]
+    dm = np.full(E, -9, np.int32)
+    nd = ctypes.c_int32(0)
+    rc = lib.hmo_recv_dest_map(_p(e2r), ctypes.c_int32(E), ctypes.c_int32(nodes), ctypes.c_int32(ranks_per_node),
+                               ctypes.c_int32(my_rank), ctypes.c_int32(stage), _p(dm), ctypes.byref(nd))
+    if rc != 0:
+        raise ValueError("hmo_recv_dest_map: argument error %d" % rc)
+    return dm, int(nd.value)
+
+
+def plan_mapped(ids, weights, dest_map, num_dest: int, dedup: bool) -> Plan:
+    """Plan for an arbitrary expert -> destination table; Plan.rank_mask holds the destination mask."""
+    lib = _load()
+    ids = _c(ids, np.int32)
+    w = _c(weights, np.float32)
+    dm = _c(dest_map, np.int32)
+    rows, K = ids.shape
+    E = dm.shape[0]
+    dest_count = np.zeros(num_dest, np.int32)
+    dest_offset = np.zeros(num_dest + 1, np.int32)
+    row_token = np.full(max(rows * K, 1), -1, np.int32)
+    slot_row = np.full((rows, K), -1, np.int32)
+    slot_keep = np.zeros((rows, K), np.uint8)
+    row_weight = np.zeros(max(rows * K, 1), np.float32)
+    dest_mask = np.zeros(max(rows, 1), np.uint64)
+    status = np.zeros(1, np.int32)
+    # numpy hands out a null pointer for empty arrays; the C side wants real ones
+    ids_p = ids if ids.size else np.zeros((1, K), np.int32)
+    w_p = w if w.size else np.zeros((1, K), np.float32)
+    sr_p = slot_row if slot_row.size else np.zeros((1, K), np.int32)
+    sk_p = slot_keep if slot_keep.size else np.zeros((1, K), np.uint8)
+    rc = lib.hmo_plan_mapped(_p(ids_p), _p(w_p), _p(dm), ctypes.c_int32(rows), ctypes.c_int32(K), ctypes.c_int32(E),
+                             ctypes.c_int32(num_dest), ctypes.c_int32(1 if dedup else 0), _p(dest_count),
+                             _p(dest_offset), _p(row_token), _p(sr_p), _p(sk_p), _p(row_weight), _p(dest_mask),
+                             _p(status))
+    if rc != 0:
+        raise ValueError("hmo_plan_mapped: argument error %d" % rc)
+    total = int(dest_offset[num_dest])
+    return Plan(LEVEL_GPU if dedup else LEVEL_NONE, num_dest, dest_count, dest_offset, row_token[:total].copy(),
+                slot_row, slot_keep, row_weight[:total].copy(), dest_mask[:rows], np.zeros(rows, np.uint32),
+                int(status[0]))
+
+
+def combine_mix(y_bf16: np.ndarray, weights, slot_row) -> np.ndarray:
+    """out[i] = bf16(sum_k w[i,k] Y[slot_row[i,k]] / sum_k w[i,k]) over the valid slots, binary64."""
+    lib = _load()
+    y = _c(y_bf16, np.uint16)
+    w = _c(weights, np.float32)
+    sr = _c(slot_row, np.int32)
+    rows, K = sr.shape
+    H = y.shape[1]
+    out = np.empty((rows, H), np.uint16)
+    if out.size == 0:
+        return out
+    if y.shape[0] == 0:
+        y = np.zeros((1, H), np.uint16)
+    rc = lib.hmo_combine_mix(_p(y), ctypes.c_int64(y.shape[0]), _p(w), _p(sr), ctypes.c_int64(rows), ctypes.c_int32(K),
+                             ctypes.c_int64(H), _p(out))
+    if rc != 0:
+        raise ValueError("hmo_combine_mix: argument error %d" % rc)
+    return out
 
 
 def f64_to_bf16(v: float) -> int:

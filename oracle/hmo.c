@@ -280,5 +280,143 @@ int hmo_expert_load(const int32_t *topk_ids, const int32_t *expert_to_rank, int3
     return HMO_OK;
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Receiver side of the two-hop exchange (HD2, Section III-A: an Inter-node AlltoAll followed by an
+ * Intra-node AlltoAll, duplicates removed in both dimensions; Alg.1's process() step: the tokens a
+ * rank received become the input of the next level).  A received row carries the top-K expert
+ * ids and router weights of the token behind it; what changes from hop to hop is only the map
+ * from an expert to a destination of that hop.
+ * ------------------------------------------------------------------------------------------------ */
+enum { HMO_RECV_INTRA_NODE = 0, HMO_RECV_LOCAL_EXPERTS = 1 };
+
+/*
+ * hmo_recv_dest_map -- destination of every expert as seen from rank `my_rank` at a stage:
+ *   INTRA_NODE     experts on a rank of my node -> that rank's index inside the node (0..R-1);
+ *                  experts on other nodes -> -1 (their copies travelled to other nodes).
+ *                  The rank groups of one node are contiguous (Section III-B), so this is the
+ *                  G-group mask of Eq.(7) restricted to the G/U[1] groups of my node.
+ *   LOCAL_EXPERTS  experts placed on my rank -> 0,1,2,.. in ascending expert id; all others -> -1.
+ * Placement entries outside [0,G) map to -2 (invalid).  *num_dest receives R, respectively the
+ * number of experts on my rank.
+ */
+int hmo_recv_dest_map(const int32_t *expert_to_rank, int32_t E, int32_t nodes, int32_t ranks_per_node,
+                      int32_t my_rank, int32_t stage, int32_t *dest_map, int32_t *num_dest)
+{
+    if (!expert_to_rank || !dest_map || !num_dest || E <= 0 || nodes <= 0 || ranks_per_node <= 0) return HMO_ERR_ARG;
+    const int32_t G = nodes * ranks_per_node;
+    if (my_rank < 0 || my_rank >= G) return HMO_ERR_ARG;
+    if (stage != HMO_RECV_INTRA_NODE && stage != HMO_RECV_LOCAL_EXPERTS) return HMO_ERR_ARG;
+    int32_t next_local = 0;
+    for (int32_t e = 0; e < E; ++e) {
+        const int32_t g = expert_to_rank[e];
+        if (g < 0 || g >= G) { dest_map[e] = -2; continue; }
+        if (stage == HMO_RECV_INTRA_NODE)
+            dest_map[e] = (g / ranks_per_node == my_rank / ranks_per_node) ? g % ranks_per_node : -1;
+        else
+            dest_map[e] = (g == my_rank) ? next_local++ : -1;
+    }
+    *num_dest = (stage == HMO_RECV_INTRA_NODE) ? ranks_per_node : next_local;
+    return HMO_OK;
+}
+
+/*
+ * hmo_plan_mapped -- the plan of hmo_plan for an arbitrary expert -> destination table:
+ * dest_map[e] in [0,num_dest) is a destination, -1 means "no copy at this hop" (the slot is
+ * skipped without error: slot_row = -1, slot_keep = 0), anything else or an id outside [0,E) is
+ * invalid (skipped, *status = HMO_BAD_ID).  dedup != 0 keeps one row per (row, destination) as in
+ * Eq.(7), the lowest k owning it; dedup == 0 gives every valid slot its own row.  Everything else
+ * (counts, offsets, stable order, row weights) is as in hmo_plan.  dest_mask[i] (optional) gets
+ * bit d set iff row i has a valid slot for destination d.
+ */
+int hmo_plan_mapped(const int32_t *ids, const float *weights, const int32_t *dest_map, int32_t rows, int32_t K,
+                    int32_t E, int32_t num_dest, int32_t dedup, int32_t *dest_count, int32_t *dest_offset,
+                    int32_t *row_token, int32_t *slot_row, uint8_t *slot_keep, float *row_weight,
+                    uint64_t *dest_mask, int32_t *status)
+{
+    if (!ids || !weights || !dest_map || !dest_count || !dest_offset || !row_token || !slot_row || !slot_keep ||
+        !row_weight || !status)
+        return HMO_ERR_ARG;
+    if (rows < 0 || K <= 0 || E <= 0 || num_dest <= 0 || num_dest > 64) return HMO_ERR_ARG;
+    *status = HMO_OK;
+    for (int32_t d = 0; d < num_dest; ++d) dest_count[d] = 0;
+    /* destination of every slot, ownership flags, counts */
+    for (int32_t i = 0; i < rows; ++i) {
+        uint64_t mask = 0;
+        for (int32_t k = 0; k < K; ++k) {
+            const size_t s = (size_t)i * K + k;
+            const int32_t id = ids[s];
+            int32_t d = -1;
+            if (id < 0 || id >= E) *status = HMO_BAD_ID;
+            else if (dest_map[id] >= 0 && dest_map[id] < num_dest) d = dest_map[id];
+            else if (dest_map[id] != -1) *status = HMO_BAD_ID;
+            slot_row[s] = d;                       /* holds the destination until rows are numbered */
+            int keep = d >= 0;
+            if (keep && dedup)
+                for (int32_t k1 = 0; k1 < k; ++k1)
+                    if (slot_row[(size_t)i * K + k1] == d) keep = 0;
+            slot_keep[s] = (uint8_t)keep;
+            if (keep) dest_count[d] += 1;
+            if (d >= 0) mask |= (uint64_t)1 << d;
+        }
+        if (dest_mask) dest_mask[i] = mask;
+    }
+    dest_offset[0] = 0;
+    for (int32_t d = 0; d < num_dest; ++d) dest_offset[d + 1] = dest_offset[d] + dest_count[d];
+    /* number the rows: ascending flat slot index inside each destination */
+    int32_t cursor[64], row_of[64];
+    for (int32_t d = 0; d < num_dest; ++d) cursor[d] = dest_offset[d];
+    for (int32_t i = 0; i < rows; ++i) {
+        for (int32_t d = 0; d < num_dest; ++d) row_of[d] = -1;
+        for (int32_t k = 0; k < K; ++k) {
+            const size_t s = (size_t)i * K + k;
+            const int32_t d = slot_row[s];
+            if (d < 0) continue;                   /* stays -1 */
+            if (slot_keep[s]) {
+                const int32_t row = cursor[d]++;
+                row_token[row] = i;
+                row_weight[row] = weights[s];
+                row_of[d] = row;
+                slot_row[s] = row;
+            } else {
+                slot_row[s] = row_of[d];
+                row_weight[row_of[d]] = row_weight[row_of[d]] + weights[s];   /* ascending k, binary32 */
+            }
+        }
+    }
+    return HMO_OK;
+}
+
+/*
+ * hmo_combine_mix -- the merge a receiving rank performs before it sends results back one hop:
+ * the row it returns for a received token is the weight-normalised mixture of what came back
+ * for that token's slots,
+ *     out[i][j] = bf16( (sum_k w[i,k] * Y[slot_row[i,k]][j]) / (sum_k w[i,k]) ),
+ * both sums over the slots with slot_row >= 0, in binary64, rounded once.  With these mixtures
+ * as the packed-layout Y of the previous hop, hmo_combine at the source reproduces
+ * sum_k w_k f_k(x) exactly (up to the bf16 roundings of the rows in flight).  A row without a
+ * valid slot gives zeros.
+ */
+int hmo_combine_mix(const uint16_t *y, int64_t y_rows, const float *weights, const int32_t *slot_row,
+                    int64_t rows, int32_t K, int64_t H, uint16_t *out)
+{
+    if (!y || !weights || !slot_row || !out || rows < 0 || K <= 0 || H <= 0) return HMO_ERR_ARG;
+    for (int64_t i = 0; i < rows; ++i) {
+        double wsum = 0.0;
+        for (int32_t k = 0; k < K; ++k)
+            if (slot_row[i * K + k] >= 0) wsum += (double)weights[i * K + k];
+        for (int64_t j = 0; j < H; ++j) {
+            double acc = 0.0;
+            for (int32_t k = 0; k < K; ++k) {
+                const int64_t row = slot_row[i * K + k];
+                if (row < 0) continue;
+                if (row >= y_rows) return HMO_ERR_ARG;
+                acc += (double)weights[i * K + k] * bf16_to_f64(y[row * H + j]);
+            }
+            out[i * H + j] = f64_to_bf16_rne(wsum != 0.0 ? acc / wsum : 0.0);
+        }
+    }
+    return HMO_OK;
+}
+
 /* Exposed so tests can pin the rounding routine by itself. */
 uint16_t hmo_f64_to_bf16(double v) { return f64_to_bf16_rne(v); }

@@ -120,3 +120,38 @@ def exact_round_to_bf16(q: Fraction) -> int:
     else:
         pick = i - 1 if (int(_ENC[i - 1]) & 1) == 0 else i
     return sign | int(_ENC[pick])
+
+
+def brute_plan_mapped(ids, w, dest_map, num_dest, dedup):
+    """Set-based plan for an arbitrary expert -> destination table (-1 = no copy at this hop)."""
+    rows_n, K = ids.shape
+
+    def dest(i, k):
+        return int(dest_map[ids[i, k]])
+
+    valid = [(i, k) for i in range(rows_n) for k in range(K) if dest(i, k) >= 0]
+    if dedup:
+        rows = sorted({(dest(i, k), i) for i, k in valid})
+        index = {r: n for n, r in enumerate(rows)}
+        slot_row = [[index[(dest(i, k), i)] if dest(i, k) >= 0 else -1 for k in range(K)] for i in range(rows_n)]
+        slot_keep = [[int(dest(i, k) >= 0 and k == min(k1 for k1 in range(K) if dest(i, k1) == dest(i, k)))
+                      for k in range(K)] for i in range(rows_n)]
+        dest_count = [len({i for i, k in valid if dest(i, k) == j}) for j in range(num_dest)]
+    else:
+        rows = sorted((dest(i, k), i, k) for i, k in valid)
+        index = {r: n for n, r in enumerate(rows)}
+        slot_row = [[index[(dest(i, k), i, k)] if dest(i, k) >= 0 else -1 for k in range(K)] for i in range(rows_n)]
+        slot_keep = [[int(dest(i, k) >= 0) for k in range(K)] for i in range(rows_n)]
+        dest_count = [sum(1 for i, k in valid if dest(i, k) == j) for j in range(num_dest)]
+    row_weight = []
+    for n, r in enumerate(rows):
+        acc = None
+        for k in range(K):
+            if slot_row[r[1]][k] == n:
+                acc = np.float32(w[r[1], k]) if acc is None else np.float32(acc + np.float32(w[r[1], k]))
+        row_weight.append(acc)
+    mask = [0] * rows_n
+    for i, k in valid:
+        mask[i] |= 1 << dest(i, k)
+    return dict(dest_count=dest_count, row_token=[r[1] for r in rows], slot_row=slot_row, slot_keep=slot_keep,
+                row_weight=row_weight, dest_mask=mask)
