@@ -159,6 +159,57 @@ hm_status hm_expert_load(const int32_t *topk_ids, const int32_t *expert_to_rank,
                          hm_topology topo, int32_t *load_expert, int32_t *load_rank, int32_t *load_node,
                          int32_t *status, void *hip_stream);
 
+/*
+ * ---- Receiver side of the two-hop exchange (HD2: an Inter-node AlltoAll, then an Intra-node
+ * AlltoAll, duplicates removed in both dimensions, Section III-A; the tokens a rank received
+ * become the input of the next level, Alg.1's process()) -------------------------------------
+ * A received row travels with the top-K expert ids and router weights of the token behind it
+ * (pack them with hm_dispatch_pack like any other row: it copies bytes, H counts 2-byte units).
+ * From hop to hop only the expert -> destination table changes.
+ */
+typedef enum {
+  HM_RECV_INTRA_NODE = 0,   /* destinations: the ranks of my node (0..ranks_per_node-1)            */
+  HM_RECV_LOCAL_EXPERTS = 1 /* destinations: the experts placed on my rank, ascending expert id    */
+} hm_recv_stage;
+
+/*
+ * hm_recv_dest_map -- fills dest_map[E] (device) with the destination of every expert as seen from
+ * `my_rank` at `stage`: INTRA_NODE: rank index inside my node for experts on my node, -1 for experts
+ * on other nodes (their copies went elsewhere; the G-group mask of Eq.(7) restricted to my node's
+ * contiguous groups).  LOCAL_EXPERTS: 0,1,2.. in ascending expert id for experts on my rank, else -1.
+ * Placement entries outside [0,G) become -2.  num_dest (device int32[1]) receives ranks_per_node,
+ * respectively the number of experts on my rank.  One small launch; call it when the placement
+ * changes, not per layer.
+ */
+hm_status hm_recv_dest_map(const int32_t *expert_to_rank, int32_t E, hm_topology topo, int32_t my_rank,
+                           hm_recv_stage stage, int32_t *dest_map, int32_t *num_dest, void *hip_stream);
+
+/*
+ * hm_plan_mapped -- hm_plan for an arbitrary expert -> destination table (device int32[E]):
+ * dest_map[e] in [0,num_dest) is a destination, -1 means no copy at this hop (slot skipped without
+ * error: slot_row = -1, slot_keep = 0), anything else -- or an id outside [0,E) -- is invalid
+ * (skipped, HM_ERR_BAD_ID).  dedup != 0 keeps one row per (row, destination), the OR of Eq.(7);
+ * dedup == 0 gives every valid slot a row of its own.  `rows` tokens (received rows) of K slots
+ * each; num_dest <= 64.  Fills *out as hm_plan does; out->rank_mask, if given, receives the
+ * per-row destination mask and out->node_mask zeros.  Workspace: hm_plan_mapped_workspace_bytes.
+ */
+size_t hm_plan_mapped_workspace_bytes(int32_t rows, int32_t K, int32_t num_dest);
+hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_weights, const int32_t *dest_map, int32_t rows,
+                         int32_t K, int32_t E, int32_t num_dest, int32_t dedup, hm_plan_out *out /* host struct */,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * hm_combine_mix -- the merge a receiving rank does before it returns results one hop back: the
+ * row it returns for a received token is the weight-normalised mixture of what came back for
+ * that token's slots,
+ *     out[i,:] = bf16( (sum_k w[i,k] * y[slot_row[i,k], :]) / (sum_k w[i,k]) ),   valid slots only,
+ * fp32 accumulation and one fp32 division.  With these mixtures as the packed-layout y of the
+ * previous hop, hm_combine at the source yields sum_k w_k f_k(x) (Section II-A).  A row without
+ * a valid slot gives zeros.  Arguments as hm_combine (T = number of received rows).
+ */
+hm_status hm_combine_mix(const void *y_bf16, int64_t y_rows, const float *row_weights, int32_t T, int32_t K,
+                         int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char *hm_status_string(hm_status s);
 

@@ -15,6 +15,7 @@ from typing import Optional
 import torch  # must be imported before the library so both share one HIP runtime
 
 HM_DEDUP_NONE, HM_DEDUP_GPU, HM_DEDUP_NODE = 0, 1, 2
+HM_RECV_INTRA_NODE, HM_RECV_LOCAL_EXPERTS = 0, 1
 HM_OK = 0
 HM_ERR_NULL, HM_ERR_SHAPE, HM_ERR_TOPOLOGY, HM_ERR_LEVEL = -1, -2, -3, -4
 HM_ERR_WORKSPACE, HM_ERR_CAPACITY, HM_ERR_BAD_ID, HM_ERR_HIP = -5, -6, -7, -8
@@ -22,7 +23,8 @@ HM_ERR_WORKSPACE, HM_ERR_CAPACITY, HM_ERR_BAD_ID, HM_ERR_HIP = -5, -6, -7, -8
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhiermoe.so")
 
 EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_pack", "hm_combine",
-           "hm_combine_transpose", "hm_expert_load", "hm_status_string")
+           "hm_combine_transpose", "hm_expert_load", "hm_status_string", "hm_recv_dest_map",
+           "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix")
 
 
 class hm_topology(ctypes.Structure):
@@ -71,6 +73,15 @@ def lib():
         L.hm_combine_transpose.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
         L.hm_expert_load.restype = ctypes.c_int
         L.hm_expert_load.argtypes = [vp, vp, i32, i32, i32, hm_topology, vp, vp, vp, vp, vp]
+        L.hm_recv_dest_map.restype = ctypes.c_int
+        L.hm_recv_dest_map.argtypes = [vp, i32, hm_topology, i32, ctypes.c_int, vp, vp, vp]
+        L.hm_plan_mapped_workspace_bytes.restype = ctypes.c_size_t
+        L.hm_plan_mapped_workspace_bytes.argtypes = [i32, i32, i32]
+        L.hm_plan_mapped.restype = ctypes.c_int
+        L.hm_plan_mapped.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp,
+                                     ctypes.c_size_t, vp]
+        L.hm_combine_mix.restype = ctypes.c_int
+        L.hm_combine_mix.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
         L.hm_status_string.restype = ctypes.c_char_p
         L.hm_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -132,14 +143,18 @@ def hm_plan_workspace_bytes(T: int, K: int, E: int, nodes: int, ranks_per_node: 
 
 
 def alloc_plan(T: int, K: int, E: int, nodes: int, ranks_per_node: int, level: int, device="cuda",
-               row_capacity: Optional[int] = None, masks: bool = True) -> Plan:
-    """Allocate (uninitialised) plan buffers; row_capacity defaults to the worst case."""
+               row_capacity: Optional[int] = None, masks: bool = True, num_dest: Optional[int] = None) -> Plan:
+    """Allocate (uninitialised) plan buffers; row_capacity defaults to the worst case.  With
+    num_dest given the buffers are sized for hm_plan_mapped (level none = no dedup)."""
     G = nodes * ranks_per_node
-    Dn = nodes if level == HM_DEDUP_NODE else G
+    Dn = num_dest if num_dest is not None else (nodes if level == HM_DEDUP_NODE else G)
     if row_capacity is None:
         row_capacity = T * (K if level == HM_DEDUP_NONE else min(K, Dn))
     e = lambda n, dt: torch.empty(max(int(n), 1), dtype=dt, device=device)
-    ws_bytes = hm_plan_workspace_bytes(T, K, E, nodes, ranks_per_node, level)
+    if num_dest is not None:
+        ws_bytes = int(lib().hm_plan_mapped_workspace_bytes(T, K, num_dest))
+    else:
+        ws_bytes = hm_plan_workspace_bytes(T, K, E, nodes, ranks_per_node, level)
     bufs = dict(dest_count=e(Dn, torch.int32), dest_offset=e(Dn + 1, torch.int32),
                 row_token=e(row_capacity, torch.int32), slot_row=e(T * K, torch.int32),
                 slot_keep=e(T * K, torch.uint8), row_weight=e(row_capacity, torch.float32),
@@ -213,3 +228,37 @@ def hm_expert_load(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, nodes: 
                               _dev(status, torch.int32, "status"), _stream(stream))
     _check("hm_expert_load", rc)
     return load_expert, load_rank, load_node
+
+
+def hm_recv_dest_map(expert_to_rank: torch.Tensor, nodes: int, ranks_per_node: int, my_rank: int, stage: int,
+                     dest_map: torch.Tensor, num_dest: torch.Tensor, stream=None):
+    E = expert_to_rank.shape[0]
+    rc = lib().hm_recv_dest_map(_dev(expert_to_rank, torch.int32, "expert_to_rank"), E,
+                                hm_topology(nodes, ranks_per_node), my_rank, stage,
+                                _dev(dest_map, torch.int32, "dest_map"), _dev(num_dest, torch.int32, "num_dest"),
+                                _stream(stream))
+    _check("hm_recv_dest_map", rc)
+    return dest_map, num_dest
+
+
+def hm_plan_mapped(row_ids: torch.Tensor, row_weights: torch.Tensor, dest_map: torch.Tensor, num_dest: int,
+                   dedup: bool, plan: Optional[Plan] = None, stream=None) -> Plan:
+    rows, K = row_ids.shape
+    E = dest_map.shape[0]
+    if plan is None:
+        plan = alloc_plan(rows, K, E, 1, 1, HM_DEDUP_GPU if dedup else HM_DEDUP_NONE, device=dest_map.device,
+                          num_dest=num_dest)
+    rc = lib().hm_plan_mapped(_dev(row_ids, torch.int32, "row_ids"), _dev(row_weights, torch.float32, "row_weights"),
+                              _dev(dest_map, torch.int32, "dest_map"), rows, K, E, num_dest, 1 if dedup else 0,
+                              plan.ref(), plan.workspace.data_ptr(), plan.workspace.numel() * 4, _stream(stream))
+    _check("hm_plan_mapped", rc)
+    plan.num_dest = int(plan.c.num_dest)
+    return plan
+
+
+def hm_combine_mix(y: torch.Tensor, row_weights: torch.Tensor, plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
+    T, H = out.shape
+    rc = lib().hm_combine_mix(_dev(y, torch.bfloat16, "y"), y.shape[0], _dev(row_weights, torch.float32, "row_weights"),
+                              T, plan.K, H, plan.ref(), _dev(out, torch.bfloat16, "out"), _stream(stream))
+    _check("hm_combine_mix", rc)
+    return out

@@ -25,6 +25,7 @@ struct PlanParams {
   const int32_t *ids;
   const float *weights;
   const int32_t *expert_to_rank;
+  const int32_t *dest_map;  // non-null: destinations come from this table (hm_plan_mapped)
   int32_t T, K, E, G, R, Dn, level;
   int32_t nslots, nblocks;
   int64_t row_capacity;
@@ -42,8 +43,8 @@ struct Slot {
   bool live;   // inside the table
   int t, k;    // token and position in the token
   int tok0;    // LDS index of the token's slot 0
-  int rank;    // -1: invalid expert id or placement entry
-  int dest;    // destination at the chosen level, -1 if invalid
+  int rank;    // -1: invalid expert id or table entry; -2: valid, but no copy at this hop
+  int dest;    // destination at the chosen level, -1 if there is none
   bool keep;   // owns the row of (token, dest)
 };
 
@@ -58,8 +59,17 @@ __device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *
     const int64_t s = first - halo + i;
     int r = -1, d = -1;
     if (s >= 0 && s < p.nslots) {
-      r = rank_of(p.expert_to_rank, p.E, p.G, p.ids[s]);
-      if (r >= 0) d = p.level == HM_DEDUP_NODE ? r / p.R : r;
+      if (p.dest_map) {
+        const int id = p.ids[s];
+        if ((unsigned)id < (unsigned)p.E) {
+          const int v = p.dest_map[id];
+          if (v >= 0 && v < p.Dn) r = d = v;
+          else if (v == -1) r = -2;
+        }
+      } else {
+        r = rank_of(p.expert_to_rank, p.E, p.G, p.ids[s]);
+        if (r >= 0) d = p.level == HM_DEDUP_NODE ? r / p.R : r;
+      }
     }
     s_rank[i] = (int8_t)r;
     s_dest[i] = (int8_t)d;
@@ -170,10 +180,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
 
   if (!me.live) return;
   const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
-  if (me.rank < 0) {
+  if (me.dest < 0) {
     p.slot_row[s] = -1;
     p.slot_keep[s] = 0;
-    flag(p.status, HM_ERR_BAD_ID);
+    if (me.rank == -1) flag(p.status, HM_ERR_BAD_ID);
   } else if (!me.keep) {
     p.slot_keep[s] = 0;  // its slot_row is written by the slot that owns the row
   } else {
@@ -206,12 +216,55 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
       const int r2 = s_rank[me.tok0 + k2];
       if (r2 >= 0) {
         rm |= 1ull << r2;
-        nm |= 1u << (r2 / p.R);
+        if (!p.dest_map) nm |= 1u << (r2 / p.R);
       }
     }
     if (p.rank_mask) p.rank_mask[me.t] = rm;
     if (p.node_mask) p.node_mask[me.t] = nm;
   }
+}
+
+// Destination table of a receiver stage: one workgroup walks the E experts in chunks of 1024 and
+// numbers the experts placed on `my_rank` with a ballot scan, so local indices ascend with the
+// expert id.
+__global__ __launch_bounds__(kPlanThreads) void recv_dest_map_kernel(const int32_t *__restrict__ expert_to_rank, int E,
+                                                                      int G, int R, int my_rank, int stage,
+                                                                      int32_t *__restrict__ dest_map,
+                                                                      int32_t *__restrict__ num_dest) {
+  __shared__ int32_t wave_cnt[kPlanWaves];
+  __shared__ int32_t base;
+  const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (int e0 = 0; e0 < E; e0 += kPlanThreads) {
+    const int e = e0 + (int)threadIdx.x;
+    int g = -1;
+    if (e < E) {
+      g = expert_to_rank[e];
+      if ((unsigned)g >= (unsigned)G) g = -2;
+    }
+    const bool mine = g == my_rank;
+    const uint64_t b = __ballot(mine);
+    if (lane == 0) wave_cnt[wv] = __popcll(b);
+    __syncthreads();
+    int before = base;
+    for (int w = 0; w < wv; ++w) before += wave_cnt[w];
+    if (e < E) {
+      int v;
+      if (g == -2) v = -2;
+      else if (stage == HM_RECV_INTRA_NODE) v = (g / R == my_rank / R) ? g % R : -1;
+      else v = mine ? before + __popcll(b & ((1ull << lane) - 1ull)) : -1;
+      dest_map[e] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int tot = 0;
+      for (int w = 0; w < kPlanWaves; ++w) tot += wave_cnt[w];
+      base += tot;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *num_dest = stage == HM_RECV_INTRA_NODE ? R : base;
 }
 
 static inline int32_t plan_blocks(int64_t nslots) {
@@ -248,6 +301,7 @@ extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights,
   p.ids = topk_ids;
   p.weights = topk_weights;
   p.expert_to_rank = expert_to_rank;
+  p.dest_map = nullptr;
   p.T = T;
   p.K = K;
   p.E = E;
@@ -274,6 +328,73 @@ extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights,
   hipLaunchKernelGGL(hm::plan_count_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
   if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   hipLaunchKernelGGL(hm::plan_write_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
+  return hm_launch_status();
+}
+
+extern "C" size_t hm_plan_mapped_workspace_bytes(int32_t rows, int32_t K, int32_t num_dest) {
+  if (hm_check_tk(rows, K) != HM_OK || num_dest < 1 || num_dest > 64) return 0;
+  return (size_t)hm::plan_blocks((int64_t)rows * K) * (size_t)num_dest * sizeof(int32_t);
+}
+
+extern "C" hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_weights, const int32_t *dest_map,
+                                    int32_t rows, int32_t K, int32_t E, int32_t num_dest, int32_t dedup, hm_plan_out *out,
+                                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+  if (!out || !dest_map || !workspace) return HM_ERR_NULL;
+  if (!out->dest_count || !out->dest_offset || !out->row_token || !out->slot_row || !out->slot_keep ||
+      !out->row_weight || !out->status)
+    return HM_ERR_NULL;
+  hm_status st = hm_check_tk(rows, K);
+  if (st != HM_OK) return st;
+  if (E < 1 || out->row_capacity < 0) return HM_ERR_SHAPE;
+  if (num_dest < 1 || num_dest > 64) return HM_ERR_TOPOLOGY;
+  if (rows > 0 && (!row_ids || !row_weights)) return HM_ERR_NULL;
+  if (workspace_bytes < hm_plan_mapped_workspace_bytes(rows, K, num_dest)) return HM_ERR_WORKSPACE;
+
+  hm::PlanParams p;
+  p.ids = row_ids;
+  p.weights = row_weights;
+  p.expert_to_rank = nullptr;
+  p.dest_map = dest_map;
+  p.T = rows;
+  p.K = K;
+  p.E = E;
+  p.R = 1;
+  p.G = num_dest;
+  p.Dn = num_dest;
+  p.level = dedup ? (int32_t)HM_DEDUP_GPU : (int32_t)HM_DEDUP_NONE;
+  p.nslots = (int32_t)((int64_t)rows * K);
+  p.nblocks = hm::plan_blocks(p.nslots);
+  p.row_capacity = out->row_capacity;
+  p.counts = (int32_t *)workspace;
+  p.dest_count = out->dest_count;
+  p.dest_offset = out->dest_offset;
+  p.row_token = out->row_token;
+  p.slot_row = out->slot_row;
+  p.slot_keep = out->slot_keep;
+  p.row_weight = out->row_weight;
+  p.rank_mask = out->rank_mask;
+  p.node_mask = out->node_mask;
+  p.status = out->status;
+  out->num_dest = num_dest;
+
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(hm::plan_count_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
+  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  hipLaunchKernelGGL(hm::plan_write_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
+  return hm_launch_status();
+}
+
+extern "C" hm_status hm_recv_dest_map(const int32_t *expert_to_rank, int32_t E, hm_topology topo, int32_t my_rank,
+                                      hm_recv_stage stage, int32_t *dest_map, int32_t *num_dest, void *hip_stream) {
+  if (!expert_to_rank || !dest_map || !num_dest) return HM_ERR_NULL;
+  if (E < 1) return HM_ERR_SHAPE;
+  hm_status st = hm_check_topology(topo);
+  if (st != HM_OK) return st;
+  const int G = topo.nodes * topo.ranks_per_node;
+  if (my_rank < 0 || my_rank >= G) return HM_ERR_TOPOLOGY;
+  if (stage != HM_RECV_INTRA_NODE && stage != HM_RECV_LOCAL_EXPERTS) return HM_ERR_LEVEL;
+  hipLaunchKernelGGL(hm::recv_dest_map_kernel, dim3(1), dim3(hm::kPlanThreads), 0, (hipStream_t)hip_stream,
+                     expert_to_rank, E, G, topo.ranks_per_node, my_rank, (int)stage, dest_map, num_dest);
   return hm_launch_status();
 }
 

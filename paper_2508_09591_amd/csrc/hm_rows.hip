@@ -112,6 +112,9 @@ __device__ __forceinline__ uint64_t merge_slots(int K, int my_row, float my_w, f
   return __ballot(first);
 }
 
+// MIX = false: hm_combine.  MIX = true: hm_combine_mix, the sum divided by the sum of the merged
+// weights (added in ascending k of each row's first slot), zero for a row without a valid slot.
+template <bool MIX>
 __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
                                                                        int64_t y_rows, const float *__restrict__ topk_weights,
                                                                        u32x4 *__restrict__ out) {
@@ -134,6 +137,9 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
   }
   float agg;
   uint64_t todo = merge_slots(p.K, my_row, my_w, agg);
+  float wsum = 0.0f;
+  if (MIX)
+    for (uint64_t m = todo; m; m &= m - 1) wsum = wsum + read_lane(agg, __builtin_ctzll(m));
 
   constexpr int U = kCombineVecs, R = kCombineRows;
   const int v0 = seg * (kWave * U) + lane;   // this lane's vectors: v0, v0+64, ...
@@ -182,6 +188,10 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
 #pragma unroll
   for (int i = 0; i < U; ++i) {
     if (v0 + i * kWave < p.nvec) {
+      if (MIX) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[i][e] = wsum != 0.0f ? acc[i][e] / wsum : 0.0f;
+      }
       u32x4 o;
 #pragma unroll
       for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[i][2 * e], acc[i][2 * e + 1]);
@@ -192,6 +202,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
 
 // Any H / alignment: one thread per (token, element); same merge order and the same fma chain
 // as the vector kernel, so both give identical bits.
+template <bool MIX>
 __global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ y,
                                                                     int64_t y_rows, const float *__restrict__ topk_weights,
                                                                     uint16_t *__restrict__ out) {
@@ -200,7 +211,7 @@ __global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p
   const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
   const int32_t *rows = p.slot_row + (int64_t)t * p.K;
   const float *w = topk_weights + (int64_t)t * p.K;
-  float acc = 0.0f;
+  float acc = 0.0f, wsum = 0.0f;
   for (int k = 0; k < p.K; ++k) {
     const int row = rows[k];
     if (row < 0) continue;
@@ -216,7 +227,9 @@ __global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p
       if (rows[k1] == row) agg = agg + w[k1];
     const float yv = __builtin_bit_cast(float, (uint32_t)y[(int64_t)row * H + j] << 16);
     acc = __builtin_fmaf(agg, yv, acc);
+    wsum = wsum + agg;
   }
+  if (MIX) acc = wsum != 0.0f ? acc / wsum : 0.0f;
   out[i] = (uint16_t)f32_to_bf16(acc);
 }
 
@@ -344,7 +357,8 @@ extern "C" hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, 
   return hm_launch_status();
 }
 
-extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
+template <bool MIX>
+static hm_status launch_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
                                 int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
   using namespace hm;
   hm_status st = check_rows_args(T, K, H, plan, false);
@@ -362,14 +376,24 @@ extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float 
   dim3 grid;
   if (H % 8 == 0 && aligned16(y_bf16) && aligned16(out_bf16)) {
     if (!grid_for_units(p, H / 8, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(combine_rows_kernel, grid, dim3(kCombineThreads), 0, stream, p, (const u32x4 *)y_bf16, y_rows,
-                       topk_weights, (u32x4 *)out_bf16);
+    hipLaunchKernelGGL((combine_rows_kernel<MIX>), grid, dim3(kCombineThreads), 0, stream, p, (const u32x4 *)y_bf16,
+                       y_rows, topk_weights, (u32x4 *)out_bf16);
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(combine_elems_kernel, grid, dim3(kElemThreads), 0, stream, p, H, (const uint16_t *)y_bf16, y_rows,
-                       topk_weights, (uint16_t *)out_bf16);
+    hipLaunchKernelGGL((combine_elems_kernel<MIX>), grid, dim3(kElemThreads), 0, stream, p, H, (const uint16_t *)y_bf16,
+                       y_rows, topk_weights, (uint16_t *)out_bf16);
   }
   return hm_launch_status();
+}
+
+extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
+                                int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
+  return launch_combine<false>(y_bf16, y_rows, topk_weights, T, K, H, plan, out_bf16, hip_stream);
+}
+
+extern "C" hm_status hm_combine_mix(const void *y_bf16, int64_t y_rows, const float *row_weights, int32_t T, int32_t K,
+                                    int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
+  return launch_combine<true>(y_bf16, y_rows, row_weights, T, K, H, plan, out_bf16, hip_stream);
 }
 
 extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,

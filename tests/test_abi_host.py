@@ -100,6 +100,26 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_expert_load(fake, fake, 4, 99, 8, topo, fake, fake, fake, None, None) == B.HM_ERR_SHAPE
     assert L.hm_plan_status(None, None, None) == B.HM_ERR_NULL
 
+    # receiver-side entry points
+    assert L.hm_recv_dest_map(None, 8, topo, 0, 0, fake, fake, None) == B.HM_ERR_NULL
+    assert L.hm_recv_dest_map(fake, 0, topo, 0, 0, fake, fake, None) == B.HM_ERR_SHAPE
+    assert L.hm_recv_dest_map(fake, 8, topo, 4, 0, fake, fake, None) == B.HM_ERR_TOPOLOGY     # rank 4 of 4
+    assert L.hm_recv_dest_map(fake, 8, topo, 0, 2, fake, fake, None) == B.HM_ERR_LEVEL
+    assert L.hm_plan_mapped_workspace_bytes(8192, 8, 8) == 64 * 8 * 4
+    assert L.hm_plan_mapped_workspace_bytes(8192, 8, 65) == 0
+
+    def mapped(ids=fake, w=fake, dm=fake, rows=4, K=2, E=8, nd=4, out=ref, ws=fake, ws_bytes=1 << 20):
+        return L.hm_plan_mapped(ids, w, dm, rows, K, E, nd, 1, out, ws, ws_bytes, None)
+
+    assert mapped(dm=None) == B.HM_ERR_NULL
+    assert mapped(ids=None) == B.HM_ERR_NULL
+    assert mapped(rows=-2) == B.HM_ERR_SHAPE
+    assert mapped(nd=0) == B.HM_ERR_TOPOLOGY
+    assert mapped(nd=65) == B.HM_ERR_TOPOLOGY
+    assert mapped(ws_bytes=4) == B.HM_ERR_WORKSPACE
+    assert L.hm_combine_mix(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
+    assert L.hm_combine_mix(fake, -1, fake, 4, 2, 64, ref, fake, None) == B.HM_ERR_SHAPE
+
 
 def test_binding_refuses_cpu_tensors(B):
     import torch
