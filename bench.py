@@ -55,6 +55,8 @@ def main() -> int:
     ap.add_argument("--warm-y", action="store_true",
                     help="combine reads the buffer dispatch wrote in the same step (partly cache-resident) instead of "
                          "an identical one written sets/2 steps earlier")
+    ap.add_argument("--path", default="send", choices=["send", "recv"],
+                    help="send: the headline step (default); recv: the receiver stages of the two-hop exchange")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -76,6 +78,8 @@ def main() -> int:
         return 2
     B.lib()
     torch.cuda.set_device(0)
+    if args.path == "recv":
+        return run_recv(args)
     wl = W.WORKLOADS[args.workload]
     level = LEVELS[args.level] if args.level else wl.levels[0]
     level_name = W.LEVEL_NAMES[level]
@@ -246,6 +250,137 @@ def main() -> int:
                  "tokens_per_s": round(T / (pair_ms * 1e-3), 1)},
         "plan_ms": round(avg_ms["hm_plan"], 5),
         "expert_load_ms": round(avg_ms["hm_expert_load"], 5),
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def run_recv(args) -> int:
+    """Receiver stages of the two-hop exchange (HD2) at the workload's shape, on the rank with local
+    index 0 of node 1.  Set-up (untimed) runs the sender path for the 32 source ranks that feed that
+    node, so the receiver's inputs have the real size and routing mix:
+      stage A (intra-node hop):  hm_plan_mapped(dedup per local rank) + hm_dispatch_pack, and on the
+                                 way back hm_combine_mix;
+      stage B (local experts):   hm_plan_mapped(one row per slot, expert-contiguous) +
+                                 hm_dispatch_pack, and hm_combine_mix after the experts.
+    Row contents are random bf16 (they do not affect timing); ids and weights are the real ones."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2508_09591_amd import binding as B
+    from paper_2508_09591_amd import workloads as W
+
+    wl = W.WORKLOADS[args.workload]
+    T, K, H, E, R, N = wl.T, wl.K, wl.H, wl.E, wl.ranks_per_node, wl.nodes
+    node = 1 % N
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    e2r = W.contiguous_placement(E, wl.G)
+    e2r_d = dev(e2r)
+    stream = torch.cuda.Stream()
+
+    def pack_meta(plan, t, rows):                     # ids / weights travel as rows of 2K 2-byte units
+        out = torch.empty((rows, 2 * K), dtype=torch.bfloat16, device="cuda")
+        B.hm_dispatch_pack(t.view(torch.bfloat16).view(-1, 2 * K), plan, out, stream=stream)
+        return out
+
+    t0 = time.time()
+    with torch.cuda.stream(stream):
+        recv_ids, recv_w = [], []                     # per receiver (node, r): rows arriving from the N source nodes
+        for r in range(R):
+            parts_i, parts_w = [], []
+            for n in range(N):
+                rt = W.make_routing(dataclasses.replace(wl, seed=1000 + n * R + r))
+                ids_d, w_d = dev(rt.topk_ids), dev(rt.topk_weights)
+                p1 = B.hm_plan(ids_d, w_d, e2r_d, N, R, B.HM_DEDUP_NODE, stream=stream)
+                st, tot = B.hm_plan_status(p1, stream=stream)
+                assert st == 0
+                off = p1.dest_offset[:N + 1].cpu().numpy()
+                a, b = int(off[node]), int(off[node + 1])
+                parts_i.append(pack_meta(p1, ids_d, tot)[a:b].contiguous().view(torch.int32).view(-1, K))
+                parts_w.append(pack_meta(p1, w_d, tot)[a:b].contiguous().view(torch.float32).view(-1, K))
+            recv_ids.append(torch.cat(parts_i).contiguous())
+            recv_w.append(torch.cat(parts_w).contiguous())
+        # stage A on every receiver of the node (needed to build stage B's input for local rank 0)
+        dmA = torch.empty(E, dtype=torch.int32, device="cuda")
+        ndA = torch.empty(1, dtype=torch.int32, device="cuda")
+        B.hm_recv_dest_map(e2r_d, N, R, node * R, B.HM_RECV_INTRA_NODE, dmA, ndA, stream=stream)
+        b_ids, b_w = [], []
+        planA = None
+        for r in range(R):
+            pa = B.hm_plan_mapped(recv_ids[r], recv_w[r], dmA, R, True, stream=stream)
+            st, tot = B.hm_plan_status(pa, stream=stream)
+            assert st == 0
+            off = pa.dest_offset[:R + 1].cpu().numpy()
+            b_ids.append(pack_meta(pa, recv_ids[r], tot)[int(off[0]):int(off[1])].contiguous().view(torch.int32).view(-1, K))
+            b_w.append(pack_meta(pa, recv_w[r], tot)[int(off[0]):int(off[1])].contiguous().view(torch.float32).view(-1, K))
+            if r == 0:
+                planA, rowsA_out = pa, tot
+        idsA, wA = recv_ids[0], recv_w[0]
+        idsB, wB = torch.cat(b_ids).contiguous(), torch.cat(b_w).contiguous()
+        dmB = torch.empty(E, dtype=torch.int32, device="cuda")
+        ndB = torch.empty(1, dtype=torch.int32, device="cuda")
+        B.hm_recv_dest_map(e2r_d, N, R, node * R, B.HM_RECV_LOCAL_EXPERTS, dmB, ndB, stream=stream)
+        n_local = int(ndB.item())
+        planB = B.hm_plan_mapped(idsB, wB, dmB, n_local, False, stream=stream)
+        st, rowsB_out = B.hm_plan_status(planB, stream=stream)
+        assert st == 0
+    rowsA_in, rowsB_in = idsA.shape[0], idsB.shape[0]
+    log("set-up %.1f s; stage A: %d rows in -> %d rows out (x%.2f); stage B: %d rows in -> %d expert rows (x%.2f, %d local experts)"
+        % (time.time() - t0, rowsA_in, rowsA_out, rowsA_out / rowsA_in, rowsB_in, rowsB_out, rowsB_out / rowsB_in, n_local))
+
+    nsets = max(1, args.sets)
+    mk = lambda rows: [torch.randn((rows, H), dtype=torch.float32, device="cuda").to(torch.bfloat16) for _ in range(nsets)]
+    inA, outA, backA = mk(rowsA_in), mk(rowsA_out), mk(rowsA_in)
+    inB, outB, backB = mk(rowsB_in), mk(rowsB_out), mk(rowsB_in)
+
+    calls = [
+        ("A.hm_plan_mapped", lambda s: B.hm_plan_mapped(idsA, wA, dmA, R, True, plan=planA, stream=stream), 0),
+        ("A.hm_dispatch_pack", lambda s: B.hm_dispatch_pack(inA[s], planA, outA[s], stream=stream), (rowsA_in + rowsA_out) * 2 * H),
+        ("A.hm_combine_mix", lambda s: B.hm_combine_mix(outA[(s + nsets // 2) % nsets], wA, planA, backA[s], stream=stream), (rowsA_in + rowsA_out) * 2 * H),
+        ("B.hm_plan_mapped", lambda s: B.hm_plan_mapped(idsB, wB, dmB, n_local, False, plan=planB, stream=stream), 0),
+        ("B.hm_dispatch_pack", lambda s: B.hm_dispatch_pack(inB[s], planB, outB[s], stream=stream), (rowsB_in + rowsB_out) * 2 * H),
+        ("B.hm_combine_mix", lambda s: B.hm_combine_mix(outB[(s + nsets // 2) % nsets], wB, planB, backB[s], stream=stream), (rowsB_in + rowsB_out) * 2 * H),
+    ]
+
+    def step(i, ev=None):
+        s = i % nsets
+        for j, (_, fn, _) in enumerate(calls):
+            if ev: ev[j].record(stream)
+            fn(s)
+        if ev: ev[len(calls)].record(stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    kern = {}
+    for j, (name, _, nbytes) in enumerate(calls):
+        ms = sum(e[j].elapsed_time(e[j + 1]) for e in events) / args.steps
+        kern[name] = {"avg_ms": round(ms, 5)}
+        if nbytes:
+            gbs = nbytes / (ms * 1e-3) / 1e9
+            kern[name].update({"alg_bytes": int(nbytes), "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4)})
+        log("%-20s %.4f ms %s" % (name, ms, ("%.0f GB/s (%.1f%%)" % (kern[name]["achieved_GBps"], 100 * kern[name]["frac"])) if nbytes else ""))
+    dominant = max((n for n in kern if "frac" in kern[n]), key=lambda n: kern[n]["avg_ms"])
+    ms_per_step = elapsed * 1e3 / args.steps
+    result = {
+        "metric": "HD2 receiver stages (intra-node re-dedup + local-expert expand, forward and normalised merge back): received rows/s",
+        "value": round(rowsA_in / (ms_per_step * 1e-3), 1), "unit": "rows/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s receiver: rank 0 of node %d, %d nodes x %d ranks, H=%d; stage A %d->%d rows, stage B %d->%d rows"
+                               % (wl.name, node, N, R, H, rowsA_in, rowsA_out, rowsB_in, rowsB_out), "buffer_sets": nsets},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": kern[dominant]["achieved_GBps"], "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": kern[dominant]["frac"], "traffic": None},
+        "cpu_baseline": None, "kernels": kern,
     }
     print(json.dumps(result), flush=True)
     return 0

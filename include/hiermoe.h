@@ -203,7 +203,7 @@ hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_weights, const
  * row it returns for a received token is the weight-normalised mixture of what came back for
  * that token's slots,
  *     out[i,:] = bf16( (sum_k w[i,k] * y[slot_row[i,k], :]) / (sum_k w[i,k]) ),   valid slots only,
- * fp32 accumulation and one fp32 division.  With these mixtures as the packed-layout y of the
+ * fp32 accumulation, then a multiply by the fp32 reciprocal of the weight sum.  With these mixtures as the packed-layout y of the
  * previous hop, hm_combine at the source yields sum_k w_k f_k(x) (Section II-A).  A row without
  * a valid slot gives zeros.  Arguments as hm_combine (T = number of received rows).
  */

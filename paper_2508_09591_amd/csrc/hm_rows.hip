@@ -112,8 +112,9 @@ __device__ __forceinline__ uint64_t merge_slots(int K, int my_row, float my_w, f
   return __ballot(first);
 }
 
-// MIX = false: hm_combine.  MIX = true: hm_combine_mix, the sum divided by the sum of the merged
-// weights (added in ascending k of each row's first slot), zero for a row without a valid slot.
+// MIX = false: hm_combine.  MIX = true: hm_combine_mix, the sum times the reciprocal of the sum of
+// the merged weights (added in ascending k of each row's first slot); zero for a row without a
+// valid slot.  (A true division per element made the kernel ALU-bound: 8 divisions per 16 bytes.)
 template <bool MIX>
 __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
                                                                        int64_t y_rows, const float *__restrict__ topk_weights,
@@ -137,9 +138,12 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
   }
   float agg;
   uint64_t todo = merge_slots(p.K, my_row, my_w, agg);
-  float wsum = 0.0f;
-  if (MIX)
+  float inv_wsum = 0.0f;   // MIX: one division per wave, then a multiply per element
+  if (MIX) {
+    float wsum = 0.0f;
     for (uint64_t m = todo; m; m &= m - 1) wsum = wsum + read_lane(agg, __builtin_ctzll(m));
+    inv_wsum = wsum != 0.0f ? 1.0f / wsum : 0.0f;
+  }
 
   constexpr int U = kCombineVecs, R = kCombineRows;
   const int v0 = seg * (kWave * U) + lane;   // this lane's vectors: v0, v0+64, ...
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
     if (v0 + i * kWave < p.nvec) {
       if (MIX) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[i][e] = wsum != 0.0f ? acc[i][e] / wsum : 0.0f;
+        for (int e = 0; e < 8; ++e) acc[i][e] = acc[i][e] * inv_wsum;
       }
       u32x4 o;
 #pragma unroll
@@ -229,7 +233,7 @@ __global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p
     acc = __builtin_fmaf(agg, yv, acc);
     wsum = wsum + agg;
   }
-  if (MIX) acc = wsum != 0.0f ? acc / wsum : 0.0f;
+  if (MIX) acc = acc * (wsum != 0.0f ? 1.0f / wsum : 0.0f);   // same reciprocal-multiply as the vector kernel
   out[i] = (uint16_t)f32_to_bf16(acc);
 }
 
