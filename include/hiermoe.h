@@ -210,6 +210,40 @@ hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_weights, const
 hm_status hm_combine_mix(const void *y_bf16, int64_t y_rows, const float *row_weights, int32_t T, int32_t K,
                          int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream);
 
+/*
+ * ---- Choosing the dimension of the hierarchical exchange (Section III-B/C, Alg.1) -------------
+ *
+ * hm_group_counts -- the duplicate-free counts of Eq.(7) for up to 4 group sizes in one pass over
+ * the routing table: counts[l*64 + j] (device int32[depth*64], entries beyond groups[l] zeroed) =
+ * number of tokens with a valid slot whose rank lies in group j when the G ranks are cut into
+ * groups[l] (host array) contiguous equal groups; groups[l] must divide G <= 64.  groups = {G}
+ * gives p of Eq.(2), groups = {U[i]} gives p^(i,U[i]) on this rank's tokens.  status: optional
+ * device int32[1], cleared, set to HM_ERR_BAD_ID when an invalid slot is met (it is not counted).
+ */
+hm_status hm_group_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                          int32_t G, int32_t depth, const int32_t *groups /* host */, int32_t *counts,
+                          int32_t *status, void *hip_stream);
+
+/*
+ * hm_alltoall_times -- Eq.(1)-(6) on the device (no host round trip: the counts stay where the
+ * plan kernels wrote them).  D <= 4 dimensions, U[0..D-1] (host) the group counts of the Inter-level
+ * AlltoAlls with U[0] = 1, each dividing the next and G.
+ *   p_inter[i*64 + j]  (device) tokens per U[i]-group at the input of Inter-level-i, 1 <= i < D
+ *   p_intra[l*64 + j]  (device) tokens per GPU at the input of Intra-level-l, 0 <= l < D; l = 0 is the
+ *                      one-dimensional exchange (p of Eq.(2))
+ *   alpha/beta_inter[i], alpha/beta_intra[l] (host, D entries each): the linear model of Eq.(1) per
+ *                      kind of AlltoAll; intra index 0 is the standard AlltoAll (as in Eq.(8))
+ *   n_inter(i) = U[i]/U[i-1] * max(p_inter[i]) * M * v      n_intra(l) = G/U[l] * max(p_intra[l]) * M * v
+ *   t_d = sum_{i<d} (alpha_inter[i] + n_inter(i) beta_inter[i]) + alpha_intra[d-1] + n_intra(d-1) beta_intra[d-1]
+ *   d*  = 1 if t_1 < min_{d>1} t_d, else the lowest d > 1 with the smallest t_d
+ * times (device double[4]) receives t_1..t_D, best (device int32[1]) receives d*.  fp64, evaluated
+ * in the order written above without fused multiply-adds.
+ */
+hm_status hm_alltoall_times(int32_t D, const int32_t *U /* host */, int32_t G, double M, double v,
+                            const int32_t *p_inter, const int32_t *p_intra, const double *alpha_inter /* host */,
+                            const double *beta_inter /* host */, const double *alpha_intra /* host */,
+                            const double *beta_intra /* host */, double *times, int32_t *best, void *hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char *hm_status_string(hm_status s);
 

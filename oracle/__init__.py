@@ -246,5 +246,42 @@ def combine_mix(y_bf16: np.ndarray, weights, slot_row) -> np.ndarray:
     return out
 
 
+def group_counts(topk_ids, expert_to_rank, G: int, groups):
+    """counts[l][j]: tokens with a slot in group j when the G ranks are cut into groups[l] groups."""
+    lib = _load()
+    ids = _c(topk_ids, np.int32)
+    e2r = _c(expert_to_rank, np.int32)
+    T, K = ids.shape
+    gr = np.asarray(groups, np.int32)
+    counts = np.zeros((len(gr), 64), np.int32)
+    status = np.zeros(1, np.int32)
+    ids_p = ids if ids.size else np.zeros((1, K), np.int32)
+    rc = lib.hmo_group_counts(_p(ids_p), _p(e2r), ctypes.c_int32(T), ctypes.c_int32(K), ctypes.c_int32(e2r.shape[0]),
+                              ctypes.c_int32(G), ctypes.c_int32(len(gr)), _p(gr), _p(counts), _p(status))
+    if rc != 0:
+        raise ValueError("hmo_group_counts: argument error %d" % rc)
+    return counts, int(status[0])
+
+
+def alltoall_times(U, G: int, M: float, v: float, p_inter, p_intra, alpha_inter, beta_inter, alpha_intra, beta_intra):
+    """(times[D], d*) from Eq.(1)-(6); p_inter / p_intra are int32 [D,64] (see hmo.c)."""
+    lib = _load()
+    U = np.asarray(U, np.int32)
+    D = len(U)
+    pi = _c(p_inter, np.int32).reshape(-1)
+    pa = _c(p_intra, np.int32).reshape(-1)
+    arrs = [np.zeros(4) for _ in range(4)]
+    for a, src in zip(arrs, (alpha_inter, beta_inter, alpha_intra, beta_intra)):
+        a[:len(src)] = src
+    times = np.zeros(4)
+    best = ctypes.c_int32(0)
+    rc = lib.hmo_alltoall_times(ctypes.c_int32(D), _p(U), ctypes.c_int32(G), ctypes.c_double(M), ctypes.c_double(v),
+                                _p(pi), _p(pa), _p(arrs[0]), _p(arrs[1]), _p(arrs[2]), _p(arrs[3]), _p(times),
+                                ctypes.byref(best))
+    if rc != 0:
+        raise ValueError("hmo_alltoall_times: argument error %d" % rc)
+    return times[:D].copy(), int(best.value)
+
+
 def f64_to_bf16(v: float) -> int:
     return int(_load().hmo_f64_to_bf16(float(v)))

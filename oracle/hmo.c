@@ -418,5 +418,92 @@ int hmo_combine_mix(const uint16_t *y, int64_t y_rows, const float *weights, con
     return HMO_OK;
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Choosing the dimension of the hierarchical exchange (Section III-B/C, Eq.(1)-(6), Alg.1).
+ * ------------------------------------------------------------------------------------------------ */
+
+/*
+ * hmo_group_counts -- the duplicate-free counts of Eq.(7) for several group sizes at once:
+ * counts[l*64 + j] = number of tokens with a valid slot whose rank lies in group j when the G
+ * ranks are cut into groups[l] contiguous equal groups (groups[l] must divide G).  groups = {G}
+ * gives p of Eq.(2); groups = {U[i]} gives p^(i,U[i]) on this rank's own tokens.
+ */
+int hmo_group_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                     int32_t G, int32_t depth, const int32_t *groups, int32_t *counts, int32_t *status)
+{
+    if (!topk_ids || !expert_to_rank || !groups || !counts || !status) return HMO_ERR_ARG;
+    if (T < 0 || K <= 0 || E <= 0 || G <= 0 || G > 64 || depth < 1 || depth > 4) return HMO_ERR_ARG;
+    for (int32_t l = 0; l < depth; ++l)
+        if (groups[l] < 1 || groups[l] > G || G % groups[l] != 0) return HMO_ERR_ARG;
+    *status = HMO_OK;
+    for (int32_t i = 0; i < depth * 64; ++i) counts[i] = 0;
+    for (int32_t t = 0; t < T; ++t)
+        for (int32_t l = 0; l < depth; ++l) {
+            int in_group[64] = {0};
+            const int32_t ranks_per_group = G / groups[l];
+            for (int32_t k = 0; k < K; ++k) {
+                const int rank = slot_rank(expert_to_rank, E, G, topk_ids[(size_t)t * K + k]);
+                if (rank < 0) { *status = HMO_BAD_ID; continue; }
+                in_group[rank / ranks_per_group] = 1;
+            }
+            for (int32_t j = 0; j < groups[l]; ++j) counts[l * 64 + j] += in_group[j];
+        }
+    return HMO_OK;
+}
+
+static double max_count(const int32_t *p, int32_t n)
+{
+    int32_t m = 0;
+    for (int32_t j = 0; j < n; ++j)
+        if (p[j] > m) m = p[j];
+    return (double)m;
+}
+
+/*
+ * hmo_alltoall_times -- estimated time of the d-dimensional deduplicated exchange for d = 1..D and
+ * the dimension to use.
+ *   U[0..D-1]      group counts of the Inter-level AlltoAlls, U[0] = 1 (Section III-B)
+ *   p_inter[i*64+j] duplicate-free tokens per U[i]-group at the input of Inter-level-i, 1 <= i < D
+ *   p_intra[l*64+j] duplicate-free tokens per GPU at the input of Intra-level-l, 0 <= l < D
+ *                  (l = 0: the one-dimensional exchange, p of Eq.(2))
+ *   alpha/beta_inter[i], alpha/beta_intra[l]: the linear model of Eq.(1) per kind of AlltoAll;
+ *                  index 0 of the intra arrays is the standard AlltoAll (the convention of Eq.(8))
+ *   n_inter(i) = U[i]/U[i-1] * max(p_inter[i]) * M * v                              Eq.(4)
+ *   n_intra(l) = G/U[l]      * max(p_intra[l]) * M * v                              Eq.(2),(5)
+ *   t_d = sum_{i=1}^{d-1} (alpha_inter[i] + n_inter(i) beta_inter[i])
+ *         + alpha_intra[d-1] + n_intra(d-1) beta_intra[d-1]                         Eq.(1),(3)
+ *   d* = 1 if t_1 < min_{d>1} t_d, else the (lowest) d > 1 with the smallest t_d    Eq.(6)
+ * times[d-1] receives t_d; *best receives d*.
+ */
+int hmo_alltoall_times(int32_t D, const int32_t *U, int32_t G, double M, double v, const int32_t *p_inter,
+                       const int32_t *p_intra, const double *alpha_inter, const double *beta_inter,
+                       const double *alpha_intra, const double *beta_intra, double *times, int32_t *best)
+{
+    if (!U || !p_inter || !p_intra || !alpha_inter || !beta_inter || !alpha_intra || !beta_intra || !times || !best)
+        return HMO_ERR_ARG;
+    if (D < 1 || D > 4 || G < 1 || G > 64 || U[0] != 1) return HMO_ERR_ARG;
+    for (int32_t i = 1; i < D; ++i)
+        if (U[i] < U[i - 1] || U[i] > G || U[i] % U[i - 1] != 0 || G % U[i] != 0) return HMO_ERR_ARG;
+    for (int32_t d = 1; d <= D; ++d) {
+        double t = 0.0;
+        for (int32_t i = 1; i <= d - 1; ++i) {
+            const double n = (double)(U[i] / U[i - 1]) * max_count(p_inter + i * 64, U[i]) * M * v;
+            t = t + (alpha_inter[i] + n * beta_inter[i]);
+        }
+        const double n = (double)(G / U[d - 1]) * max_count(p_intra + (d - 1) * 64, G) * M * v;
+        t = t + (alpha_intra[d - 1] + n * beta_intra[d - 1]);
+        times[d - 1] = t;
+    }
+    int32_t arg = 1;
+    if (D > 1) {
+        arg = 2;
+        for (int32_t d = 3; d <= D; ++d)
+            if (times[d - 1] < times[arg - 1]) arg = d;
+        if (times[0] < times[arg - 1]) arg = 1;
+    }
+    *best = arg;
+    return HMO_OK;
+}
+
 /* Exposed so tests can pin the rounding routine by itself. */
 uint16_t hmo_f64_to_bf16(double v) { return f64_to_bf16_rne(v); }

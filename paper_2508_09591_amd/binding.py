@@ -24,7 +24,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhiermoe
 
 EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_pack", "hm_combine",
            "hm_combine_transpose", "hm_expert_load", "hm_status_string", "hm_recv_dest_map",
-           "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix")
+           "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
+           "hm_alltoall_times")
 
 
 class hm_topology(ctypes.Structure):
@@ -82,6 +83,12 @@ def lib():
                                      ctypes.c_size_t, vp]
         L.hm_combine_mix.restype = ctypes.c_int
         L.hm_combine_mix.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
+        L.hm_group_counts.restype = ctypes.c_int
+        L.hm_group_counts.argtypes = [vp, vp, i32, i32, i32, i32, i32, ctypes.POINTER(i32), vp, vp, vp]
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.hm_alltoall_times.restype = ctypes.c_int
+        L.hm_alltoall_times.argtypes = [i32, ctypes.POINTER(i32), i32, ctypes.c_double, ctypes.c_double, vp, vp,
+                                        dp, dp, dp, dp, vp, vp, vp]
         L.hm_status_string.restype = ctypes.c_char_p
         L.hm_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -262,3 +269,30 @@ def hm_combine_mix(y: torch.Tensor, row_weights: torch.Tensor, plan: Plan, out: 
                               T, plan.K, H, plan.ref(), _dev(out, torch.bfloat16, "out"), _stream(stream))
     _check("hm_combine_mix", rc)
     return out
+
+
+def hm_group_counts(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, G: int, groups, counts: torch.Tensor,
+                    status: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """counts: int32 [len(groups), 64] on the GPU."""
+    T, K = topk_ids.shape
+    E = expert_to_rank.shape[0]
+    arr = (ctypes.c_int32 * len(groups))(*[int(g) for g in groups])
+    rc = lib().hm_group_counts(_dev(topk_ids, torch.int32, "topk_ids"), _dev(expert_to_rank, torch.int32, "expert_to_rank"),
+                               T, K, E, G, len(groups), arr, _dev(counts, torch.int32, "counts"),
+                               _dev(status, torch.int32, "status"), _stream(stream))
+    _check("hm_group_counts", rc)
+    return counts
+
+
+def hm_alltoall_times(U, G: int, M: float, v: float, p_inter: torch.Tensor, p_intra: torch.Tensor, alpha_inter,
+                      beta_inter, alpha_intra, beta_intra, times: torch.Tensor, best: torch.Tensor, stream=None):
+    """times: float64 [4], best: int32 [1] on the GPU; p_inter / p_intra: int32 [D,64] on the GPU."""
+    D = len(U)
+    ua = (ctypes.c_int32 * D)(*[int(u) for u in U])
+    dbl = lambda a: (ctypes.c_double * D)(*[float(x) for x in a])
+    rc = lib().hm_alltoall_times(D, ua, G, float(M), float(v), _dev(p_inter, torch.int32, "p_inter"),
+                                 _dev(p_intra, torch.int32, "p_intra"), dbl(alpha_inter), dbl(beta_inter),
+                                 dbl(alpha_intra), dbl(beta_intra), _dev(times, torch.float64, "times"),
+                                 _dev(best, torch.int32, "best"), _stream(stream))
+    _check("hm_alltoall_times", rc)
+    return times, best

@@ -120,6 +120,19 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_combine_mix(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
     assert L.hm_combine_mix(fake, -1, fake, 4, 2, 64, ref, fake, None) == B.HM_ERR_SHAPE
 
+    # dimension selection
+    i32x = lambda *a: (ctypes.c_int32 * len(a))(*a)
+    dbl = lambda *a: (ctypes.c_double * len(a))(*a)
+    assert L.hm_group_counts(fake, fake, 4, 2, 8, 4, 1, i32x(3), fake, None, None) == B.HM_ERR_TOPOLOGY   # 3 does not divide 4
+    assert L.hm_group_counts(fake, fake, 4, 2, 8, 65, 1, i32x(1), fake, None, None) == B.HM_ERR_TOPOLOGY
+    assert L.hm_group_counts(fake, fake, 4, 2, 8, 4, 5, i32x(1, 1, 1, 1, 1), fake, None, None) == B.HM_ERR_TOPOLOGY
+    assert L.hm_group_counts(fake, None, 4, 2, 8, 4, 1, i32x(4), fake, None, None) == B.HM_ERR_NULL
+    z = dbl(0, 0)
+    assert L.hm_alltoall_times(2, i32x(2, 4), 4, 1.0, 1.0, fake, fake, z, z, z, z, fake, fake, None) == B.HM_ERR_TOPOLOGY
+    assert L.hm_alltoall_times(2, i32x(1, 3), 4, 1.0, 1.0, fake, fake, z, z, z, z, fake, fake, None) == B.HM_ERR_TOPOLOGY
+    assert L.hm_alltoall_times(5, i32x(1, 1, 1, 1, 1), 4, 1.0, 1.0, fake, fake, z, z, z, z, fake, fake, None) == B.HM_ERR_TOPOLOGY
+    assert L.hm_alltoall_times(2, i32x(1, 2), 4, 1.0, 1.0, None, fake, z, z, z, z, fake, fake, None) == B.HM_ERR_NULL
+
 
 def test_binding_refuses_cpu_tensors(B):
     import torch
