@@ -283,5 +283,50 @@ def alltoall_times(U, G: int, M: float, v: float, p_inter, p_intra, alpha_inter,
     return times[:D].copy(), int(best.value)
 
 
+def swap_counts(topk_ids, expert_to_rank, G: int, ng: int, method: str = "incremental"):
+    """(Z[E,E,ng], status): duplicate-free tokens per group after swapping experts r and c.
+    method "naive" recounts every pair from the definition; "incremental" is the paper's update."""
+    lib = _load()
+    ids = _c(topk_ids, np.int32)
+    e2r = _c(expert_to_rank, np.int32)
+    T, K = ids.shape
+    E = e2r.shape[0]
+    Z = np.zeros((E, E, ng), np.int32)
+    status = np.zeros(1, np.int32)
+    ids_p = ids if ids.size else np.zeros((1, K), np.int32)
+    fn = lib.hmo_swap_counts_naive if method == "naive" else lib.hmo_swap_counts_incremental
+    rc = fn(_p(ids_p), _p(e2r), ctypes.c_int32(T), ctypes.c_int32(K), ctypes.c_int32(E), ctypes.c_int32(G),
+            ctypes.c_int32(ng), _p(Z), _p(status))
+    if rc != 0:
+        raise ValueError("hmo_swap_counts: argument error %d" % rc)
+    return Z, int(status[0])
+
+
+def swap_select(U, G: int, M: float, v: float, z_inter, z_intra, scale_inter, scale_intra, alpha_inter, beta_inter,
+                alpha_intra: float, beta_intra: float, gamma: float):
+    """(Q[E,E], (r*,c*), best time) for dimension d = len(U); z_inter[i] is Z of the U[i] cut (None at 0)."""
+    lib = _load()
+    U = np.asarray(U, np.int32)
+    d = len(U)
+    zi = [None if z is None else _c(z, np.int32) for z in z_inter]
+    za = _c(z_intra, np.int32)
+    E = za.shape[0]
+    ptrs = (ctypes.c_void_p * 4)()
+    for i in range(1, d):
+        ptrs[i] = zi[i].ctypes.data
+    pad = lambda a: np.asarray(list(a) + [0.0] * (4 - len(a)), np.float64)
+    si, ai, bi = pad(scale_inter), pad(alpha_inter), pad(beta_inter)
+    Q = np.zeros((E, E), np.float64)
+    best = np.zeros(2, np.int32)
+    bt = ctypes.c_double(0.0)
+    rc = lib.hmo_swap_select(ctypes.c_int32(d), _p(U), ctypes.c_int32(G), ctypes.c_int32(E), ctypes.c_double(M),
+                             ctypes.c_double(v), ptrs, _p(za), _p(si), ctypes.c_double(scale_intra), _p(ai), _p(bi),
+                             ctypes.c_double(alpha_intra), ctypes.c_double(beta_intra), ctypes.c_double(gamma),
+                             _p(Q), _p(best), ctypes.byref(bt))
+    if rc != 0:
+        raise ValueError("hmo_swap_select: argument error %d" % rc)
+    return Q, (int(best[0]), int(best[1])), float(bt.value)
+
+
 def f64_to_bf16(v: float) -> int:
     return int(_load().hmo_f64_to_bf16(float(v)))

@@ -505,5 +505,164 @@ int hmo_alltoall_times(int32_t D, const int32_t *U, int32_t G, double M, double 
     return HMO_OK;
 }
 
+/* ------------------------------------------------------------------------------------------------
+ * Hierarchical expert swap, HierD-ES (Section IV, Eq.(8)-(11)).
+ * ------------------------------------------------------------------------------------------------ */
+
+/* Duplicate-free tokens per group for a placement, ranks cut into ng contiguous groups; slots with
+ * an invalid id or placement entry are ignored.  (Eq.(7) by sets.) */
+static void count_groups(const int32_t *ids, const int32_t *placement, int32_t T, int32_t K, int32_t E, int32_t G,
+                         int32_t ng, int32_t *out)
+{
+    const int32_t per = G / ng;
+    for (int32_t j = 0; j < ng; ++j) out[j] = 0;
+    for (int32_t t = 0; t < T; ++t) {
+        int in_group[64] = {0};
+        for (int32_t k = 0; k < K; ++k) {
+            const int rank = slot_rank(placement, E, G, ids[(size_t)t * K + k]);
+            if (rank >= 0) in_group[rank / per] = 1;
+        }
+        for (int32_t j = 0; j < ng; ++j) out[j] += in_group[j];
+    }
+}
+
+/*
+ * hmo_swap_counts_naive -- the definition of Z (Section IV-A): Z[r][c][j] = duplicate-free number
+ * of tokens assigned to group j after the positions of experts r and c are exchanged, i.e. the
+ * counts of Eq.(7) under the placement with entries r and c swapped.  O(E^2 T K).
+ * A pair in which either expert has no valid placement keeps the unswapped counts, and *status
+ * is set to HMO_BAD_ID (as for any invalid slot).
+ */
+int hmo_swap_counts_naive(const int32_t *ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                          int32_t G, int32_t ng, int32_t *Z, int32_t *status)
+{
+    if (!ids || !expert_to_rank || !Z || !status) return HMO_ERR_ARG;
+    if (T < 0 || K <= 0 || E <= 0 || G <= 0 || G > 64 || ng < 1 || ng > G || G % ng != 0) return HMO_ERR_ARG;
+    *status = HMO_OK;
+    for (size_t s = 0; s < (size_t)T * K; ++s)
+        if (slot_rank(expert_to_rank, E, G, ids[s]) < 0) *status = HMO_BAD_ID;
+    int32_t *placement = (int32_t *)malloc(sizeof(int32_t) * (size_t)E);
+    if (!placement) return HMO_ERR_ARG;
+    for (int32_t r = 0; r < E; ++r)
+        for (int32_t c = 0; c < E; ++c) {
+            for (int32_t e = 0; e < E; ++e) placement[e] = expert_to_rank[e];
+            const int valid_r = expert_to_rank[r] >= 0 && expert_to_rank[r] < G;
+            const int valid_c = expert_to_rank[c] >= 0 && expert_to_rank[c] < G;
+            if (valid_r && valid_c) {
+                placement[r] = expert_to_rank[c];
+                placement[c] = expert_to_rank[r];
+            } else {
+                *status = HMO_BAD_ID;
+            }
+            count_groups(ids, placement, T, K, E, G, ng, Z + ((size_t)r * E + c) * ng);
+        }
+    free(placement);
+    return HMO_OK;
+}
+
+/*
+ * hmo_swap_counts_incremental -- the paper's O(T K E) procedure (Section IV-A, the four cases of
+ * Fig.8): start every Z[r][c][:] from the counts without a swap; then for every token and every
+ * pair (A selected, B not selected) in different groups:
+ *   the group of B gains the token unless the token already selects an expert there (cases 1,2 / 3,4);
+ *   the group of A loses the token if A is its only selected expert there (cases 2,4 / 1,3).
+ * Pairs both selected or both unselected change nothing.  The update goes to Z[A][B] and Z[B][A].
+ */
+int hmo_swap_counts_incremental(const int32_t *ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                                int32_t G, int32_t ng, int32_t *Z, int32_t *status)
+{
+    if (!ids || !expert_to_rank || !Z || !status) return HMO_ERR_ARG;
+    if (T < 0 || K <= 0 || E <= 0 || G <= 0 || G > 64 || ng < 1 || ng > G || G % ng != 0) return HMO_ERR_ARG;
+    *status = HMO_OK;
+    const int32_t per = G / ng;
+    int32_t base[64];
+    count_groups(ids, expert_to_rank, T, K, E, G, ng, base);
+    for (int32_t e = 0; e < E; ++e)
+        if (expert_to_rank[e] < 0 || expert_to_rank[e] >= G) *status = HMO_BAD_ID;
+    for (size_t rc = 0; rc < (size_t)E * E; ++rc)
+        for (int32_t j = 0; j < ng; ++j) Z[rc * ng + j] = base[j];
+    uint8_t *selected = (uint8_t *)malloc((size_t)E);
+    if (!selected) return HMO_ERR_ARG;
+    for (int32_t t = 0; t < T; ++t) {
+        int in_group[64] = {0};                       /* selected experts of the token per group */
+        for (int32_t e = 0; e < E; ++e) selected[e] = 0;
+        for (int32_t k = 0; k < K; ++k) {
+            const int32_t id = ids[(size_t)t * K + k];
+            const int rank = slot_rank(expert_to_rank, E, G, id);
+            if (rank < 0) { *status = HMO_BAD_ID; continue; }
+            if (!selected[id]) { selected[id] = 1; in_group[rank / per] += 1; }
+        }
+        for (int32_t a = 0; a < E; ++a) {
+            if (!selected[a]) continue;
+            const int32_t ga = expert_to_rank[a] / per;
+            for (int32_t b = 0; b < E; ++b) {
+                if (selected[b]) continue;
+                if (expert_to_rank[b] < 0 || expert_to_rank[b] >= G) continue;   /* pair keeps the unswapped counts */
+                const int32_t gb = expert_to_rank[b] / per;
+                if (ga == gb) continue;
+                const int gain = in_group[gb] == 0;   /* B's group had none of the token's experts   */
+                const int loss = in_group[ga] == 1;   /* A was the token's only expert in its group  */
+                int32_t *zab = Z + ((size_t)a * E + b) * ng, *zba = Z + ((size_t)b * E + a) * ng;
+                zab[gb] += gain; zba[gb] += gain;
+                zab[ga] -= loss; zba[ga] -= loss;
+            }
+        }
+    }
+    free(selected);
+    return HMO_OK;
+}
+
+/* Eq.(11): max(x) * (sum_i (x_i/max(x))^gamma)^(1/gamma); the plain maximum for gamma <= 0. */
+static double smooth_max(const int32_t *x, int32_t n, double gamma)
+{
+    const double m = max_count(x, n);
+    if (gamma <= 0.0 || m == 0.0) return m;
+    double sum = 0.0;
+    for (int32_t i = 0; i < n; ++i) sum += pow((double)x[i] / m, gamma);
+    return m * pow(sum, 1.0 / gamma);
+}
+
+/*
+ * hmo_swap_select -- Eq.(8)-(10) for one dimension d: the estimated time of the d-dimensional
+ * exchange after swapping experts r and c, for every pair, and the pair that minimises it.
+ *   z_inter[i] (1 <= i < d): Z of the U[i]-group cut, [E][E][U[i]];  z_intra: Z of the G-group cut.
+ *   scale_inter[i], scale_intra: multipliers on the counts (the fan-in of the level; 1 for own counts)
+ *   N_inter(i)[r,c] = U[i]/U[i-1] * scale_inter[i] * smax(z_inter[i][r,c,:]) * M * v            Eq.(9)
+ *   N_intra[r,c]    = G/U[d-1]    * scale_intra    * smax(z_intra[r,c,:])    * M * v            Eq.(9)
+ *   Q[r,c] = sum_{i<d} (N_inter(i) beta_inter[i] + alpha_inter[i]) + N_intra beta_intra + alpha_intra   Eq.(8)
+ *   (r*,c*) = argmin Q, the first pair in row-major order among equals                          Eq.(10)
+ * smax is the smooth maximum of Eq.(11) with parameter gamma (plain max if gamma <= 0).
+ */
+int hmo_swap_select(int32_t d, const int32_t *U, int32_t G, int32_t E, double M, double v,
+                    const int32_t *const *z_inter, const int32_t *z_intra, const double *scale_inter,
+                    double scale_intra, const double *alpha_inter, const double *beta_inter, double alpha_intra,
+                    double beta_intra, double gamma, double *Q, int32_t *best_pair, double *best_time)
+{
+    if (!U || !z_intra || !Q || !best_pair || !best_time) return HMO_ERR_ARG;
+    if (d < 1 || d > 4 || E < 1 || G < 1 || G > 64 || U[0] != 1) return HMO_ERR_ARG;
+    if (d > 1 && (!z_inter || !scale_inter || !alpha_inter || !beta_inter)) return HMO_ERR_ARG;
+    for (int32_t i = 1; i < d; ++i)
+        if (!z_inter[i] || U[i] < U[i - 1] || U[i] % U[i - 1] != 0 || G % U[i] != 0) return HMO_ERR_ARG;
+    double best = 0.0;
+    int32_t br = -1, bc = -1;
+    for (int32_t r = 0; r < E; ++r)
+        for (int32_t c = 0; c < E; ++c) {
+            const size_t rc = (size_t)r * E + c;
+            double q = 0.0;
+            for (int32_t i = 1; i < d; ++i) {
+                const double n = (double)(U[i] / U[i - 1]) * scale_inter[i] * smooth_max(z_inter[i] + rc * U[i], U[i], gamma) * M * v;
+                q = q + (n * beta_inter[i] + alpha_inter[i]);
+            }
+            const double n = (double)(G / U[d - 1]) * scale_intra * smooth_max(z_intra + rc * G, G, gamma) * M * v;
+            q = q + (n * beta_intra + alpha_intra);
+            Q[rc] = q;
+            if (br < 0 || q < best) { best = q; br = r; bc = c; }
+        }
+    best_pair[0] = br;
+    best_pair[1] = bc;
+    *best_time = best;
+    return HMO_OK;
+}
+
 /* Exposed so tests can pin the rounding routine by itself. */
 uint16_t hmo_f64_to_bf16(double v) { return f64_to_bf16_rne(v); }
