@@ -55,8 +55,9 @@ def main() -> int:
     ap.add_argument("--warm-y", action="store_true",
                     help="combine reads the buffer dispatch wrote in the same step (partly cache-resident) instead of "
                          "an identical one written sets/2 steps earlier")
-    ap.add_argument("--path", default="send", choices=["send", "recv"],
-                    help="send: the headline step (default); recv: the receiver stages of the two-hop exchange")
+    ap.add_argument("--path", default="send", choices=["send", "recv", "planner"],
+                    help="send: the headline step (default); recv: the receiver stages of the two-hop exchange; "
+                         "planner: dimension selection + expert-swap planner")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -80,6 +81,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.path == "recv":
         return run_recv(args)
+    if args.path == "planner":
+        return run_planner(args)
     wl = W.WORKLOADS[args.workload]
     level = LEVELS[args.level] if args.level else wl.levels[0]
     level_name = W.LEVEL_NAMES[level]
@@ -382,6 +385,102 @@ def run_recv(args) -> int:
                      "unit": "GB/s", "frac": kern[dominant]["frac"], "traffic": None},
         "cpu_baseline": None, "kernels": kern,
     }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def run_planner(args) -> int:
+    """The per-iteration planner work of Sections III-C and IV on the device: per-level counts,
+    the time model and d*, the swap tensor Z for every level of a 4-level hierarchy, and the
+    selection of the best expert pair (gamma = 10).  Default workload here: skew (config 4)."""
+    import numpy as np
+    import torch
+    from paper_2508_09591_amd import binding as B
+    from paper_2508_09591_amd import workloads as W
+
+    wl = W.WORKLOADS[args.workload if args.workload != "dsv3" or "--workload" in sys.argv else "skew"]
+    r = W.make_routing(wl)
+    e2r = r.extras.get("expert_to_rank_swapped", r.expert_to_rank)
+    T, K, E, G, H = wl.T, wl.K, wl.E, wl.G, wl.H
+    U = [1, wl.nodes, wl.nodes * 2, wl.nodes * 4]
+    U = [u for u in U if G % u == 0 and u <= G]
+    D = len(U)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    ids_d, e2r_d = dev(r.topk_ids), dev(e2r)
+    stream = torch.cuda.Stream()
+    ai, bi = [0, 4.97e-1, 3.01e-1, 1.49e-1][:D], [0, 5.29e-7, 1.17e-7, 2.06e-8][:D]     # the paper's Fig.9 fit
+    aa, ba = [7.22e-1, 5.71e-1, 1.14e-1, 2.04e-1][:D], [5.70e-7, 1.27e-7, 2.63e-8, 1.64e-8][:D]
+    own = torch.zeros((D, 64), dtype=torch.int32, device="cuda")
+    times = torch.zeros(4, dtype=torch.float64, device="cuda")
+    best_d = torch.zeros(1, dtype=torch.int32, device="cuda")
+    cuts = sorted(set(U[1:] + [G]))
+    Z = {u: torch.empty((E, E, u), dtype=torch.int32, device="cuda") for u in cuts}
+    ws = {u: torch.empty(int(B.lib().hm_swap_workspace_bytes(E, u)) // 4 + 4, dtype=torch.int32, device="cuda") for u in cuts}
+    Q = torch.empty((E, E), dtype=torch.float64, device="cuda")
+    bp = torch.zeros(2, dtype=torch.int32, device="cuda")
+    bt = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws_sel = torch.empty(int(B.lib().hm_swap_select_workspace_bytes(E)) // 8 + 2, dtype=torch.float64, device="cuda")
+    fan_in = torch.tensor(U, dtype=torch.int32, device="cuda")[:, None]
+    si = [0.0] + [float(U[i - 1]) for i in range(1, D)]
+
+    def step(ev=None):
+        if ev: ev[0].record(stream)
+        B.hm_group_counts(ids_d, e2r_d, G, [G] + U[1:], own, stream=stream)
+        if ev: ev[1].record(stream)
+        with torch.cuda.stream(stream):                 # harness: counts before Intra-level-l = own counts x fan-in
+            p_intra = (own[0:1] * fan_in).contiguous()
+        B.hm_alltoall_times(U, G, H, 2.0, own, p_intra, ai, bi, aa, ba, times, best_d, stream=stream)
+        if ev: ev[2].record(stream)
+        for u in cuts:
+            B.hm_swap_counts(ids_d, e2r_d, G, u, Z[u], workspace=ws[u], stream=stream)
+        if ev: ev[3].record(stream)
+        B.hm_swap_select(U, G, H, 2.0, [None] + [Z[u] for u in U[1:]], Z[G], si, float(U[D - 1]), ai, bi, aa[D - 1],
+                         ba[D - 1], 10.0, Q, bp, bt, workspace=ws_sel, stream=stream)
+        if ev: ev[4].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    names = ["hm_group_counts", "hm_alltoall_times", "hm_swap_counts x%d" % len(cuts), "hm_swap_select"]
+    kern = {n: round(sum(e[j].elapsed_time(e[j + 1]) for e in events) / args.steps, 5) for j, n in enumerate(names)}
+    log("planner on %s (T=%d K=%d E=%d G=%d, U=%s): %.4f ms per step; " % (wl.name, T, K, E, G, U, ms_per_step)
+        + ", ".join("%s %.4f ms" % kv for kv in kern.items()))
+    log("d* = %d, t_d = %s; best swap %s -> %.4f vs %.4f without a swap"
+        % (int(best_d.item()), np.round(times.cpu().numpy()[:D], 4).tolist(), tuple(bp.cpu().numpy().tolist()),
+           float(bt.item()), float(Q[0, 0].item())))
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        t1 = time.perf_counter()
+        oracle.group_counts(r.topk_ids, e2r, G, [G] + U[1:])
+        zs = {u: oracle.swap_counts(r.topk_ids, e2r, G, u, "incremental")[0] for u in cuts}
+        oracle.swap_select(U, G, H, 2.0, [None] + [zs[u] for u in U[1:]], zs[G], si, float(U[D - 1]), ai, bi, aa[D - 1],
+                           ba[D - 1], 10.0)
+        dt = time.perf_counter() - t1
+        cpu = {"value": round(T / dt, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
+               "sample": "the whole %s batch once (incremental Z update for %d cuts + selection), %.2f s" % (wl.name, len(cuts), dt)}
+        log("cpu oracle: %.2f s" % dt)
+    swap_ms = kern[names[2]]
+    # integer work of the factor pass: T*K*(K + ng) table updates per cut, plus E*E*ng outputs
+    updates = sum(T * K * (K + u) + E * E * u for u in cuts)
+    result = {"metric": "planner (counts + d* + swap tensor Z + best pair) tokens/s", "value": round(T / (ms_per_step * 1e-3), 1),
+              "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+              "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+              "config": {"workload": "%s: T=%d K=%d E=%d G=%d, hierarchy U=%s, gamma=10" % (wl.name, T, K, E, G, U)},
+              "roofline": {"bound": "alu", "kernel": "hm_swap_counts", "achieved": round(updates / (swap_ms * 1e-3) / 1e12, 5),
+                           "peak": 157.3 / 2, "unit": "Tupdate/s (int32 add, vs the 78.6 Tadd/s vector rate)",
+                           "frac": round(updates / (swap_ms * 1e-3) / 1e12 / (157.3 / 2), 6), "traffic": None},
+              "cpu_baseline": cpu, "kernels": kern}
     print(json.dumps(result), flush=True)
     return 0
 

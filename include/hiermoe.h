@@ -244,6 +244,46 @@ hm_status hm_alltoall_times(int32_t D, const int32_t *U /* host */, int32_t G, d
                             const double *beta_inter /* host */, const double *alpha_intra /* host */,
                             const double *beta_intra /* host */, double *times, int32_t *best, void *hip_stream);
 
+/*
+ * ---- Hierarchical expert swap, HierD-ES (Section IV) ------------------------------------------
+ *
+ * hm_swap_counts -- the swap tensor of Section IV-A: Z[(r*E + c)*ng + j] (device int32) = the
+ * duplicate-free number of tokens assigned to group j (the G ranks cut into ng contiguous equal
+ * groups) after the positions of experts r and c are exchanged, for every pair.  Computed in
+ * O(T K (K + ng)) from per-expert / per-(expert,group) / per-(expert,expert) co-occurrence counts
+ * instead of the paper's O(T K E) update: only the two groups involved in a swap can change, and
+ * the change is  +#{tokens selecting r, nothing in c's group}  -#{tokens where c is the only
+ * selected expert of its group and r is not selected}  for c's group (and symmetrically).
+ * A pair in which either expert's placement entry is outside [0,G) keeps the unswapped counts;
+ * invalid slots are ignored; both set *status (optional device int32[1]) to HM_ERR_BAD_ID.
+ * workspace: hm_swap_workspace_bytes(E, ng) bytes of device scratch.
+ */
+size_t hm_swap_workspace_bytes(int32_t E, int32_t ng);
+hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                         int32_t G, int32_t ng, int32_t *Z, int32_t *status, void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
+/*
+ * hm_swap_select -- Eq.(8)-(10) for dimension d (1..4): the estimated time Q[r*E + c] (device
+ * double[E*E]) of the d-dimensional exchange after swapping experts r and c, and the pair with
+ * the smallest time (first in row-major order among equals): best_pair (device int32[2]),
+ * best_time (device double[1]).
+ *   z_inter (host array of d device pointers, entry 0 unused): z_inter[i] = Z of the U[i]-group cut;
+ *   z_intra = Z of the G-group cut;  U, scale_inter, alpha_inter, beta_inter: host arrays of d entries.
+ *   N_inter(i) = U[i]/U[i-1] * scale_inter[i] * smax(z_inter[i][r,c,:]) * M * v                Eq.(9)
+ *   N_intra    = G/U[d-1]    * scale_intra    * smax(z_intra[r,c,:])    * M * v                Eq.(9)
+ *   Q = sum_{i<d} (N_inter(i) beta_inter[i] + alpha_inter[i]) + N_intra beta_intra + alpha_intra   Eq.(8)
+ * smax = max(x) * (sum_i (x_i/max(x))^gamma)^(1/gamma), Eq.(11); the plain maximum if gamma <= 0.
+ * workspace: hm_swap_select_workspace_bytes(E) bytes of device scratch.
+ */
+size_t hm_swap_select_workspace_bytes(int32_t E);
+hm_status hm_swap_select(int32_t d, const int32_t *U /* host */, int32_t G, int32_t E, double M, double v,
+                         const int32_t *const *z_inter /* host array of device pointers */, const int32_t *z_intra,
+                         const double *scale_inter /* host */, double scale_intra, const double *alpha_inter /* host */,
+                         const double *beta_inter /* host */, double alpha_intra, double beta_intra, double gamma,
+                         double *Q, int32_t *best_pair, double *best_time, void *workspace, size_t workspace_bytes,
+                         void *hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char *hm_status_string(hm_status s);
 

@@ -25,7 +25,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libhiermoe
 EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_pack", "hm_combine",
            "hm_combine_transpose", "hm_expert_load", "hm_status_string", "hm_recv_dest_map",
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
-           "hm_alltoall_times")
+           "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
+           "hm_swap_select")
 
 
 class hm_topology(ctypes.Structure):
@@ -89,6 +90,16 @@ def lib():
         L.hm_alltoall_times.restype = ctypes.c_int
         L.hm_alltoall_times.argtypes = [i32, ctypes.POINTER(i32), i32, ctypes.c_double, ctypes.c_double, vp, vp,
                                         dp, dp, dp, dp, vp, vp, vp]
+        L.hm_swap_workspace_bytes.restype = ctypes.c_size_t
+        L.hm_swap_workspace_bytes.argtypes = [i32, i32]
+        L.hm_swap_counts.restype = ctypes.c_int
+        L.hm_swap_counts.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.hm_swap_select_workspace_bytes.restype = ctypes.c_size_t
+        L.hm_swap_select_workspace_bytes.argtypes = [i32]
+        L.hm_swap_select.restype = ctypes.c_int
+        L.hm_swap_select.argtypes = [i32, ctypes.POINTER(i32), i32, i32, ctypes.c_double, ctypes.c_double,
+                                     ctypes.POINTER(vp), vp, dp, ctypes.c_double, dp, dp, ctypes.c_double,
+                                     ctypes.c_double, ctypes.c_double, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.hm_status_string.restype = ctypes.c_char_p
         L.hm_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -296,3 +307,41 @@ def hm_alltoall_times(U, G: int, M: float, v: float, p_inter: torch.Tensor, p_in
                                  _dev(best, torch.int32, "best"), _stream(stream))
     _check("hm_alltoall_times", rc)
     return times, best
+
+
+def hm_swap_counts(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, G: int, ng: int, Z: torch.Tensor,
+                   status: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """Z: int32 [E,E,ng] on the GPU."""
+    T, K = topk_ids.shape
+    E = expert_to_rank.shape[0]
+    need = int(lib().hm_swap_workspace_bytes(E, ng))
+    if workspace is None:
+        workspace = torch.empty(need // 4 + 4, dtype=torch.int32, device=Z.device)
+    rc = lib().hm_swap_counts(_dev(topk_ids, torch.int32, "topk_ids"), _dev(expert_to_rank, torch.int32, "expert_to_rank"),
+                              T, K, E, G, ng, _dev(Z, torch.int32, "Z"), _dev(status, torch.int32, "status"),
+                              workspace.data_ptr(), workspace.numel() * 4, _stream(stream))
+    _check("hm_swap_counts", rc)
+    return Z
+
+
+def hm_swap_select(U, G: int, M: float, v: float, z_inter, z_intra: torch.Tensor, scale_inter, scale_intra: float,
+                   alpha_inter, beta_inter, alpha_intra: float, beta_intra: float, gamma: float, Q: torch.Tensor,
+                   best_pair: torch.Tensor, best_time: torch.Tensor, workspace: Optional[torch.Tensor] = None, stream=None):
+    """z_inter: list of d entries (entry 0 None), each an int32 [E,E,U[i]] GPU tensor."""
+    d = len(U)
+    E = z_intra.shape[0]
+    ua = (ctypes.c_int32 * d)(*[int(u) for u in U])
+    ptrs = (ctypes.c_void_p * d)()
+    for i in range(1, d):
+        ptrs[i] = _dev(z_inter[i], torch.int32, "z_inter")
+    dbl = lambda a: (ctypes.c_double * d)(*[float(x) for x in a])
+    need = int(lib().hm_swap_select_workspace_bytes(E))
+    if workspace is None:
+        workspace = torch.empty(need // 8 + 2, dtype=torch.float64, device=Q.device)
+    rc = lib().hm_swap_select(d, ua, G, E, float(M), float(v), ptrs, _dev(z_intra, torch.int32, "z_intra"),
+                              dbl(scale_inter), float(scale_intra), dbl(alpha_inter), dbl(beta_inter), float(alpha_intra),
+                              float(beta_intra), float(gamma), _dev(Q, torch.float64, "Q"),
+                              _dev(best_pair, torch.int32, "best_pair"), _dev(best_time, torch.float64, "best_time"),
+                              workspace.data_ptr(), workspace.numel() * 8, _stream(stream))
+    _check("hm_swap_select", rc)
+    return Q, best_pair, best_time

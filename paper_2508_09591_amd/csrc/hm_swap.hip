@@ -1,0 +1,347 @@
+// Hierarchical expert swap (HierMoE Section IV): the swap tensor Z and the selection of Eq.(8)-(11).
+//
+// Z[r][c][:] is the vector of duplicate-free per-group token counts after experts r and c trade
+// places.  A swap can only change the two groups involved, and by how much follows from three
+// small co-occurrence tables gathered in one pass over the tokens (one lane per token):
+//   L0[a]    tokens selecting a                      CG[a][g]  ... that also select something in g
+//   L[a]     tokens where a is alone in its group    C[a][b]   ... that also select b
+// For g_r != g_c:  Z[r][c][g_c] = base[g_c] + (L0[r] - CG[r][g_c]) - (L[c] - C[c][r])   and the same
+// with r and c exchanged for g_r.  This is O(T K (K + ng)) instead of the O(T K E) walk over all
+// unselected experts, with the per-pair work moved into an embarrassingly parallel E^2 ng kernel.
+#include "hm_device.h"
+
+namespace hm {
+
+constexpr int kSwapThreads = 256;
+constexpr int kSwapLds = 12288;   // ints of LDS for L0 + L + CG (48 KiB)
+constexpr int kSwapCopies = 8;    // private copies of C: popular expert pairs would otherwise serialise on one address
+
+struct SwapParams {
+  const int32_t *ids;
+  const int32_t *expert_to_rank;
+  int32_t T, K, E, G, ng, per;
+  int32_t *base;   // [64]
+  int32_t *L0;     // [E]
+  int32_t *L;      // [E]
+  int32_t *CG;     // [E][ng]
+  int32_t *C;      // [kSwapCopies][E][E]
+  int64_t ws_ints;
+  int32_t *Z;
+  int32_t *status;
+};
+
+__global__ __launch_bounds__(kSwapThreads) void swap_clear_kernel(SwapParams p) {
+  const int64_t i = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
+  if (i < p.ws_ints) p.base[i] = 0;   // the factor tables are contiguous behind base
+  if (i == 0 && p.status) *p.status = 0;
+}
+
+__global__ __launch_bounds__(kSwapThreads) void swap_factors_kernel(SwapParams p) {
+  __shared__ int32_t lds[kSwapLds];
+  __shared__ int32_t base_cnt[kWave];
+  const int small = p.E * (p.ng + 2);
+  const bool use_lds = small <= kSwapLds;
+  int32_t *sL0 = lds, *sL = lds + p.E, *sCG = lds + 2 * p.E;
+  if (use_lds)
+    for (int i = threadIdx.x; i < small; i += kSwapThreads) lds[i] = 0;
+  if (threadIdx.x < kWave) base_cnt[threadIdx.x] = 0;
+  __syncthreads();
+
+  const int lane = lane_id();
+  int my_base = 0;
+  int32_t *myC = p.C + (int64_t)(blockIdx.x % kSwapCopies) * p.E * p.E;
+  const int64_t stride = (int64_t)gridDim.x * kSwapThreads;
+  const int64_t rounds = ((int64_t)p.T + stride - 1) / stride;
+  for (int64_t it = 0; it < rounds; ++it) {
+    const int64_t t = it * stride + (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
+    uint64_t gm = 0;
+    if (t < p.T) {
+      const int32_t *tok = p.ids + t * p.K;
+      // the selected experts form a set: `firsts` marks the first valid occurrence of each
+      uint64_t firsts = 0;
+      for (int k = 0; k < p.K; ++k) {
+        const int a = tok[k];
+        const int g = rank_of(p.expert_to_rank, p.E, p.G, a);
+        if (g < 0) {
+          flag(p.status, HM_ERR_BAD_ID);
+          continue;
+        }
+        gm |= 1ull << (g / p.per);
+        bool repeat = false;
+        for (int k1 = 0; k1 < k; ++k1) repeat = repeat || tok[k1] == a;
+        if (!repeat) firsts |= 1ull << k;
+      }
+      for (uint64_t ma = firsts; ma; ma &= ma - 1) {
+        const int a = tok[__builtin_ctzll(ma)];
+        const int ga = p.expert_to_rank[a] / p.per;
+        int in_ga = 0;   // distinct selected experts in a's group
+        for (uint64_t mb = firsts; mb; mb &= mb - 1)
+          in_ga += (p.expert_to_rank[tok[__builtin_ctzll(mb)]] / p.per == ga) ? 1 : 0;
+        const bool alone = in_ga == 1;
+        if (use_lds) {
+          atomicAdd(&sL0[a], 1);
+          if (alone) atomicAdd(&sL[a], 1);
+          for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&sCG[a * p.ng + __builtin_ctzll(m)], 1);
+        } else {
+          atomicAdd(&p.L0[a], 1);
+          if (alone) atomicAdd(&p.L[a], 1);
+          for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&p.CG[(int64_t)a * p.ng + __builtin_ctzll(m)], 1);
+        }
+        if (alone)
+          for (uint64_t mb = firsts; mb; mb &= mb - 1) {
+            const int b = tok[__builtin_ctzll(mb)];
+            if (b != a) atomicAdd(&myC[(int64_t)a * p.E + b], 1);
+          }
+      }
+    }
+    for (int j = 0; j < p.ng; ++j) {
+      const uint64_t b = __ballot((gm >> j) & 1ull);
+      if (lane == j) my_base += __popcll(b);
+    }
+  }
+  if (lane < p.ng && my_base) atomicAdd(&base_cnt[lane], my_base);
+  __syncthreads();
+  if ((int)threadIdx.x < p.ng && base_cnt[threadIdx.x]) atomicAdd(&p.base[threadIdx.x], base_cnt[threadIdx.x]);
+  if (use_lds) {
+    for (int i = threadIdx.x; i < p.E; i += kSwapThreads) {
+      if (sL0[i]) atomicAdd(&p.L0[i], sL0[i]);
+      if (sL[i]) atomicAdd(&p.L[i], sL[i]);
+    }
+    for (int i = threadIdx.x; i < p.E * p.ng; i += kSwapThreads)
+      if (sCG[i]) atomicAdd(&p.CG[i], sCG[i]);
+  }
+}
+
+// One lane per element of Z.
+__global__ __launch_bounds__(kSwapThreads) void swap_build_kernel(SwapParams p) {
+  const int64_t i = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
+  const int64_t total = (int64_t)p.E * p.E * p.ng;
+  if (i >= total) return;
+  const int j = (int)(i % p.ng);
+  const int64_t rc = i / p.ng;
+  const int r = (int)(rc / p.E), c = (int)(rc % p.E);
+  int val = p.base[j];
+  const int rr = p.expert_to_rank[r], rk = p.expert_to_rank[c];
+  const bool valid = (unsigned)rr < (unsigned)p.G && (unsigned)rk < (unsigned)p.G;
+  if (!valid) {
+    if (j == 0) flag(p.status, HM_ERR_BAD_ID);
+  } else {
+    const int gr = rr / p.per, gc = rk / p.per;
+    if (gr != gc && (j == gc || j == gr)) {
+      const int a = j == gc ? r : c, b = j == gc ? c : r;   // group j gains tokens of a, loses tokens of b
+      int cba = 0;
+      for (int k = 0; k < kSwapCopies; ++k) cba += p.C[((int64_t)k * p.E + b) * p.E + a];
+      val += (p.L0[a] - p.CG[(int64_t)a * p.ng + j]) - (p.L[b] - cba);
+    }
+  }
+  p.Z[i] = val;
+}
+
+// ---------------------------------------------------------------------------------------------
+// selection
+// ---------------------------------------------------------------------------------------------
+constexpr int kMaxDim = 4;
+
+struct SelectParams {
+  int32_t d, G, E;
+  int32_t U[kMaxDim];
+  double M, v, gamma;
+  const int32_t *z_inter[kMaxDim];
+  const int32_t *z_intra;
+  double scale_inter[kMaxDim], alpha_inter[kMaxDim], beta_inter[kMaxDim];
+  double scale_intra, alpha_intra, beta_intra;
+  double *Q;
+  double *block_min;    // workspace [nblocks]
+  int32_t *block_arg;   // workspace [nblocks]
+  int32_t nblocks;
+  int32_t *best_pair;
+  double *best_time;
+};
+
+__device__ __forceinline__ double smooth_max(const int32_t *x, int n, double gamma) {
+  int mi = 0;
+  for (int i = 0; i < n; ++i) mi = max(mi, x[i]);
+  const double m = (double)mi;
+  if (gamma <= 0.0 || m == 0.0) return m;
+  double sum = 0.0;
+  for (int i = 0; i < n; ++i) sum += pow((double)x[i] / m, gamma);
+  return m * pow(sum, 1.0 / gamma);
+}
+
+__global__ __launch_bounds__(kSwapThreads) void swap_q_kernel(SelectParams p) {
+#pragma clang fp contract(off)
+  __shared__ double s_val[kSwapThreads];
+  __shared__ int32_t s_arg[kSwapThreads];
+  const int64_t rc = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
+  const int64_t pairs = (int64_t)p.E * p.E;
+  double q = 0.0;
+  const bool live = rc < pairs;
+  if (live) {
+    for (int i = 1; i < p.d; ++i) {
+      const double n = (double)(p.U[i] / p.U[i - 1]) * p.scale_inter[i] * smooth_max(p.z_inter[i] + rc * p.U[i], p.U[i], p.gamma) * p.M * p.v;
+      q = q + (n * p.beta_inter[i] + p.alpha_inter[i]);
+    }
+    const double n = (double)(p.G / p.U[p.d - 1]) * p.scale_intra * smooth_max(p.z_intra + rc * p.G, p.G, p.gamma) * p.M * p.v;
+    q = q + (n * p.beta_intra + p.alpha_intra);
+    p.Q[rc] = q;
+  }
+  s_val[threadIdx.x] = q;
+  s_arg[threadIdx.x] = live ? (int32_t)rc : -1;
+  __syncthreads();
+  for (int off = kSwapThreads / 2; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      const int o = threadIdx.x + off;
+      const bool take = s_arg[o] >= 0 && (s_arg[threadIdx.x] < 0 || s_val[o] < s_val[threadIdx.x] ||
+                                          (s_val[o] == s_val[threadIdx.x] && s_arg[o] < s_arg[threadIdx.x]));
+      if (take) {   // among equal times the lower pair index survives
+        s_val[threadIdx.x] = s_val[o];
+        s_arg[threadIdx.x] = s_arg[o];
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    p.block_min[blockIdx.x] = s_val[0];
+    p.block_arg[blockIdx.x] = s_arg[0];
+  }
+}
+
+__global__ __launch_bounds__(kSwapThreads) void swap_argmin_kernel(SelectParams p) {
+  __shared__ double s_val[kSwapThreads];
+  __shared__ int32_t s_arg[kSwapThreads];
+  double best = 0.0;
+  int32_t arg = -1;
+  for (int b = threadIdx.x; b < p.nblocks; b += kSwapThreads) {   // ascending blocks: first minimum wins
+    const int32_t a = p.block_arg[b];
+    if (a >= 0 && (arg < 0 || p.block_min[b] < best)) {
+      best = p.block_min[b];
+      arg = a;
+    }
+  }
+  s_val[threadIdx.x] = best;
+  s_arg[threadIdx.x] = arg;
+  __syncthreads();
+  for (int off = kSwapThreads / 2; off > 0; off >>= 1) {
+    if ((int)threadIdx.x < off) {
+      const int o = threadIdx.x + off;
+      const bool better = s_arg[o] >= 0 && (s_arg[threadIdx.x] < 0 || s_val[o] < s_val[threadIdx.x] ||
+                                            (s_val[o] == s_val[threadIdx.x] && s_arg[o] < s_arg[threadIdx.x]));
+      if (better) {
+        s_val[threadIdx.x] = s_val[o];
+        s_arg[threadIdx.x] = s_arg[o];
+      }
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    p.best_pair[0] = s_arg[0] / p.E;
+    p.best_pair[1] = s_arg[0] % p.E;
+    *p.best_time = s_val[0];
+  }
+}
+
+static inline int64_t swap_ws_ints(int64_t E, int64_t ng) { return 64 + 2 * E + E * ng + kSwapCopies * E * E; }
+
+}  // namespace hm
+
+extern "C" size_t hm_swap_workspace_bytes(int32_t E, int32_t ng) {
+  if (E < 1 || ng < 1 || ng > 64) return 0;
+  return (size_t)hm::swap_ws_ints(E, ng) * sizeof(int32_t);
+}
+
+extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
+                                    int32_t E, int32_t G, int32_t ng, int32_t *Z, int32_t *status, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream) {
+  using namespace hm;
+  if (!expert_to_rank || !Z || !workspace) return HM_ERR_NULL;
+  hm_status st = hm_check_tk(T, K);
+  if (st != HM_OK) return st;
+  if (E < 1 || (int64_t)E * E * 64 > 2147483647LL) return HM_ERR_SHAPE;
+  if (T > 0 && !topk_ids) return HM_ERR_NULL;
+  if (G < 1 || G > 64 || ng < 1 || ng > G || G % ng != 0) return HM_ERR_TOPOLOGY;
+  if (workspace_bytes < hm_swap_workspace_bytes(E, ng)) return HM_ERR_WORKSPACE;
+  SwapParams p;
+  p.ids = topk_ids;
+  p.expert_to_rank = expert_to_rank;
+  p.T = T;
+  p.K = K;
+  p.E = E;
+  p.G = G;
+  p.ng = ng;
+  p.per = G / ng;
+  p.base = (int32_t *)workspace;
+  p.L0 = p.base + 64;
+  p.L = p.L0 + E;
+  p.CG = p.L + E;
+  p.C = p.CG + (int64_t)E * ng;
+  p.ws_ints = swap_ws_ints(E, ng);
+  p.Z = Z;
+  p.status = status;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(swap_clear_kernel, dim3((unsigned)((p.ws_ints + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads),
+                     0, stream, p);
+  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  if (T > 0) {
+    int64_t blocks = ((int64_t)T + kSwapThreads - 1) / kSwapThreads;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(swap_factors_kernel, dim3((unsigned)blocks), dim3(kSwapThreads), 0, stream, p);
+    if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  }
+  const int64_t total = (int64_t)E * E * ng;
+  hipLaunchKernelGGL(swap_build_kernel, dim3((unsigned)((total + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads), 0,
+                     stream, p);
+  return hm_launch_status();
+}
+
+extern "C" size_t hm_swap_select_workspace_bytes(int32_t E) {
+  if (E < 1) return 0;
+  const int64_t blocks = ((int64_t)E * E + hm::kSwapThreads - 1) / hm::kSwapThreads;
+  return (size_t)blocks * (sizeof(double) + sizeof(int32_t)) + 16;
+}
+
+extern "C" hm_status hm_swap_select(int32_t d, const int32_t *U, int32_t G, int32_t E, double M, double v,
+                                    const int32_t *const *z_inter, const int32_t *z_intra, const double *scale_inter,
+                                    double scale_intra, const double *alpha_inter, const double *beta_inter,
+                                    double alpha_intra, double beta_intra, double gamma, double *Q, int32_t *best_pair,
+                                    double *best_time, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  using namespace hm;
+  if (!U || !z_intra || !Q || !best_pair || !best_time || !workspace) return HM_ERR_NULL;
+  if (d < 1 || d > kMaxDim || G < 1 || G > 64 || U[0] != 1) return HM_ERR_TOPOLOGY;
+  if (E < 1 || (int64_t)E * E > 2147483647LL) return HM_ERR_SHAPE;
+  if (d > 1 && (!z_inter || !scale_inter || !alpha_inter || !beta_inter)) return HM_ERR_NULL;
+  for (int i = 1; i < d; ++i) {
+    if (!z_inter[i]) return HM_ERR_NULL;
+    if (U[i] < U[i - 1] || U[i] > G || U[i] % U[i - 1] != 0 || G % U[i] != 0) return HM_ERR_TOPOLOGY;
+  }
+  if (workspace_bytes < hm_swap_select_workspace_bytes(E)) return HM_ERR_WORKSPACE;
+  SelectParams p;
+  p.d = d;
+  p.G = G;
+  p.E = E;
+  p.M = M;
+  p.v = v;
+  p.gamma = gamma;
+  for (int i = 0; i < kMaxDim; ++i) {
+    const bool in = i >= 1 && i < d;
+    p.U[i] = i < d ? U[i] : 1;
+    p.z_inter[i] = in ? z_inter[i] : nullptr;
+    p.scale_inter[i] = in ? scale_inter[i] : 0.0;
+    p.alpha_inter[i] = in ? alpha_inter[i] : 0.0;
+    p.beta_inter[i] = in ? beta_inter[i] : 0.0;
+  }
+  p.z_intra = z_intra;
+  p.scale_intra = scale_intra;
+  p.alpha_intra = alpha_intra;
+  p.beta_intra = beta_intra;
+  p.Q = Q;
+  p.nblocks = (int32_t)(((int64_t)E * E + kSwapThreads - 1) / kSwapThreads);
+  p.block_min = (double *)workspace;
+  p.block_arg = (int32_t *)(p.block_min + p.nblocks);
+  p.best_pair = best_pair;
+  p.best_time = best_time;
+  hipStream_t stream = (hipStream_t)hip_stream;
+  hipLaunchKernelGGL(swap_q_kernel, dim3(p.nblocks), dim3(kSwapThreads), 0, stream, p);
+  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  hipLaunchKernelGGL(swap_argmin_kernel, dim3(1), dim3(kSwapThreads), 0, stream, p);
+  return hm_launch_status();
+}

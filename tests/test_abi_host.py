@@ -133,6 +133,21 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_alltoall_times(5, i32x(1, 1, 1, 1, 1), 4, 1.0, 1.0, fake, fake, z, z, z, z, fake, fake, None) == B.HM_ERR_TOPOLOGY
     assert L.hm_alltoall_times(2, i32x(1, 2), 4, 1.0, 1.0, None, fake, z, z, z, z, fake, fake, None) == B.HM_ERR_NULL
 
+    # expert swap
+    assert L.hm_swap_workspace_bytes(256, 32) == (64 + 2 * 256 + 256 * 32 + 8 * 256 * 256) * 4
+    assert L.hm_swap_workspace_bytes(0, 4) == 0
+    big = 1 << 30
+    assert L.hm_swap_counts(fake, fake, 4, 2, 8, 4, 3, fake, None, fake, big, None) == B.HM_ERR_TOPOLOGY     # 3 does not divide 4
+    assert L.hm_swap_counts(fake, fake, 4, 2, 8, 4, 2, None, None, fake, big, None) == B.HM_ERR_NULL
+    assert L.hm_swap_counts(fake, fake, 4, 2, 8, 4, 2, fake, None, fake, 16, None) == B.HM_ERR_WORKSPACE
+    assert L.hm_swap_counts(fake, fake, 4, 2, 10000, 4, 2, fake, None, fake, big, None) == B.HM_ERR_SHAPE    # E*E*64 overflows
+    zp = (ctypes.c_void_p * 2)(None, 0x1000)
+    assert L.hm_swap_select(2, i32x(1, 2), 4, 8, 1.0, 1.0, zp, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, 8, None) == B.HM_ERR_WORKSPACE
+    assert L.hm_swap_select(2, i32x(1, 3), 4, 8, 1.0, 1.0, zp, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_TOPOLOGY
+    zn = (ctypes.c_void_p * 2)(None, None)
+    assert L.hm_swap_select(2, i32x(1, 2), 4, 8, 1.0, 1.0, zn, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
+    assert L.hm_swap_select(1, i32x(1), 4, 8, 1.0, 1.0, None, None, None, 1.0, None, None, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
+
 
 def test_binding_refuses_cpu_tensors(B):
     import torch

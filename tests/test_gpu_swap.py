@@ -1,0 +1,97 @@
+"""GPU parity for the hierarchical expert swap: the swap tensor Z (bit-exact against the oracle's
+definition-based recount on small inputs and against its incremental update at full size) and
+the selection of Eq.(8)-(11) (bit-exact for the plain maximum, 1e-12 with the smooth maximum)."""
+import numpy as np
+import pytest
+
+from paper_2508_09591_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def hw():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import gpu_harness
+    from paper_2508_09591_amd import binding
+    binding.lib()
+    return gpu_harness
+
+
+def _gpu_z(hw, ids, e2r, G, ng):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    E = e2r.shape[0]
+    Z = torch.full((E, E, ng), -9, dtype=torch.int32, device="cuda")
+    st = torch.full((1,), 5, dtype=torch.int32, device="cuda")
+    B.hm_swap_counts(hw.dev(ids), hw.dev(e2r), G, ng, Z, st)
+    return Z, int(st.item())
+
+
+def test_swap_counts_small_against_definition(hw, oracle):
+    rng = np.random.default_rng(5)
+    for trial in range(60):
+        G = int(rng.choice([2, 4, 8, 6, 64]))
+        ng = int(rng.choice([g for g in (1, 2, 3, 4, 6, 8, 32, 64) if G % g == 0 and g <= G]))
+        E = int(rng.integers(2, 40))
+        T, K = int(rng.integers(0, 300)), int(rng.integers(1, 7))
+        ids = rng.integers(0, E, (T, K), dtype=np.int32)
+        e2r = rng.integers(0, G, E).astype(np.int32)
+        if trial % 5 == 0 and T:
+            ids[rng.integers(0, T), 0] = -2
+        if trial % 7 == 0:
+            e2r[rng.integers(0, E)] = G + 1
+        ref, st_ref = oracle.swap_counts(ids, e2r, G, ng, "naive")
+        Z, st = _gpu_z(hw, ids, e2r, G, ng)
+        assert np.array_equal(Z.cpu().numpy(), ref) and st == st_ref, (trial, G, ng, E, T, K)
+
+
+@pytest.mark.parametrize("name,placement", [("qwen3", "contiguous"), ("dsv3", "contiguous"), ("skew", "swapped")])
+def test_swap_counts_full_size(hw, oracle, name, placement):
+    wl = W.WORKLOADS[name]
+    r = W.make_routing(wl)
+    e2r = r.extras["expert_to_rank_swapped"] if placement == "swapped" else r.expert_to_rank
+    for ng in (wl.G, wl.nodes):
+        ref, st_ref = oracle.swap_counts(r.topk_ids, e2r, wl.G, ng, "incremental")
+        Z, st = _gpu_z(hw, r.topk_ids, e2r, wl.G, ng)
+        assert np.array_equal(Z.cpu().numpy(), ref) and st == st_ref == 0, (name, ng)
+
+
+def test_swap_select_parity(hw, oracle):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["skew"]
+    r = W.make_routing(wl, T=4096)
+    e2r = r.extras["expert_to_rank_swapped"]
+    G, E = wl.G, wl.E
+    cuts = {u: _gpu_z(hw, r.topk_ids, e2r, G, u)[0] for u in (4, 8, 16, 32)}
+    host = {u: z.cpu().numpy() for u, z in cuts.items()}
+    ai, bi = [0, 4.97e-1, 3.01e-1, 1.49e-1], [0, 5.29e-7, 1.17e-7, 2.06e-8]
+    aa, ba = [7.22e-1, 5.71e-1, 1.14e-1, 2.04e-1], [5.70e-7, 1.27e-7, 2.63e-8, 1.64e-8]
+    Ufull = [1, 4, 8, 16]
+    for d in (1, 2, 3, 4):
+        U = Ufull[:d]
+        for gamma in (0.0, 10.0, 5.0):
+            zi_h = [None] + [host[U[i]] for i in range(1, d)]
+            zi_d = [None] + [cuts[U[i]] for i in range(1, d)]
+            si = [0.0] + [float(U[i - 1]) for i in range(1, d)]              # fan-in of each inter level
+            Qr, best_r, bt_r = oracle.swap_select(U, G, wl.H, 2.0, zi_h, host[32], si, float(U[d - 1]), ai[:d], bi[:d],
+                                                  aa[d - 1], ba[d - 1], gamma)
+            Q = torch.full((E, E), float("nan"), dtype=torch.float64, device="cuda")
+            bp = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+            bt = torch.zeros(1, dtype=torch.float64, device="cuda")
+            B.hm_swap_select(U, G, wl.H, 2.0, zi_d, cuts[32], si, float(U[d - 1]), ai[:d], bi[:d], aa[d - 1], ba[d - 1],
+                             gamma, Q, bp, bt)
+            Qg = Q.cpu().numpy()
+            pair = tuple(int(x) for x in bp.cpu().numpy())
+            if gamma <= 0:
+                assert np.array_equal(Qg.view(np.uint64), Qr.view(np.uint64)), (d, gamma)
+                assert pair == best_r and float(bt.item()) == bt_r
+            else:
+                assert np.allclose(Qg, Qr, rtol=1e-12, atol=0), (d, gamma)
+                assert Qr[pair] <= bt_r * (1 + 1e-12) and abs(float(bt.item()) - bt_r) <= 1e-12 * bt_r
+            assert float(bt.item()) == Qg[pair] == Qg.min()
+            flat = int(np.argmin(Qg))
+            assert pair == (flat // E, flat % E)                               # first minimiser in row-major order
+    print("d=4 gamma=5 best pair", pair, "time", float(bt.item()), "no swap", Qg[0, 0])
