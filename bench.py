@@ -55,9 +55,9 @@ def main() -> int:
     ap.add_argument("--warm-y", action="store_true",
                     help="combine reads the buffer dispatch wrote in the same step (partly cache-resident) instead of "
                          "an identical one written sets/2 steps earlier")
-    ap.add_argument("--path", default="send", choices=["send", "recv", "planner"],
+    ap.add_argument("--path", default="send", choices=["send", "recv", "planner", "table4"],
                     help="send: the headline step (default); recv: the receiver stages of the two-hop exchange; "
-                         "planner: dimension selection + expert-swap planner")
+                         "planner: dimension selection + expert-swap planner; table4: the K/E/G grid of the paper's Table IV")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -83,6 +83,8 @@ def main() -> int:
         return run_recv(args)
     if args.path == "planner":
         return run_planner(args)
+    if args.path == "table4":
+        return run_table4(args)
     wl = W.WORKLOADS[args.workload]
     level = LEVELS[args.level] if args.level else wl.levels[0]
     level_name = W.LEVEL_NAMES[level]
@@ -481,6 +483,71 @@ def run_planner(args) -> int:
                            "peak": 157.3 / 2, "unit": "Tupdate/s (int32 add, vs the 78.6 Tadd/s vector rate)",
                            "frac": round(updates / (swap_ms * 1e-3) / 1e12 / (157.3 / 2), 6), "traffic": None},
               "cpu_baseline": cpu, "kernels": kern}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+def run_table4(args) -> int:
+    """The K / E / G grid of the paper's Table IV on the Qwen3-shaped layer: rows per token at the
+    three dedup levels (what the deduplication saves) and the dispatch+combine rate at each."""
+    import numpy as np
+    import torch
+    from paper_2508_09591_amd import binding as B
+    from paper_2508_09591_amd import workloads as W
+
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    stream = torch.cuda.Stream()
+    table = []
+    for wl in W.table4_variants():
+        T, K, H, E = wl.T, wl.K, wl.H, wl.E
+        r = W.make_routing(wl)
+        ids_d, w_d, e2r_d = dev(r.topk_ids), dev(r.topk_weights), dev(r.expert_to_rank)
+        x = torch.randn((T, H), dtype=torch.float32, device="cuda").to(torch.bfloat16)
+        row = {"variant": wl.name, "K": K, "E": E, "G": wl.G}
+        for level, lname in ((0, "none"), (1, "gpu"), (2, "node")):
+            plan = B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, stream=stream)
+            st, total = B.hm_plan_status(plan, stream=stream)
+            assert st == 0
+            nsets = 4
+            xs = [x.clone() for _ in range(nsets)]
+            packs = [torch.empty((total, H), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
+            outs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
+            for s_ in range(nsets):
+                B.hm_dispatch_pack(xs[s_], plan, packs[s_], stream=stream)
+
+            def pair(i):
+                s_ = i % nsets
+                B.hm_dispatch_pack(xs[s_], plan, packs[s_], stream=stream)
+                B.hm_combine(packs[(s_ + 2) % nsets], w_d, plan, outs[s_], stream=stream)
+
+            for i in range(args.warmup):
+                pair(i)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for i in range(args.steps):
+                pair(i)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            nbytes = 2 * (T + total) * H * 2
+            row[lname] = {"rows_per_token": round(total / T, 4), "pair_ms": round(ms, 5),
+                          "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1), "frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        row["bytes_saved_vs_none"] = {l: round(1 - (1 + row[l]["rows_per_token"]) / (1 + row["none"]["rows_per_token"]), 4)
+                                      for l in ("gpu", "node")}
+        table.append(row)
+        log("%-5s K=%-2d E=%-3d G=%-2d  rows/token none %.2f gpu %.3f node %.3f | pair ms %.4f / %.4f / %.4f | %% of peak %.1f / %.1f / %.1f"
+            % (wl.name, K, E, wl.G, row["none"]["rows_per_token"], row["gpu"]["rows_per_token"], row["node"]["rows_per_token"],
+               row["none"]["pair_ms"], row["gpu"]["pair_ms"], row["node"]["pair_ms"],
+               100 * row["none"]["frac"], 100 * row["gpu"]["frac"], 100 * row["node"]["frac"]))
+    ref = next(r_ for r_ in table if r_["variant"] == "K8")
+    result = {"metric": "dispatch+combine over the Table IV grid (Qwen3 shape): tokens/s at K=8, E=128, G=32, node level",
+              "value": round(8192 / (ref["node"]["pair_ms"] * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+              "warmup": args.warmup, "ms_per_step": ref["node"]["pair_ms"], "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+              "config": {"workload": "qwen3 shape (T=8192, H=2048), K in {6,8,10}, E in {64,128,256}, G in {8,16,32}"},
+              "roofline": {"bound": "hbm", "kernel": "hm_dispatch_pack+hm_combine", "achieved": ref["node"]["GBps"],
+                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ref["node"]["frac"], "traffic": None},
+              "cpu_baseline": None, "grid": table}
     print(json.dumps(result), flush=True)
     return 0
 

@@ -19,6 +19,9 @@
  *     kernels (an expert id outside [0,E), a rank outside [0,G), a row index outside the
  *     caller's buffer) never fault: the offending slot / row is skipped and the code is stored
  *     in the plan's device status word, which hm_plan_status returns.
+ *   - The expert id -1 marks a slot the router dropped (capacity-limited routing): every entry
+ *     point skips such a slot (slot_row = -1, slot_keep = 0, not counted, weight ignored) without
+ *     reporting an error.
  *   - Row and token indices are int32; byte offsets inside the kernels are 64-bit.
  *   - Limits: nodes*ranks_per_node <= 64, nodes <= 32 (bit masks), 1 <= K <= 64,
  *     T*K <= 2^31-1.

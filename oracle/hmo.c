@@ -23,12 +23,15 @@
 enum { HMO_LEVEL_NONE = 0, HMO_LEVEL_GPU = 1, HMO_LEVEL_NODE = 2 };
 enum { HMO_OK = 0, HMO_ERR_ARG = -1, HMO_BAD_ID = -7 };
 
-/* Destination of one slot at a level, or -1 when the expert id or its rank is out of range.
+/* Rank of one slot's expert, -1 when the expert id or its rank is out of range, -2 when the id
+ * is the drop marker -1 (a router with a capacity limit marks the slots it dropped so: such a
+ * slot is skipped everywhere without being an error).
  * Rank of an expert: expert_to_rank (contiguous blocks in Eq.(7); an arbitrary map here so that
  * an expert swap of Section IV is an exchange of two entries).  Node of a rank: rank / R, ranks
  * of one node being contiguous (Section III-B, the index illustration of Fig.6). */
 static int slot_rank(const int32_t *expert_to_rank, int32_t E, int32_t G, int32_t id)
 {
+    if (id == -1) return -2;
     if (id < 0 || id >= E) return -1;
     int32_t g = expert_to_rank[id];
     if (g < 0 || g >= G) return -1;
@@ -59,7 +62,8 @@ static int slot_dest(int rank, int32_t ranks_per_node, int32_t level)
  *  step 6  masks       rank_mask[t] = OR_k 1<<rank, node_mask[t] = OR_k 1<<node (level-free).
  *
  * Invalid slots (expert id outside [0,E), rank outside [0,G)) are dropped everywhere and
- * *status is set to HMO_BAD_ID.  rank_mask / node_mask may be NULL.
+ * *status is set to HMO_BAD_ID; the id -1 marks a slot the router dropped and is skipped the same
+ * way without an error.  rank_mask / node_mask may be NULL.
  * Buffers: dest_count[Dn], dest_offset[Dn+1], row_token/row_weight[>= T*K], slot_row/slot_keep[T*K].
  */
 int hmo_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
@@ -90,7 +94,7 @@ int hmo_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *
             const int rank = slot_rank(expert_to_rank, E, G, topk_ids[s]);
             dest[s] = slot_dest(rank, ranks_per_node, level);
             if (rank < 0) {
-                *status = HMO_BAD_ID;
+                if (rank == -1) *status = HMO_BAD_ID;
                 slot_keep[s] = 0;
                 continue;
             }
@@ -269,7 +273,7 @@ int hmo_expert_load(const int32_t *topk_ids, const int32_t *expert_to_rank, int3
         for (int32_t k = 0; k < K; ++k) {
             const int32_t id = topk_ids[(size_t)t * K + k];
             const int rank = slot_rank(expert_to_rank, E, G, id);
-            if (rank < 0) { *status = HMO_BAD_ID; continue; }
+            if (rank < 0) { if (rank == -1) *status = HMO_BAD_ID; continue; }
             load_expert[id] += 1;
             in_rank[rank] = 1;
             in_node[rank / ranks_per_node] = 1;
@@ -346,7 +350,8 @@ int hmo_plan_mapped(const int32_t *ids, const float *weights, const int32_t *des
             const size_t s = (size_t)i * K + k;
             const int32_t id = ids[s];
             int32_t d = -1;
-            if (id < 0 || id >= E) *status = HMO_BAD_ID;
+            if (id == -1) d = -1;                  /* drop marker: skipped silently */
+            else if (id < 0 || id >= E) *status = HMO_BAD_ID;
             else if (dest_map[id] >= 0 && dest_map[id] < num_dest) d = dest_map[id];
             else if (dest_map[id] != -1) *status = HMO_BAD_ID;
             slot_row[s] = d;                       /* holds the destination until rows are numbered */
@@ -443,7 +448,7 @@ int hmo_group_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int
             const int32_t ranks_per_group = G / groups[l];
             for (int32_t k = 0; k < K; ++k) {
                 const int rank = slot_rank(expert_to_rank, E, G, topk_ids[(size_t)t * K + k]);
-                if (rank < 0) { *status = HMO_BAD_ID; continue; }
+                if (rank < 0) { if (rank == -1) *status = HMO_BAD_ID; continue; }
                 in_group[rank / ranks_per_group] = 1;
             }
             for (int32_t j = 0; j < groups[l]; ++j) counts[l * 64 + j] += in_group[j];
@@ -540,7 +545,7 @@ int hmo_swap_counts_naive(const int32_t *ids, const int32_t *expert_to_rank, int
     if (T < 0 || K <= 0 || E <= 0 || G <= 0 || G > 64 || ng < 1 || ng > G || G % ng != 0) return HMO_ERR_ARG;
     *status = HMO_OK;
     for (size_t s = 0; s < (size_t)T * K; ++s)
-        if (slot_rank(expert_to_rank, E, G, ids[s]) < 0) *status = HMO_BAD_ID;
+        if (slot_rank(expert_to_rank, E, G, ids[s]) == -1) *status = HMO_BAD_ID;
     int32_t *placement = (int32_t *)malloc(sizeof(int32_t) * (size_t)E);
     if (!placement) return HMO_ERR_ARG;
     for (int32_t r = 0; r < E; ++r)
@@ -589,7 +594,7 @@ int hmo_swap_counts_incremental(const int32_t *ids, const int32_t *expert_to_ran
         for (int32_t k = 0; k < K; ++k) {
             const int32_t id = ids[(size_t)t * K + k];
             const int rank = slot_rank(expert_to_rank, E, G, id);
-            if (rank < 0) { *status = HMO_BAD_ID; continue; }
+            if (rank < 0) { if (rank == -1) *status = HMO_BAD_ID; continue; }
             if (!selected[id]) { selected[id] = 1; in_group[rank / per] += 1; }
         }
         for (int32_t a = 0; a < E; ++a) {

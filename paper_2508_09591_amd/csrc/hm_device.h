@@ -21,8 +21,10 @@ __device__ __forceinline__ void flag(int32_t *status, int32_t code) {
   if (status) atomicMin(status, code);
 }
 
-// Rank of an expert id, or -1 when the id or the placement entry is out of range.
+// Rank of an expert id; -1 when the id or the placement entry is out of range (an error), -2 for
+// the id -1, the marker of a slot the router dropped (skipped everywhere, not an error).
 __device__ __forceinline__ int rank_of(const int32_t *__restrict__ expert_to_rank, int E, int G, int id) {
+  if (id == -1) return -2;
   if ((unsigned)id >= (unsigned)E) return -1;
   const int g = expert_to_rank[id];
   return ((unsigned)g >= (unsigned)G) ? -1 : g;

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kLoadThreads) void load_count_kernel(LoadParams p) 
         const int id = tok[k];
         const int g = rank_of(p.expert_to_rank, p.E, p.G, id);
         if (g < 0) {
-          flag(p.status, HM_ERR_BAD_ID);
+          if (g == -1) flag(p.status, HM_ERR_BAD_ID);
           continue;
         }
         if (lds_hist) atomicAdd(&hist[id], 1);

@@ -40,8 +40,8 @@ __global__ __launch_bounds__(kGroupThreads) void group_count_kernel(GroupParams 
       const int32_t *tok = p.ids + t * p.K;
       for (int k = 0; k < p.K; ++k) {
         const int g = rank_of(p.expert_to_rank, p.E, p.G, tok[k]);
-        if (g < 0) flag(p.status, HM_ERR_BAD_ID);
-        else rm |= 1ull << g;
+        if (g >= 0) rm |= 1ull << g;
+        else if (g == -1) flag(p.status, HM_ERR_BAD_ID);
       }
     }
     for (int l = 0; l < p.depth; ++l) {

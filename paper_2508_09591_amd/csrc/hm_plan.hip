@@ -61,7 +61,9 @@ __device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *
     if (s >= 0 && s < p.nslots) {
       if (p.dest_map) {
         const int id = p.ids[s];
-        if ((unsigned)id < (unsigned)p.E) {
+        if (id == -1) {
+          r = -2;   // slot dropped by the router
+        } else if ((unsigned)id < (unsigned)p.E) {
           const int v = p.dest_map[id];
           if (v >= 0 && v < p.Dn) r = d = v;
           else if (v == -1) r = -2;

@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kSwapThreads) void swap_factors_kernel(SwapParams p
         const int a = tok[k];
         const int g = rank_of(p.expert_to_rank, p.E, p.G, a);
         if (g < 0) {
-          flag(p.status, HM_ERR_BAD_ID);
+          if (g == -1) flag(p.status, HM_ERR_BAD_ID);
           continue;
         }
         gm |= 1ull << (g / p.per);

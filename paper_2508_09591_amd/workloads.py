@@ -91,6 +91,21 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
+def table4_variants():
+    """The K / E / G grid of the paper's Table IV (one parameter varied at a time around the
+    defaults K=8, E=128, G=32) on the Qwen3-30B-A3B-shaped layer; 8 ranks per node."""
+    import dataclasses
+    base = WORKLOADS["qwen3"]
+    out = []
+    for K in (6, 8, 10):
+        out.append(dataclasses.replace(base, name="K%d" % K, K=K, seed=40 + K))
+    for E in (64, 256):
+        out.append(dataclasses.replace(base, name="E%d" % E, E=E, seed=50 + E))
+    for G in (8, 16):
+        out.append(dataclasses.replace(base, name="G%d" % G, nodes=G // 8, seed=60 + G))
+    return out
+
+
 @dataclass
 class Routing:
     topk_ids: np.ndarray        # [T,K] int32, slot order = descending score

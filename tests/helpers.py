@@ -19,31 +19,32 @@ NONE, GPU, NODE = 0, 1, 2
 # ---------------------------------------------------------------------------
 def brute_plan(ids, w, e2r, nodes, rpn, level):
     """Plan from the set definition.  Rows are the sorted list of (destination, token[, slot])
-    tuples -- a global sort instead of the oracle's per-destination cursors."""
+    tuples -- a global sort instead of the oracle's per-destination cursors.  Slots with the id
+    -1 (dropped by the router) take no part in anything."""
     T, K = ids.shape
     G = nodes * rpn
     Dn = nodes if level == NODE else G
+    live = [(t, k) for t in range(T) for k in range(K) if ids[t, k] != -1]
+    live_k = {t: [k for k in range(K) if ids[t, k] != -1] for t in range(T)}
 
     def dest(t, k):
         g = int(e2r[ids[t, k]])
         return g // rpn if level == NODE else g
 
     if level == NONE:
-        rows = sorted((dest(t, k), t, k) for t in range(T) for k in range(K))
+        rows = sorted((dest(t, k), t, k) for t, k in live)
         index = {r: i for i, r in enumerate(rows)}
-        slot_row = [[index[(dest(t, k), t, k)] for k in range(K)] for t in range(T)]
-        slot_keep = [[1] * K for _ in range(T)]
+        slot_row = [[index[(dest(t, k), t, k)] if ids[t, k] != -1 else -1 for k in range(K)] for t in range(T)]
+        slot_keep = [[int(ids[t, k] != -1) for k in range(K)] for t in range(T)]
+        dest_count = [sum(1 for t, k in live if dest(t, k) == j) for j in range(Dn)]
     else:
-        rows = sorted({(dest(t, k), t) for t in range(T) for k in range(K)})
+        rows = sorted({(dest(t, k), t) for t, k in live})
         index = {r: i for i, r in enumerate(rows)}
-        slot_row = [[index[(dest(t, k), t)] for k in range(K)] for t in range(T)]
-        slot_keep = [[int(k == min(k1 for k1 in range(K) if dest(t, k1) == dest(t, k))) for k in range(K)]
-                     for t in range(T)]
-    # duplicate-free count of group j = |{tokens whose group mask is set}|  (none: plain slot count)
-    if level == NONE:
-        dest_count = [sum(1 for t in range(T) for k in range(K) if dest(t, k) == j) for j in range(Dn)]
-    else:
-        dest_count = [len({t for t in range(T) for k in range(K) if dest(t, k) == j}) for j in range(Dn)]
+        slot_row = [[index[(dest(t, k), t)] if ids[t, k] != -1 else -1 for k in range(K)] for t in range(T)]
+        slot_keep = [[int(ids[t, k] != -1 and k == min(k1 for k1 in live_k[t] if dest(t, k1) == dest(t, k)))
+                      for k in range(K)] for t in range(T)]
+        # duplicate-free count of group j = |{tokens whose group mask is set}|
+        dest_count = [len({t for t, k in live if dest(t, k) == j}) for j in range(Dn)]
     row_token = [r[1] for r in rows]
     row_weight = []
     for i, r in enumerate(rows):
@@ -55,11 +56,10 @@ def brute_plan(ids, w, e2r, nodes, rpn, level):
         row_weight.append(acc)
     rank_mask = [0] * T
     node_mask = [0] * T
-    for t in range(T):
-        for k in range(K):
-            g = int(e2r[ids[t, k]])
-            rank_mask[t] |= 1 << g
-            node_mask[t] |= 1 << (g // rpn)
+    for t, k in live:
+        g = int(e2r[ids[t, k]])
+        rank_mask[t] |= 1 << g
+        node_mask[t] |= 1 << (g // rpn)
     return dict(dest_count=dest_count, row_token=row_token, slot_row=slot_row, slot_keep=slot_keep,
                 row_weight=row_weight, rank_mask=rank_mask, node_mask=node_mask, num_dest=Dn)
 

@@ -182,6 +182,14 @@ def test_full_size_stress_sampled(hw, oracle):
         torch.cuda.empty_cache()
 
 
+def test_table4_grid(hw, oracle):
+    """K in {6,8,10}, E in {64,128,256}, G in {8,16,32} (the grid of the paper's Table IV), all
+    three levels, reduced T."""
+    for wl in W.table4_variants():
+        for level in (NONE, GPU, NODE):
+            _run_layer(hw, oracle, wl, 1200, 512, level, expert_model="scaled")
+
+
 # ---- edge cases ------------------------------------------------------------------------------------
 @pytest.mark.parametrize("T,K,E,nodes,rpn,H", [
     (0, 2, 8, 2, 2, 64),        # empty
@@ -311,6 +319,56 @@ def test_bad_ids_and_small_buffers_are_flagged_not_faulted(hw, oracle):
     assert g2.status == B.HM_ERR_CAPACITY and g2.total_rows == ora.total_rows
     assert np.array_equal(g2.host()["dest_count"], ora.dest_count)
     assert np.array_equal(g2.host()["row_token"], ora.row_token[:ora.total_rows - 5])
+
+
+def test_dropped_slots_on_the_gpu(hw, oracle):
+    """Capacity-limited routing: slots marked -1 are skipped by every entry point, without error."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["qwen3"]
+    T, H = 1500, 256
+    r = W.make_routing(wl, T=T)
+    rng = np.random.default_rng(77)
+    ids = r.topk_ids.copy()
+    ids[rng.random(ids.shape) < 0.2] = -1
+    ids[11, :] = -1                                              # a token with nothing left
+    w, e2r = r.topk_weights, r.expert_to_rank
+    x = W.make_activations(wl, T=T, H=H)
+    for level in (NONE, GPU, NODE):
+        ora = oracle.plan(ids, w, e2r, wl.nodes, wl.ranks_per_node, level)
+        g = hw.GpuPlan(ids, w, e2r, wl.nodes, wl.ranks_per_node, level)
+        assert g.status == 0 == ora.status
+        hw.assert_plan_equal(g, ora, "dropped level %d" % level)
+        n = ora.total_rows
+        packed_d = torch.zeros((n, H), dtype=torch.bfloat16, device="cuda")
+        B.hm_dispatch_pack(hw.to_dev_bf16(x), g.plan, packed_d)
+        packed = hw.bf16_to_host(packed_d)
+        assert np.array_equal(packed, oracle.dispatch_pack(x, ora.row_token))
+        out_d = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.hm_combine(packed_d, g.w_d, g.plan, out_d)
+        out = hw.bf16_to_host(out_d)
+        assert bf16_ulp_distance(out, oracle.combine(packed, w, ora.slot_row)).max() <= 1
+        assert not out[11].any()
+    le, lr, ln, st = oracle.expert_load(ids, e2r, wl.nodes, wl.ranks_per_node)
+    le_d, lr_d, ln_d = (torch.full((m,), -1, dtype=torch.int32, device="cuda") for m in (wl.E, wl.G, wl.nodes))
+    st_d = torch.full((1,), 3, dtype=torch.int32, device="cuda")
+    B.hm_expert_load(hw.dev(ids), hw.dev(e2r), wl.nodes, wl.ranks_per_node, le_d, lr_d, ln_d, st_d)
+    assert np.array_equal(le_d.cpu().numpy(), le) and np.array_equal(lr_d.cpu().numpy(), lr)
+    assert np.array_equal(ln_d.cpu().numpy(), ln) and int(st_d.item()) == st == 0
+    counts_d = torch.zeros((2, 64), dtype=torch.int32, device="cuda")
+    B.hm_group_counts(hw.dev(ids), hw.dev(e2r), wl.G, [wl.G, wl.nodes], counts_d, st_d)
+    ref, st = oracle.group_counts(ids, e2r, wl.G, [wl.G, wl.nodes])
+    assert np.array_equal(counts_d.cpu().numpy(), ref) and int(st_d.item()) == st == 0
+    Z = torch.zeros((wl.E, wl.E, wl.nodes), dtype=torch.int32, device="cuda")
+    B.hm_swap_counts(hw.dev(ids), hw.dev(e2r), wl.G, wl.nodes, Z, st_d)
+    zr, st = oracle.swap_counts(ids, e2r, wl.G, wl.nodes)
+    assert np.array_equal(Z.cpu().numpy(), zr) and int(st_d.item()) == st == 0
+    dm = (e2r // wl.ranks_per_node).astype(np.int32)
+    ora = oracle.plan_mapped(ids, w, dm, wl.nodes, True)
+    plan = B.hm_plan_mapped(hw.dev(ids), hw.dev(w), hw.dev(dm), wl.nodes, True)
+    st, total = B.hm_plan_status(plan)
+    assert st == 0 == ora.status and total == ora.total_rows
+    assert np.array_equal(plan.slot_row.cpu().numpy().reshape(T, wl.K), ora.slot_row)
 
 
 def test_plan_is_deterministic(hw, oracle):

@@ -73,6 +73,34 @@ def test_random_small_tables_match_set_definition(oracle):
             _assert_plan_equals_brute(oracle, ids, w, e2r, nodes, rpn, level)
 
 
+def test_dropped_slots_are_skipped_without_error(oracle):
+    """The id -1 marks a slot a capacity-limited router dropped: it takes no part in the plan, the
+    loads or the combine, and it is not an error."""
+    rng = np.random.default_rng(19)
+    for _ in range(200):
+        nodes, rpn = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        G = nodes * rpn
+        E = G * int(rng.integers(1, 4))
+        K, T = int(rng.integers(1, 6)), int(rng.integers(1, 10))
+        ids = rng.integers(0, E, size=(T, K), dtype=np.int32)
+        ids[rng.random((T, K)) < 0.3] = -1
+        w = rng.random((T, K), dtype=np.float32)
+        e2r = rng.integers(0, G, size=E, dtype=np.int32)
+        for level in (NONE, GPU, NODE):
+            _assert_plan_equals_brute(oracle, ids, w, e2r, nodes, rpn, level)
+        le, lr, ln, st = oracle.expert_load(ids, e2r, nodes, rpn)
+        assert st == 0 and int(le.sum()) == int((ids != -1).sum())
+        assert np.array_equal(le, np.bincount(ids[ids != -1], minlength=E))
+    # a token whose slots were all dropped gets no row and a zero output
+    ids = np.array([[-1, -1], [0, -1]], np.int32)
+    w = np.array([[.5, .5], [.25, .75]], np.float32)
+    p = oracle.plan(ids, w, np.array([0, 1], np.int32), 1, 2, GPU)
+    assert p.status == 0 and p.total_rows == 1 and p.slot_row.tolist() == [[-1, -1], [0, -1]]
+    y = W.f32_to_bf16_bits(np.array([[2.0, -4.0]], np.float32))
+    out = oracle.combine(y, w, p.slot_row)
+    assert W.bf16_bits_to_f32(out).tolist() == [[0.0, 0.0], [0.5, -1.0]]
+
+
 # ---- library-routine special cases ---------------------------------------------------------
 @pytest.mark.parametrize("name", ["tiny", "qwen3"])
 def test_plan_is_bincount_and_stable_argsort(oracle, name):
