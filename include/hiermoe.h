@@ -79,6 +79,10 @@ typedef struct {
  *   rank_mask  [T]  optional  bit g set iff some valid slot of the token maps to rank g
  *   node_mask  [T]  optional  bit n set iff some valid slot maps to node n
  *   status     [1]            0, or the last HM_ERR_BAD_ID / HM_ERR_CAPACITY a kernel stored
+ *   load_expert [E], load_rank [G], load_node [nodes]   optional, all three or none: when given,
+ *                             hm_plan also produces the counts of hm_expert_load, in the same two
+ *                             launches (the planner of Section IV needs them every iteration).
+ *                             hm_plan_mapped ignores them.
  */
 typedef struct {
   int32_t num_dest;
@@ -92,6 +96,9 @@ typedef struct {
   uint64_t *rank_mask;
   uint32_t *node_mask;
   int32_t *status;
+  int32_t *load_expert;
+  int32_t *load_rank;
+  int32_t *load_node;
 } hm_plan_out;
 
 /* Bytes of device scratch hm_plan needs for these sizes (0 on invalid arguments). */

@@ -39,7 +39,8 @@ class hm_plan_out(ctypes.Structure):
                 ("row_token", ctypes.c_void_p), ("slot_row", ctypes.c_void_p),
                 ("slot_keep", ctypes.c_void_p), ("row_weight", ctypes.c_void_p),
                 ("rank_mask", ctypes.c_void_p), ("node_mask", ctypes.c_void_p),
-                ("status", ctypes.c_void_p)]
+                ("status", ctypes.c_void_p), ("load_expert", ctypes.c_void_p),
+                ("load_rank", ctypes.c_void_p), ("load_node", ctypes.c_void_p)]
 
 
 class HierMoEError(RuntimeError):
@@ -151,6 +152,9 @@ class Plan:
     status: torch.Tensor
     workspace: torch.Tensor
     c: hm_plan_out
+    load_expert: Optional[torch.Tensor] = None
+    load_rank: Optional[torch.Tensor] = None
+    load_node: Optional[torch.Tensor] = None
 
     def ref(self):
         return ctypes.byref(self.c)
@@ -161,9 +165,11 @@ def hm_plan_workspace_bytes(T: int, K: int, E: int, nodes: int, ranks_per_node: 
 
 
 def alloc_plan(T: int, K: int, E: int, nodes: int, ranks_per_node: int, level: int, device="cuda",
-               row_capacity: Optional[int] = None, masks: bool = True, num_dest: Optional[int] = None) -> Plan:
+               row_capacity: Optional[int] = None, masks: bool = True, num_dest: Optional[int] = None,
+               loads: bool = False) -> Plan:
     """Allocate (uninitialised) plan buffers; row_capacity defaults to the worst case.  With
-    num_dest given the buffers are sized for hm_plan_mapped (level none = no dedup)."""
+    num_dest given the buffers are sized for hm_plan_mapped (level none = no dedup); with loads
+    hm_plan also fills load_expert / load_rank / load_node."""
     G = nodes * ranks_per_node
     Dn = num_dest if num_dest is not None else (nodes if level == HM_DEDUP_NODE else G)
     if row_capacity is None:
@@ -178,12 +184,14 @@ def alloc_plan(T: int, K: int, E: int, nodes: int, ranks_per_node: int, level: i
                 slot_keep=e(T * K, torch.uint8), row_weight=e(row_capacity, torch.float32),
                 rank_mask=e(T, torch.int64) if masks else None,
                 node_mask=e(T, torch.int32) if masks else None,
-                status=e(1, torch.int32), workspace=e(max(ws_bytes, 16) // 4 + 4, torch.int32))
+                status=e(1, torch.int32), workspace=e(max(ws_bytes, 16) // 4 + 4, torch.int32),
+                load_expert=e(E, torch.int32) if loads else None, load_rank=e(G, torch.int32) if loads else None,
+                load_node=e(nodes, torch.int32) if loads else None)
     c = hm_plan_out()
     c.num_dest = Dn
     c.row_capacity = int(row_capacity)
     for name in ("dest_count", "dest_offset", "row_token", "slot_row", "slot_keep", "row_weight",
-                 "rank_mask", "node_mask", "status"):
+                 "rank_mask", "node_mask", "status", "load_expert", "load_rank", "load_node"):
         t = bufs[name]
         setattr(c, name, t.data_ptr() if t is not None else None)
     return Plan(T=T, K=K, level=level, num_dest=Dn, row_capacity=int(row_capacity), c=c, **bufs)

@@ -20,6 +20,7 @@ constexpr int kPlanThreads = 1024;
 constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kPlanHalo = 63;                              // K - 1 <= 63
 constexpr int kPlanStaged = kPlanThreads + 2 * kPlanHalo;
+constexpr int kPlanHist = 8192;                            // experts histogrammed in LDS for the fused loads
 
 struct PlanParams {
   const int32_t *ids;
@@ -36,6 +37,7 @@ struct PlanParams {
   uint64_t *rank_mask;
   uint32_t *node_mask;
   int32_t *status;
+  int32_t *load_expert, *load_rank, *load_node;  // optional: the counts of hm_expert_load, fused
 };
 
 // What one lane knows about its slot after staging.
@@ -118,6 +120,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanParams p) 
     p.counts[(int64_t)blockIdx.x * p.Dn + threadIdx.x] = sum;
   }
   if (blockIdx.x == 0 && threadIdx.x == 0) *p.status = 0;
+  if (p.load_expert) {   // the write kernel accumulates into these with atomics
+    const int64_t stride = (int64_t)gridDim.x * kPlanThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x; i < p.E; i += stride) p.load_expert[i] = 0;
+    if (blockIdx.x == 0 && (int)threadIdx.x < p.G) p.load_rank[threadIdx.x] = 0;
+    if (blockIdx.x == 0 && (int)threadIdx.x < p.G / p.R) p.load_node[threadIdx.x] = 0;
+  }
 }
 
 __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) {
@@ -128,7 +136,16 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   __shared__ int32_t block_base[kWave];             // first row of this workgroup per destination
   __shared__ uint64_t ballots[kPlanWaves][kWave];   // [wave][destination] -> lanes that keep a slot
   __shared__ int32_t wave_base[kPlanWaves][kWave];  // kept slots in earlier waves of the workgroup
+  __shared__ int32_t hist[kPlanHist];               // fused expert load: slots per expert
+  __shared__ int32_t blk_rank[kWave], blk_node[kWave];
   const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
+  const bool loads = p.load_expert != nullptr;
+  const bool lds_hist = p.E <= kPlanHist;
+  if (loads) {
+    if (lds_hist)
+      for (int e = threadIdx.x; e < p.E; e += kPlanThreads) hist[e] = 0;
+    if (threadIdx.x < kWave) blk_rank[threadIdx.x] = blk_node[threadIdx.x] = 0;
+  }
 
   // Column sums of the count matrix: over all workgroups (destination total) and over the
   // earlier ones (this workgroup's base).  Wave wv takes rows wv, wv+16, ...
@@ -180,40 +197,42 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   }
   __syncthreads();
 
-  if (!me.live) return;
   const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
-  if (me.dest < 0) {
-    p.slot_row[s] = -1;
-    p.slot_keep[s] = 0;
-    if (me.rank == -1) flag(p.status, HM_ERR_BAD_ID);
-  } else if (!me.keep) {
-    p.slot_keep[s] = 0;  // its slot_row is written by the slot that owns the row
-  } else {
-    const uint64_t b = ballots[wv][me.dest];
-    const int pos = __popcll(b & ((1ull << lane) - 1ull));
-    const int row = block_base[me.dest] + wave_base[wv][me.dest] + pos;
-    p.slot_keep[s] = 1;
-    p.slot_row[s] = row;
-    float wsum = p.weights[s];
-    if (p.level != HM_DEDUP_NONE) {
-      for (int k2 = me.k + 1; k2 < p.K; ++k2) {
-        if (s_dest[me.tok0 + k2] == me.dest) {
-          const int64_t s2 = s + (k2 - me.k);
-          p.slot_row[s2] = row;
-          wsum = wsum + p.weights[s2];  // ascending k, fp32
+  if (me.live) {
+    if (me.dest < 0) {
+      p.slot_row[s] = -1;
+      p.slot_keep[s] = 0;
+      if (me.rank == -1) flag(p.status, HM_ERR_BAD_ID);
+    } else if (!me.keep) {
+      p.slot_keep[s] = 0;  // its slot_row is written by the slot that owns the row
+    } else {
+      const uint64_t b = ballots[wv][me.dest];
+      const int pos = __popcll(b & ((1ull << lane) - 1ull));
+      const int row = block_base[me.dest] + wave_base[wv][me.dest] + pos;
+      p.slot_keep[s] = 1;
+      p.slot_row[s] = row;
+      float wsum = p.weights[s];
+      if (p.level != HM_DEDUP_NONE) {
+        for (int k2 = me.k + 1; k2 < p.K; ++k2) {
+          if (s_dest[me.tok0 + k2] == me.dest) {
+            const int64_t s2 = s + (k2 - me.k);
+            p.slot_row[s2] = row;
+            wsum = wsum + p.weights[s2];  // ascending k, fp32
+          }
         }
       }
-    }
-    if (row < p.row_capacity) {
-      p.row_token[row] = me.t;
-      p.row_weight[row] = wsum;
-    } else {
-      flag(p.status, HM_ERR_CAPACITY);
+      if (row < p.row_capacity) {
+        p.row_token[row] = me.t;
+        p.row_weight[row] = wsum;
+      } else {
+        flag(p.status, HM_ERR_CAPACITY);
+      }
     }
   }
-  if (me.k == 0 && (p.rank_mask || p.node_mask)) {
-    uint64_t rm = 0;
-    uint32_t nm = 0;
+  // Per-token masks, owned by the lane of the token's slot 0.
+  uint64_t rm = 0;
+  uint32_t nm = 0;
+  if (me.live && me.k == 0 && (p.rank_mask || p.node_mask || loads)) {
     for (int k2 = 0; k2 < p.K; ++k2) {
       const int r2 = s_rank[me.tok0 + k2];
       if (r2 >= 0) {
@@ -224,6 +243,33 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
     if (p.rank_mask) p.rank_mask[me.t] = rm;
     if (p.node_mask) p.node_mask[me.t] = nm;
   }
+  if (!loads) return;
+
+  // Fused hm_expert_load: slots per expert, and tokens per rank / node counted once each from the
+  // masks above (a ballot per group; lane g keeps the count of group g).
+  if (me.live && me.rank >= 0) {
+    const int id = p.ids[s];
+    if (lds_hist) atomicAdd(&hist[id], 1);
+    else atomicAdd(&p.load_expert[id], 1);
+  }
+  int my_rank_cnt = 0, my_node_cnt = 0;
+  const int nodes = p.G / p.R;
+  for (int g = 0; g < p.G; ++g) {
+    const uint64_t b = __ballot((rm >> g) & 1ull);
+    if (lane == g) my_rank_cnt = __popcll(b);
+  }
+  for (int n = 0; n < nodes; ++n) {
+    const uint64_t b = __ballot((nm >> n) & 1u);
+    if (lane == n) my_node_cnt = __popcll(b);
+  }
+  if (my_rank_cnt) atomicAdd(&blk_rank[lane], my_rank_cnt);
+  if (my_node_cnt) atomicAdd(&blk_node[lane], my_node_cnt);
+  __syncthreads();
+  if (lds_hist)
+    for (int e = threadIdx.x; e < p.E; e += kPlanThreads)
+      if (hist[e]) atomicAdd(&p.load_expert[e], hist[e]);
+  if ((int)threadIdx.x < p.G && blk_rank[threadIdx.x]) atomicAdd(&p.load_rank[threadIdx.x], blk_rank[threadIdx.x]);
+  if ((int)threadIdx.x < nodes && blk_node[threadIdx.x]) atomicAdd(&p.load_node[threadIdx.x], blk_node[threadIdx.x]);
 }
 
 // Destination table of a receiver stage: one workgroup walks the E experts in chunks of 1024 and
@@ -294,6 +340,8 @@ extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights,
   if (st != HM_OK) return st;
   if (E < 1 || out->row_capacity < 0) return HM_ERR_SHAPE;
   if (T > 0 && (!topk_ids || !topk_weights)) return HM_ERR_NULL;
+  if (out->load_expert && (!out->load_rank || !out->load_node)) return HM_ERR_NULL;
+  if (!out->load_expert && (out->load_rank || out->load_node)) return HM_ERR_NULL;
   st = hm_check_topology(topo);
   if (st != HM_OK) return st;
   if (level != HM_DEDUP_NONE && level != HM_DEDUP_GPU && level != HM_DEDUP_NODE) return HM_ERR_LEVEL;
@@ -324,6 +372,9 @@ extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights,
   p.rank_mask = out->rank_mask;
   p.node_mask = out->node_mask;
   p.status = out->status;
+  p.load_expert = out->load_expert;
+  p.load_rank = out->load_rank;
+  p.load_node = out->load_node;
   out->num_dest = p.Dn;
 
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -377,6 +428,7 @@ extern "C" hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_wei
   p.rank_mask = out->rank_mask;
   p.node_mask = out->node_mask;
   p.status = out->status;
+  p.load_expert = p.load_rank = p.load_node = nullptr;   // the fused loads need the rank placement
   out->num_dest = num_dest;
 
   hipStream_t stream = (hipStream_t)hip_stream;

@@ -371,6 +371,54 @@ def test_dropped_slots_on_the_gpu(hw, oracle):
     assert np.array_equal(plan.slot_row.cpu().numpy().reshape(T, wl.K), ora.slot_row)
 
 
+@pytest.mark.parametrize("name,T", [("tiny", 1024), ("qwen3", 3000), ("dsv3", 8192), ("skew", 16384), ("stress", 65536)])
+def test_plan_with_fused_loads(hw, oracle, name, T):
+    """hm_plan with the optional load arrays: same plan, plus the counts of hm_expert_load."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS[name]
+    r = W.make_routing(wl, T=T)
+    ids = r.topk_ids.copy()
+    e2r = r.extras.get("expert_to_rank_swapped", r.expert_to_rank)
+    if name == "qwen3":
+        ids[7, 2] = -1                                         # a dropped slot
+        ids[100, 0] = wl.E + 1                                 # an invalid one
+    le, lr, ln, st = oracle.expert_load(ids, e2r, wl.nodes, wl.ranks_per_node)
+    ids_d, w_d, e2r_d = hw.dev(ids), hw.dev(r.topk_weights), hw.dev(e2r)
+    for level in (NONE, GPU, NODE):
+        ora = oracle.plan(ids, r.topk_weights, e2r, wl.nodes, wl.ranks_per_node, level)
+        plan = B.alloc_plan(T, wl.K, wl.E, wl.nodes, wl.ranks_per_node, level, loads=True)
+        for t in (plan.load_expert, plan.load_rank, plan.load_node):
+            t.fill_(-99)
+        B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan)
+        stg, total = B.hm_plan_status(plan)
+        assert stg == ora.status == st and total == ora.total_rows
+        assert np.array_equal(plan.slot_row.cpu().numpy().reshape(T, wl.K), ora.slot_row)
+        assert np.array_equal(plan.row_token[:total].cpu().numpy(), ora.row_token)
+        assert np.array_equal(plan.load_expert.cpu().numpy(), le), (name, level)
+        assert np.array_equal(plan.load_rank.cpu().numpy(), lr), (name, level)
+        assert np.array_equal(plan.load_node.cpu().numpy(), ln), (name, level)
+
+
+def test_fused_loads_with_many_experts(hw, oracle):
+    """More experts than the LDS histogram holds: the global-atomics path."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(404)
+    T, K, E, nodes, rpn = 3000, 4, 9000, 4, 8
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)
+    w = rng.random((T, K), dtype=np.float32)
+    e2r = rng.integers(0, nodes * rpn, E).astype(np.int32)
+    le, lr, ln, st = oracle.expert_load(ids, e2r, nodes, rpn)
+    plan = B.alloc_plan(T, K, E, nodes, rpn, GPU, loads=True)
+    B.hm_plan(hw.dev(ids), hw.dev(w), hw.dev(e2r), nodes, rpn, GPU, plan=plan)
+    stg, total = B.hm_plan_status(plan)
+    ora = oracle.plan(ids, w, e2r, nodes, rpn, GPU)
+    assert stg == 0 and total == ora.total_rows
+    assert np.array_equal(plan.load_expert.cpu().numpy(), le) and np.array_equal(plan.load_rank.cpu().numpy(), lr)
+    assert np.array_equal(plan.load_node.cpu().numpy(), ln)
+
+
 def test_plan_is_deterministic(hw, oracle):
     import torch
     wl = W.WORKLOADS["dsv3"]
