@@ -193,6 +193,20 @@ def recv_dest_map(expert_to_rank, nodes: int, ranks_per_node: int, my_rank: int,
     return dm, int(nd.value)
 
 
+def level_dest_map(expert_to_rank, G: int, my_rank: int, parent_groups: int, child_groups: int):
+    """(dest_map[E], num_dest) of one hop of the d-dimensional exchange (see hmo.c)."""
+    lib = _load()
+    e2r = _c(expert_to_rank, np.int32)
+    E = e2r.shape[0]
+    dm = np.full(E, -9, np.int32)
+    nd = ctypes.c_int32(0)
+    rc = lib.hmo_level_dest_map(_p(e2r), ctypes.c_int32(E), ctypes.c_int32(G), ctypes.c_int32(my_rank),
+                                ctypes.c_int32(parent_groups), ctypes.c_int32(child_groups), _p(dm), ctypes.byref(nd))
+    if rc != 0:
+        raise ValueError("hmo_level_dest_map: argument error %d" % rc)
+    return dm, int(nd.value)
+
+
 def plan_mapped(ids, weights, dest_map, num_dest: int, dedup: bool) -> Plan:
     """Plan for an arbitrary expert -> destination table; Plan.rank_mask holds the destination mask."""
     lib = _load()

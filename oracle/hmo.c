@@ -324,6 +324,35 @@ int hmo_recv_dest_map(const int32_t *expert_to_rank, int32_t E, int32_t nodes, i
 }
 
 /*
+ * hmo_level_dest_map -- the destination table of one hop of the d-dimensional exchange (Section
+ * III-A/B: Inter-level-i, or the final Intra-level, seen from `my_rank`).  The G ranks are cut into
+ * parent_groups (= U[i-1]) and into child_groups (= U[i], or G for the Intra-level hop) contiguous
+ * equal groups, parent | child | G.  Experts whose rank lies in my parent group map to the index
+ * of their child group inside that parent, 0 .. child/parent - 1 -- these are the U[i]/U[i-1]
+ * peers of Eq.(4) (G/U[d-1] peers in Eq.(5)); experts in other parent groups map to -1 (their
+ * copies were routed elsewhere by an earlier hop); invalid placement entries to -2.
+ * parent = 1, child = nodes is the sender's node-level cut; parent = nodes, child = G is the
+ * intra-node hop of HD2.
+ */
+int hmo_level_dest_map(const int32_t *expert_to_rank, int32_t E, int32_t G, int32_t my_rank, int32_t parent_groups,
+                       int32_t child_groups, int32_t *dest_map, int32_t *num_dest)
+{
+    if (!expert_to_rank || !dest_map || !num_dest || E <= 0 || G <= 0 || G > 64) return HMO_ERR_ARG;
+    if (my_rank < 0 || my_rank >= G || parent_groups < 1 || child_groups < parent_groups || child_groups > G) return HMO_ERR_ARG;
+    if (child_groups % parent_groups != 0 || G % child_groups != 0) return HMO_ERR_ARG;
+    const int32_t ranks_per_parent = G / parent_groups, ranks_per_child = G / child_groups;
+    const int32_t children_per_parent = child_groups / parent_groups;
+    for (int32_t e = 0; e < E; ++e) {
+        const int32_t g = expert_to_rank[e];
+        if (g < 0 || g >= G) dest_map[e] = -2;
+        else if (g / ranks_per_parent != my_rank / ranks_per_parent) dest_map[e] = -1;
+        else dest_map[e] = (g / ranks_per_child) % children_per_parent;
+    }
+    *num_dest = children_per_parent;
+    return HMO_OK;
+}
+
+/*
  * hmo_plan_mapped -- the plan of hmo_plan for an arbitrary expert -> destination table:
  * dest_map[e] in [0,num_dest) is a destination, -1 means "no copy at this hop" (the slot is
  * skipped without error: slot_row = -1, slot_keep = 0), anything else or an id outside [0,E) is

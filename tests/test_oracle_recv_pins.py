@@ -233,3 +233,94 @@ def test_hierarchical_round_trip_reproduces_the_layer(oracle, name, src_local):
     assert np.all(np.abs(out - expect) <= 4 * 2.0 ** -8 * np.abs(expect) + 1e-30)
     same = hierarchical_layer(oracle, wl, ids, w, e2r, x, np.ones_like(c), src_local)
     assert bf16_ulp_distance(same, x).max() == 0
+
+
+# ---- d-dimensional exchange: any chain of group cuts ------------------------------------------------
+def test_level_dest_map_against_numpy(oracle):
+    rng = np.random.default_rng(31)
+    for _ in range(80):
+        G = int(rng.choice([4, 8, 16, 32, 64, 12]))
+        divs = [u for u in range(1, G + 1) if G % u == 0]
+        parent = int(rng.choice(divs))
+        child = int(rng.choice([u for u in divs if u % parent == 0]))
+        E = G * int(rng.integers(1, 4))
+        e2r = rng.integers(0, G, E).astype(np.int32)
+        me = int(rng.integers(0, G))
+        dm, nd = oracle.level_dest_map(e2r, G, me, parent, child)
+        in_parent = e2r // (G // parent) == me // (G // parent)
+        want = np.where(in_parent, (e2r // (G // child)) % (child // parent), -1)
+        assert nd == child // parent and np.array_equal(dm, want)
+    # the two-level special cases are the tables of hmo_recv_dest_map and of the node-level sender plan
+    e2r = W.contiguous_placement(256, 32)
+    a, na = oracle.level_dest_map(e2r, 32, 13, 4, 32)
+    b, nb = oracle.recv_dest_map(e2r, 4, 8, 13, INTRA)
+    assert na == nb and np.array_equal(a, b)
+    a, na = oracle.level_dest_map(e2r, 32, 13, 1, 4)
+    assert na == 4 and np.array_equal(a, e2r // 8)
+
+
+def multi_hop_layer(oracle, ids, w, e2r, G, chain, x, c, holder=0):
+    """The d-dimensional exchange on the oracle for one source rank: `chain` = [U[1], .., U[d-1], G].
+    Returns (per-rank token lists, layer output).  Each hop plans with the table of its cut, packs,
+    hands every child group's rows to a rank of that group, and merges what comes back."""
+    delivered = {}
+
+    def hop(level, rank, tokens, rows):
+        """rows: bf16 rows held by `rank` for `tokens`; returns the merged result rows."""
+        parent = 1 if level == 0 else chain[level - 1]
+        child = chain[level]
+        dm, nd = oracle.level_dest_map(e2r, G, rank, parent, child)
+        p = oracle.plan_mapped(ids[tokens], w[tokens], dm, nd, True)
+        packed = oracle.dispatch_pack(rows, p.row_token)
+        y = np.zeros_like(packed)
+        for j in range(nd):
+            seg = slice(p.dest_offset[j], p.dest_offset[j + 1])
+            if seg.start == seg.stop:
+                continue
+            sub_tokens = tokens[p.row_token[seg]]
+            # a rank of child group j (inside my parent group): same offset inside the group as mine
+            first = (rank // (G // parent)) * (G // parent) + j * (G // child)
+            peer = first + rank % (G // child)
+            if level == len(chain) - 1:                      # child groups are single ranks: local experts
+                delivered[peer] = sub_tokens
+                dm3, nd3 = oracle.recv_dest_map(e2r, 1, G, peer, LOCAL)
+                p3 = oracle.plan_mapped(ids[sub_tokens], w[sub_tokens], dm3, nd3, False)
+                xin = oracle.dispatch_pack(packed[seg], p3.row_token)
+                yexp = np.zeros_like(xin)
+                for jj, e in enumerate(np.flatnonzero(e2r == peer)):
+                    s3 = slice(p3.dest_offset[jj], p3.dest_offset[jj + 1])
+                    yexp[s3] = W.f32_to_bf16_bits(c[e] * W.bf16_bits_to_f32(xin[s3]))
+                y[seg] = oracle.combine_mix(yexp, w[sub_tokens], p3.slot_row)
+            else:
+                y[seg] = hop(level + 1, peer, sub_tokens, packed[seg])
+        if level == 0:
+            return oracle.combine(y, w[tokens], p.slot_row)
+        return oracle.combine_mix(y, w[tokens], p.slot_row)
+
+    out = hop(0, holder, np.arange(ids.shape[0]), x)
+    return delivered, out
+
+
+@pytest.mark.parametrize("name,chain", [("qwen3", [4, 8, 16, 32]), ("dsv3", [4, 32]), ("dsv3", [2, 8, 32]),
+                                        ("tiny", [2, 4]), ("skew", [32]), ("qwen3", [8, 32])])
+def test_d_dimensional_exchange_delivers_and_reproduces_the_layer(oracle, name, chain):
+    """HDd for any chain of cuts (the paper's 4-level U = [1,4,8,16] on 32 GPUs included): every rank
+    receives exactly the tokens of the one-hop deduplicated exchange, and the merged result is the
+    MoE layer's output."""
+    wl = W.WORKLOADS[name]
+    T, H = 260, 40
+    r = W.make_routing(wl, T=T)
+    ids, w = r.topk_ids, r.topk_weights
+    e2r = r.extras.get("expert_to_rank_swapped", r.expert_to_rank)
+    x = W.make_activations(wl, T=T, H=H)
+    c = W.make_expert_scales(wl)
+    delivered, out = multi_hop_layer(oracle, ids, w, e2r, wl.G, chain, x, c, holder=wl.G - 1)
+    flat = oracle.plan(ids, w, e2r, wl.nodes, wl.ranks_per_node, GPU)
+    for g in range(wl.G):
+        want = flat.row_token[flat.dest_offset[g]:flat.dest_offset[g + 1]]
+        assert np.array_equal(delivered.get(g, np.zeros(0, np.int64)), want), (chain, g)
+    expect = (w.astype(np.float64) * c[ids].astype(np.float64)).sum(1)[:, None] * W.bf16_bits_to_f64(x)
+    n_roundings = len(chain) + 2                              # expert output, one merge per hop, final combine
+    assert np.all(np.abs(W.bf16_bits_to_f64(out) - expect) <= n_roundings * 2.0 ** -8 * np.abs(expect) + 1e-30)
+    _, same = multi_hop_layer(oracle, ids, w, e2r, wl.G, chain, x, np.ones_like(c), holder=0)
+    assert bf16_ulp_distance(same, x).max() == 0
