@@ -195,6 +195,20 @@ hm_status hm_recv_dest_map(const int32_t *expert_to_rank, int32_t E, hm_topology
                            hm_recv_stage stage, int32_t *dest_map, int32_t *num_dest, void *hip_stream);
 
 /*
+ * hm_level_dest_map -- the destination table of one hop of the d-dimensional exchange (Section
+ * III-A/B: Inter-level-i, or the final Intra-level hop) seen from `my_rank`.  The G ranks are cut
+ * into parent_groups (= U[i-1]) and child_groups (= U[i], or G for the Intra-level hop) contiguous
+ * equal groups, parent | child | G <= 64.  dest_map[e] (device int32[E]) = index of the expert's
+ * child group inside my parent group (0 .. child/parent - 1, the U[i]/U[i-1] peers of Eq.(4)) when
+ * its rank lies in my parent group, -1 when it lies elsewhere, -2 for an invalid placement entry;
+ * num_dest (device int32[1]) = child/parent.  parent = 1, child = nodes is the node-level cut of
+ * hm_plan; parent = nodes, child = G equals HM_RECV_INTRA_NODE.  Feed the table to hm_plan_mapped.
+ */
+hm_status hm_level_dest_map(const int32_t *expert_to_rank, int32_t E, int32_t G, int32_t my_rank,
+                            int32_t parent_groups, int32_t child_groups, int32_t *dest_map, int32_t *num_dest,
+                            void *hip_stream);
+
+/*
  * hm_plan_mapped -- hm_plan for an arbitrary expert -> destination table (device int32[E]):
  * dest_map[e] in [0,num_dest) is a destination, -1 means no copy at this hop (slot skipped without
  * error: slot_row = -1, slot_keep = 0), anything else -- or an id outside [0,E) -- is invalid

@@ -26,7 +26,7 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_combine_transpose", "hm_expert_load", "hm_status_string", "hm_recv_dest_map",
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
-           "hm_swap_select")
+           "hm_swap_select", "hm_level_dest_map")
 
 
 class hm_topology(ctypes.Structure):
@@ -101,6 +101,8 @@ def lib():
         L.hm_swap_select.argtypes = [i32, ctypes.POINTER(i32), i32, i32, ctypes.c_double, ctypes.c_double,
                                      ctypes.POINTER(vp), vp, dp, ctypes.c_double, dp, dp, ctypes.c_double,
                                      ctypes.c_double, ctypes.c_double, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.hm_level_dest_map.restype = ctypes.c_int
+        L.hm_level_dest_map.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp]
         L.hm_status_string.restype = ctypes.c_char_p
         L.hm_status_string.argtypes = [ctypes.c_int]
         _lib = L
@@ -353,3 +355,13 @@ def hm_swap_select(U, G: int, M: float, v: float, z_inter, z_intra: torch.Tensor
                               workspace.data_ptr(), workspace.numel() * 8, _stream(stream))
     _check("hm_swap_select", rc)
     return Q, best_pair, best_time
+
+
+def hm_level_dest_map(expert_to_rank: torch.Tensor, G: int, my_rank: int, parent_groups: int, child_groups: int,
+                      dest_map: torch.Tensor, num_dest: torch.Tensor, stream=None):
+    E = expert_to_rank.shape[0]
+    rc = lib().hm_level_dest_map(_dev(expert_to_rank, torch.int32, "expert_to_rank"), E, G, my_rank, parent_groups,
+                                 child_groups, _dev(dest_map, torch.int32, "dest_map"),
+                                 _dev(num_dest, torch.int32, "num_dest"), _stream(stream))
+    _check("hm_level_dest_map", rc)
+    return dest_map, num_dest

@@ -275,6 +275,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
 // Destination table of a receiver stage: one workgroup walks the E experts in chunks of 1024 and
 // numbers the experts placed on `my_rank` with a ballot scan, so local indices ascend with the
 // expert id.
+// Table of one hop for a (parent, child) pair of group cuts: purely elementwise.
+__global__ __launch_bounds__(kPlanThreads) void level_dest_map_kernel(const int32_t *__restrict__ expert_to_rank, int E,
+                                                                       int G, int my_rank, int ranks_per_parent,
+                                                                       int ranks_per_child, int children_per_parent,
+                                                                       int32_t *__restrict__ dest_map,
+                                                                       int32_t *__restrict__ num_dest) {
+  const int e = blockIdx.x * kPlanThreads + threadIdx.x;
+  if (e == 0) *num_dest = children_per_parent;
+  if (e >= E) return;
+  const int g = expert_to_rank[e];
+  int v;
+  if ((unsigned)g >= (unsigned)G) v = -2;
+  else if (g / ranks_per_parent != my_rank / ranks_per_parent) v = -1;
+  else v = (g / ranks_per_child) % children_per_parent;
+  dest_map[e] = v;
+}
+
 __global__ __launch_bounds__(kPlanThreads) void recv_dest_map_kernel(const int32_t *__restrict__ expert_to_rank, int E,
                                                                       int G, int R, int my_rank, int stage,
                                                                       int32_t *__restrict__ dest_map,
@@ -449,6 +466,21 @@ extern "C" hm_status hm_recv_dest_map(const int32_t *expert_to_rank, int32_t E, 
   if (stage != HM_RECV_INTRA_NODE && stage != HM_RECV_LOCAL_EXPERTS) return HM_ERR_LEVEL;
   hipLaunchKernelGGL(hm::recv_dest_map_kernel, dim3(1), dim3(hm::kPlanThreads), 0, (hipStream_t)hip_stream,
                      expert_to_rank, E, G, topo.ranks_per_node, my_rank, (int)stage, dest_map, num_dest);
+  return hm_launch_status();
+}
+
+extern "C" hm_status hm_level_dest_map(const int32_t *expert_to_rank, int32_t E, int32_t G, int32_t my_rank,
+                                       int32_t parent_groups, int32_t child_groups, int32_t *dest_map, int32_t *num_dest,
+                                       void *hip_stream) {
+  if (!expert_to_rank || !dest_map || !num_dest) return HM_ERR_NULL;
+  if (E < 1) return HM_ERR_SHAPE;
+  if (G < 1 || G > 64 || my_rank < 0 || my_rank >= G) return HM_ERR_TOPOLOGY;
+  if (parent_groups < 1 || child_groups < parent_groups || child_groups > G) return HM_ERR_TOPOLOGY;
+  if (child_groups % parent_groups != 0 || G % child_groups != 0) return HM_ERR_TOPOLOGY;
+  const int blocks = (E + hm::kPlanThreads - 1) / hm::kPlanThreads;
+  hipLaunchKernelGGL(hm::level_dest_map_kernel, dim3(blocks), dim3(hm::kPlanThreads), 0, (hipStream_t)hip_stream,
+                     expert_to_rank, E, G, my_rank, G / parent_groups, G / child_groups, child_groups / parent_groups,
+                     dest_map, num_dest);
   return hm_launch_status();
 }
 

@@ -120,6 +120,11 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_combine_mix(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
     assert L.hm_combine_mix(fake, -1, fake, 4, 2, 64, ref, fake, None) == B.HM_ERR_SHAPE
 
+    assert L.hm_level_dest_map(fake, 8, 8, 0, 2, 3, fake, fake, None) == B.HM_ERR_TOPOLOGY      # 2 does not divide 3
+    assert L.hm_level_dest_map(fake, 8, 8, 0, 4, 2, fake, fake, None) == B.HM_ERR_TOPOLOGY      # child coarser than parent
+    assert L.hm_level_dest_map(fake, 8, 8, 8, 1, 2, fake, fake, None) == B.HM_ERR_TOPOLOGY      # rank 8 of 8
+    assert L.hm_level_dest_map(fake, 8, 8, 0, 1, 2, None, fake, None) == B.HM_ERR_NULL
+
     # dimension selection
     i32x = lambda *a: (ctypes.c_int32 * len(a))(*a)
     dbl = lambda *a: (ctypes.c_double * len(a))(*a)

@@ -234,3 +234,112 @@ def test_hierarchical_layer_stage_by_stage(hw, oracle, name, T, H, src_local):
     expect = (w.astype(np.float64) * c[ids].astype(np.float64)).sum(1)[:, None] * W.bf16_bits_to_f64(x)
     # four bf16 roundings on the way (expert output, two merges, final combine), each <= 2^-8 relative
     assert np.all(np.abs(W.bf16_bits_to_f64(out) - expect) <= 4 * 2.0 ** -8 * np.abs(expect) + 1e-30)
+
+
+def test_level_dest_map_parity(hw, oracle):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(91)
+    for _ in range(60):
+        G = int(rng.choice([4, 8, 16, 32, 64, 12]))
+        divs = [u for u in range(1, G + 1) if G % u == 0]
+        parent = int(rng.choice(divs))
+        child = int(rng.choice([u for u in divs if u % parent == 0]))
+        E = int(rng.integers(1, 2500))
+        e2r = rng.integers(0, G, E).astype(np.int32)
+        if E > 3:
+            e2r[2] = G + 4
+        me = int(rng.integers(0, G))
+        dm_d = torch.full((E,), -77, dtype=torch.int32, device="cuda")
+        nd_d = torch.full((1,), -77, dtype=torch.int32, device="cuda")
+        B.hm_level_dest_map(hw.dev(e2r), G, me, parent, child, dm_d, nd_d)
+        dm, nd = oracle.level_dest_map(e2r, G, me, parent, child)
+        assert int(nd_d.item()) == nd and np.array_equal(dm_d.cpu().numpy(), dm), (G, parent, child, E, me)
+
+
+@pytest.mark.parametrize("name,chain,T,H", [("qwen3", [4, 8, 16, 32], 1000, 256), ("dsv3", [2, 8, 32], 800, 512)])
+def test_d_dimensional_exchange_hop_by_hop(hw, oracle, name, chain, T, H):
+    """The paper's 4-level hierarchy (U = [1,4,8,16] on 32 GPUs) and a 3-level one: every hop planned,
+    packed and merged on the GPU through the C ABI, each compared with the oracle on the same hop
+    inputs; at the end every rank holds the one-hop exchange's tokens and the output is the layer's."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS[name]
+    G, K = wl.G, wl.K
+    r = W.make_routing(wl, T=T)
+    ids, w, e2r = r.topk_ids, r.topk_weights, r.expert_to_rank
+    x = W.make_activations(wl, T=T, H=H)
+    c = W.make_expert_scales(wl)
+    e2r_d = hw.dev(e2r)
+    delivered = {}
+
+    def pack(plan, rows_d, total, units):
+        out = torch.zeros((max(total, 1), units), dtype=torch.bfloat16, device="cuda")
+        if total:
+            B.hm_dispatch_pack(rows_d, plan, out[:total])
+        return out[:total]
+
+    def hop(level, rank, tokens, rows_d, ids_d, w_d):
+        parent = 1 if level == 0 else chain[level - 1]
+        child = chain[level]
+        n = tokens.shape[0]
+        dm_d = torch.empty(wl.E, dtype=torch.int32, device="cuda")
+        nd_d = torch.empty(1, dtype=torch.int32, device="cuda")
+        B.hm_level_dest_map(e2r_d, G, rank, parent, child, dm_d, nd_d)
+        nd = int(nd_d.item())
+        dm, nd_ref = oracle.level_dest_map(e2r, G, rank, parent, child)
+        assert nd == nd_ref and np.array_equal(dm_d.cpu().numpy(), dm)
+        h_ids, h_w = ids_d.cpu().numpy(), w_d.cpu().numpy()
+        assert np.array_equal(h_ids, ids[tokens]) and np.array_equal(h_w, w[tokens])       # metadata travelled intact
+        ora = oracle.plan_mapped(h_ids, h_w, dm, nd, True)
+        plan, st, total, host, _, _ = _gpu_plan_mapped(hw, h_ids, h_w, dm_d, nd, True)
+        _assert_mapped_equal(host, st, total, ora, "level %d rank %d" % (level, rank))
+        packed_d = pack(plan, rows_d, total, H)
+        assert np.array_equal(hw.bf16_to_host(packed_d), oracle.dispatch_pack(hw.bf16_to_host(rows_d), ora.row_token))
+        pid_d = pack(plan, ids_d.view(torch.bfloat16).view(n, 2 * K), total, 2 * K).contiguous().view(torch.int32).view(-1, K)
+        pw_d = pack(plan, w_d.view(torch.bfloat16).view(n, 2 * K), total, 2 * K).contiguous().view(torch.float32).view(-1, K)
+        y_d = torch.zeros_like(packed_d)
+        for j in range(nd):
+            a, b = int(ora.dest_offset[j]), int(ora.dest_offset[j + 1])
+            if a == b:
+                continue
+            sub_tokens = tokens[ora.row_token[a:b]]
+            peer = (rank // (G // parent)) * (G // parent) + j * (G // child) + rank % (G // child)
+            sub_rows, sub_ids, sub_w = packed_d[a:b].contiguous(), pid_d[a:b].contiguous(), pw_d[a:b].contiguous()
+            if level == len(chain) - 1:
+                delivered[peer] = sub_tokens
+                dm3_d, nd3 = _gpu_dest_map(hw, e2r, 1, G, peer, LOCAL)
+                dm3, _ = oracle.recv_dest_map(e2r, 1, G, peer, LOCAL)
+                h2i, h2w = sub_ids.cpu().numpy(), sub_w.cpu().numpy()
+                o3 = oracle.plan_mapped(h2i, h2w, dm3, nd3, False)
+                plan3, st3, tot3, host3, _, w3_d = _gpu_plan_mapped(hw, h2i, h2w, dm3_d, nd3, False)
+                _assert_mapped_equal(host3, st3, tot3, o3, "experts rank %d" % peer)
+                xin = hw.bf16_to_host(pack(plan3, sub_rows, tot3, H))
+                yexp = np.zeros_like(xin)
+                for jj, e in enumerate(np.flatnonzero(e2r == peer)):
+                    s3 = slice(o3.dest_offset[jj], o3.dest_offset[jj + 1])
+                    yexp[s3] = W.f32_to_bf16_bits(c[e] * W.bf16_bits_to_f32(xin[s3]))
+                res_d = torch.zeros((b - a, H), dtype=torch.bfloat16, device="cuda")
+                B.hm_combine_mix(hw.to_dev_bf16(yexp), w3_d, plan3, res_d)
+                assert bf16_ulp_distance(hw.bf16_to_host(res_d), oracle.combine_mix(yexp, h2w, o3.slot_row)).max() <= 1
+                y_d[a:b] = res_d
+            else:
+                y_d[a:b] = hop(level + 1, peer, sub_tokens, sub_rows, sub_ids, sub_w)
+        out_d = torch.zeros((n, H), dtype=torch.bfloat16, device="cuda")
+        if level == 0:
+            B.hm_combine(y_d, w_d, plan, out_d)
+            ref = oracle.combine(hw.bf16_to_host(y_d), h_w, ora.slot_row)
+        else:
+            B.hm_combine_mix(y_d, w_d, plan, out_d)
+            ref = oracle.combine_mix(hw.bf16_to_host(y_d), h_w, ora.slot_row)
+        assert bf16_ulp_distance(hw.bf16_to_host(out_d), ref).max() <= 1
+        return out_d
+
+    out_d = hop(0, 5, np.arange(T), hw.to_dev_bf16(x), hw.dev(ids), hw.dev(w))
+    flat = oracle.plan(ids, w, e2r, wl.nodes, wl.ranks_per_node, GPU)
+    for g in range(G):
+        want = flat.row_token[flat.dest_offset[g]:flat.dest_offset[g + 1]]
+        assert np.array_equal(delivered.get(g, np.zeros(0, np.int64)), want), g
+    expect = (w.astype(np.float64) * c[ids].astype(np.float64)).sum(1)[:, None] * W.bf16_bits_to_f64(x)
+    got = W.bf16_bits_to_f64(hw.bf16_to_host(out_d))
+    assert np.all(np.abs(got - expect) <= (len(chain) + 2) * 2.0 ** -8 * np.abs(expect) + 1e-30)
