@@ -430,3 +430,46 @@ def test_plan_is_deterministic(hw, oracle):
         blob = b"".join(np.ascontiguousarray(h[k]).tobytes() for k in sorted(h))
         first = first or blob
         assert blob == first
+
+
+def test_random_shapes_against_the_oracle(hw, oracle):
+    """Seeded sweep over shapes nobody picked by hand: topology, K, E, H (vector and element-wise
+    paths), uneven placements, repeated experts, dropped and invalid slots, all three levels."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(20260)
+    for case in range(40):
+        nodes = int(rng.choice([1, 2, 3, 4, 8]))
+        rpn = int(rng.choice([1, 2, 4, 8]))
+        G = nodes * rpn
+        E = G * int(rng.integers(1, 9)) + int(rng.integers(0, 3))
+        K = int(rng.integers(1, 13))
+        T = int(rng.integers(1, 2600))
+        H = int(rng.choice([8, 24, 64, 100, 520, 1024, 2048, 2056]))
+        ids = rng.integers(0, E, (T, K), dtype=np.int32)
+        if case % 3 == 0:
+            ids[rng.random((T, K)) < 0.1] = -1
+        if case % 4 == 0:
+            ids[rng.integers(0, T), rng.integers(0, K)] = E + 7
+        w = rng.random((T, K), dtype=np.float32) + np.float32(0.02)
+        e2r = rng.integers(0, G, E).astype(np.int32)
+        x = W.f32_to_bf16_bits((rng.random((T, H)) + 0.25).astype(np.float32))
+        level = int(rng.integers(0, 3))
+        ctx = "case %d: %dx%d E=%d K=%d T=%d H=%d level=%d" % (case, nodes, rpn, E, K, T, H, level)
+        print(ctx, flush=True)
+        ora = oracle.plan(ids, w, e2r, nodes, rpn, level)
+        g = hw.GpuPlan(ids, w, e2r, nodes, rpn, level)
+        hw.assert_plan_equal(g, ora, ctx)
+        n = ora.total_rows
+        packed_d = torch.zeros((max(n, 1), H), dtype=torch.bfloat16, device="cuda")
+        B.hm_dispatch_pack(hw.to_dev_bf16(x), g.plan, packed_d[:n])
+        packed = hw.bf16_to_host(packed_d[:n])
+        assert np.array_equal(packed, oracle.dispatch_pack(x, ora.row_token)), ctx
+        out_d = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+        B.hm_combine(packed_d[:n], g.w_d, g.plan, out_d)
+        assert bf16_ulp_distance(hw.bf16_to_host(out_d), oracle.combine(packed, w, ora.slot_row)).max() <= 1, ctx
+        gout = rng.standard_normal((T, H)).astype(np.float32)
+        gy_d = torch.zeros((max(n, 1), H), dtype=torch.float32, device="cuda")
+        B.hm_combine_transpose(hw.dev(gout), g.plan, gy_d[:n])
+        gref = oracle.combine_transpose(gout, ora.row_token, ora.row_weight)
+        assert np.array_equal(gy_d[:n].cpu().numpy().view(np.uint32), gref.view(np.uint32)), ctx
