@@ -473,3 +473,27 @@ def test_random_shapes_against_the_oracle(hw, oracle):
         B.hm_combine_transpose(hw.dev(gout), g.plan, gy_d[:n])
         gref = oracle.combine_transpose(gout, ora.row_token, ora.row_weight)
         assert np.array_equal(gy_d[:n].cpu().numpy().view(np.uint32), gref.view(np.uint32)), ctx
+
+
+def test_dispatch_packs_rows_of_any_element_type(hw, oracle):
+    """hm_dispatch_pack copies bytes: fp32 rows, fp8 / uint8 rows (with their fp32 scale rows) and
+    int32 metadata rows pack through the same call when H is given in 2-byte units."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["dsv3"]
+    T, H = 900, 7168
+    r = W.make_routing(wl, T=T)
+    rng = np.random.default_rng(8)
+    ora = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, NODE)
+    g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, NODE)
+    n = ora.total_rows
+    x32 = rng.standard_normal((T, H)).astype(np.float32)                 # fp32 rows: 2H units
+    x8 = rng.integers(0, 256, (T, H), dtype=np.uint8)                    # one byte per element: H/2 units
+    scales = rng.random((T, H // 128)).astype(np.float32)               # per-128 block scales: 2*(H/128) units
+    for host, units in ((x32, 2 * H), (x8, H // 2), (scales, 2 * (H // 128))):
+        src_d = hw.dev(host).view(torch.bfloat16).view(T, units)
+        out_d = torch.zeros((n, units), dtype=torch.bfloat16, device="cuda")
+        B.hm_dispatch_pack(src_d, g.plan, out_d)
+        got = out_d.view(torch.uint8).cpu().numpy().reshape(n, -1)
+        want = oracle.dispatch_pack(host, ora.row_token).view(np.uint8).reshape(n, -1)
+        assert np.array_equal(got, want), host.dtype
