@@ -78,7 +78,8 @@ typedef struct {
  *                             serves
  *   rank_mask  [T]  optional  bit g set iff some valid slot of the token maps to rank g
  *   node_mask  [T]  optional  bit n set iff some valid slot maps to node n
- *   status     [1]            0, or the last HM_ERR_BAD_ID / HM_ERR_CAPACITY a kernel stored
+ *   status     [1]            0, or HM_ERR_BAD_ID / HM_ERR_CAPACITY as stored by the kernels (the more
+ *                             negative code wins when both occur, whatever the order of the waves)
  *   load_expert [E], load_rank [G], load_node [nodes]   optional, all three or none: when given,
  *                             hm_plan also produces the counts of hm_expert_load, in the same two
  *                             launches (the planner of Section IV needs them every iteration).
