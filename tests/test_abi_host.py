@@ -159,3 +159,10 @@ def test_binding_refuses_cpu_tensors(B):
     ids = torch.zeros((4, 2), dtype=torch.int32)
     with pytest.raises(TypeError):
         B._dev(ids, torch.int32, "topk_ids")
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout == ""

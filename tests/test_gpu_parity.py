@@ -497,3 +497,65 @@ def test_dispatch_packs_rows_of_any_element_type(hw, oracle):
         got = out_d.view(torch.uint8).cpu().numpy().reshape(n, -1)
         want = oracle.dispatch_pack(host, ora.row_token).view(np.uint8).reshape(n, -1)
         assert np.array_equal(got, want), host.dtype
+
+
+def test_step_under_hip_graph_capture(hw, oracle):
+    """The entry points only enqueue kernels (no allocation, no memset, no synchronisation), so a
+    whole step can be captured in a HIP graph and replayed: every replay, with fresh routing and
+    activations copied into the captured buffers, must match the oracle."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["dsv3"]
+    T, H, level = 2048, 1024, NODE
+    cases = []
+    for seed_shift in range(4):
+        import dataclasses
+        r = W.make_routing(dataclasses.replace(wl, seed=500 + seed_shift), T=T)
+        x = W.make_activations(dataclasses.replace(wl, seed=600 + seed_shift), T=T, H=H)
+        cases.append((r, x))
+    r0, x0 = cases[0]
+    ids_d, w_d, e2r_d = hw.dev(r0.topk_ids), hw.dev(r0.topk_weights), hw.dev(r0.expert_to_rank)
+    x_d = hw.to_dev_bf16(x0)
+    plan = B.alloc_plan(T, wl.K, wl.E, wl.nodes, wl.ranks_per_node, level, loads=True)
+    packed_d = torch.zeros((plan.row_capacity, H), dtype=torch.bfloat16, device="cuda")
+    out_d = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
+    gy_d = torch.zeros((plan.row_capacity, H), dtype=torch.float32, device="cuda")
+    gout_d = hw.dev(W.make_output_grads(wl, T=T, H=H))
+    gout = gout_d.cpu().numpy()
+
+    def step():
+        B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan)
+        B.hm_dispatch_pack(x_d, plan, packed_d)
+        B.hm_combine(packed_d, w_d, plan, out_d)
+        B.hm_combine_transpose(gout_d, plan, gy_d)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                              # warm-up outside capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for r, x in cases[1:] + cases[:1]:
+        ids_d.copy_(hw.dev(r.topk_ids))
+        w_d.copy_(hw.dev(r.topk_weights))
+        x_d.copy_(hw.to_dev_bf16(x))
+        packed_d.zero_()
+        out_d.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ora = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        st, total = B.hm_plan_status(plan)
+        assert st == 0 and total == ora.total_rows
+        assert np.array_equal(plan.slot_row.cpu().numpy().reshape(T, wl.K), ora.slot_row)
+        assert np.array_equal(plan.row_token[:total].cpu().numpy(), ora.row_token)
+        packed = hw.bf16_to_host(packed_d[:total])
+        assert np.array_equal(packed, oracle.dispatch_pack(x, ora.row_token))
+        assert bf16_ulp_distance(hw.bf16_to_host(out_d), oracle.combine(packed, r.topk_weights, ora.slot_row)).max() <= 1
+        gref = oracle.combine_transpose(gout, ora.row_token, ora.row_weight)
+        assert np.array_equal(gy_d[:total].cpu().numpy().view(np.uint32), gref.view(np.uint32))
+        le, lr, ln, _ = oracle.expert_load(r.topk_ids, r.expert_to_rank, wl.nodes, wl.ranks_per_node)
+        assert np.array_equal(plan.load_expert.cpu().numpy(), le) and np.array_equal(plan.load_node.cpu().numpy(), ln)
