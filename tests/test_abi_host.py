@@ -166,3 +166,14 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout == ""
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/hiermoe.h must compile as C99 on its own (the boundary is a C ABI, not C++)."""
+    import subprocess
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "hiermoe.h"\n'
+                   "int main(void) { hm_plan_out p; hm_topology t = {1, 1}; (void)p; (void)t;\n"
+                   "  return (int)sizeof(hm_status) > 0 ? 0 : 1; }\n")
+    subprocess.check_call(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                           "-I", os.path.join(ROOT, "include"), str(src)])
