@@ -559,3 +559,21 @@ def test_step_under_hip_graph_capture(hw, oracle):
         assert np.array_equal(gy_d[:total].cpu().numpy().view(np.uint32), gref.view(np.uint32))
         le, lr, ln, _ = oracle.expert_load(r.topk_ids, r.expert_to_rank, wl.nodes, wl.ranks_per_node)
         assert np.array_equal(plan.load_expert.cpu().numpy(), le) and np.array_equal(plan.load_node.cpu().numpy(), ln)
+
+
+def test_table2_duplication_rates_on_the_gpu(hw):
+    """The duplication rates printed in the paper's Table II, from hm_plan's own counts (uniform
+    K-subsets of 256 experts, R groups): within 1.5 points of every printed entry."""
+    import os
+    from paper_2508_09591_amd import binding as B
+    golden = os.path.join(os.path.dirname(__file__), "golden", "table2_duplication.txt")
+    rows = [tuple(int(v) for v in ln.split()) for ln in open(golden) if ln.strip() and not ln.startswith("#")]
+    E, T = 256, 20000
+    topo = {32: (4, 8), 16: (2, 8), 8: (1, 8), 4: (1, 4)}
+    for R, K, pct in rows:
+        ids, w = W.uniform_subset_routing(T, E, K, seed=100 + K)
+        nodes, rpn = topo[R]
+        g = hw.GpuPlan(ids, w, W.contiguous_placement(E, R), nodes, rpn, GPU)
+        assert g.status == 0
+        dup = 100.0 * (1.0 - g.total_rows / (T * K))
+        assert abs(dup - pct) <= 1.5, (R, K, dup, pct)
