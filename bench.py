@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="dsv3")
     ap.add_argument("--level", default=None, help="none|gpu|node (default: the workload's first level)")
+    ap.add_argument("--tokens", type=int, default=None,
+                    help="send path: tokens per batch instead of the workload's own T (size sweeps; named in config)")
     ap.add_argument("--sets", type=int, default=4, help="rotating buffer sets (cold HBM reads)")
     ap.add_argument("--warm-y", action="store_true",
                     help="combine reads the buffer dispatch wrote in the same step (partly cache-resident) instead of "
@@ -88,6 +90,9 @@ def main() -> int:
     if args.path == "table4":
         return run_table4(args)
     wl = W.WORKLOADS[args.workload]
+    if args.tokens and args.tokens != wl.T:
+        import dataclasses
+        wl = dataclasses.replace(wl, T=args.tokens, name="%s@T=%d" % (wl.name, args.tokens))   # no stored traffic figures
     level = LEVELS[args.level] if args.level else wl.levels[0]
     level_name = W.LEVEL_NAMES[level]
     T, K, H, E = wl.T, wl.K, wl.H, wl.E

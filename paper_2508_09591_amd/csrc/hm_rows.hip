@@ -12,7 +12,9 @@
 // multi-KiB items the last round of waves leaves most of the chip idle; 1 KiB items measured
 // 15-20 % faster than 7 KiB ones on the 14 KiB rows of the DeepSeek-V3 shape.  Combine, which is
 // read-heavy, did best with 4 KiB segments (4 vectors per lane) and the loads of up to four rows
-// issued before the first use.  Every row-sized stream is read and written with non-temporal
+// issued before the first use; from about 32 Ki tokens of that shape on, the ramp-up and the
+// tail no longer matter and 7 KiB segments are faster (2.5 % at 32 Ki tokens, 5.5 % at 64 Ki;
+// 1.8 % slower at 8 Ki), so the launcher picks the width from the number of segments.  Every row-sized stream is read and written with non-temporal
 // accesses: rows are touched once per kernel, and output lines left dirty in the caches were
 // measured to slow the next kernel down by about 10 %.
 #include "hm_device.h"
@@ -22,7 +24,9 @@ namespace hm {
 constexpr int kElemThreads = 256;   // element-wise fallback kernels
 constexpr int kCopyThreads = 128;   // dispatch / transpose: 2 waves per workgroup
 constexpr int kCombineThreads = 256;
-constexpr int kCombineVecs = 4;     // combine: 16-byte vectors per lane (4 KiB segments)
+constexpr int kCombineVecs = 4;     // combine: 16-byte vectors per lane (4 KiB segments) ...
+constexpr int kCombineVecsWide = 7; // ... or 7 KiB segments once the launch has this many of them:
+constexpr int64_t kCombineWideMinUnits = 65536;
 constexpr int kCombineRows = 4;     // combine: rows whose loads are in flight together
 
 struct RowParams {
@@ -115,7 +119,7 @@ __device__ __forceinline__ uint64_t merge_slots(int K, int my_row, float my_w, f
 // MIX = false: hm_combine.  MIX = true: hm_combine_mix, the sum times the reciprocal of the sum of
 // the merged weights (added in ascending k of each row's first slot); zero for a row without a
 // valid slot.  (A true division per element made the kernel ALU-bound: 8 divisions per 16 bytes.)
-template <bool MIX>
+template <bool MIX, int U>
 __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
                                                                        int64_t y_rows, const float *__restrict__ topk_weights,
                                                                        u32x4 *__restrict__ out) {
@@ -145,7 +149,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
     inv_wsum = wsum != 0.0f ? 1.0f / wsum : 0.0f;
   }
 
-  constexpr int U = kCombineVecs, R = kCombineRows;
+  constexpr int R = kCombineRows;
   const int v0 = seg * (kWave * U) + lane;   // this lane's vectors: v0, v0+64, ...
   float acc[U][8];
 #pragma unroll
@@ -379,9 +383,17 @@ static hm_status launch_combine(const void *y_bf16, int64_t y_rows, const float 
   p.status = plan->status;
   dim3 grid;
   if (H % 8 == 0 && aligned16(y_bf16) && aligned16(out_bf16)) {
-    if (!grid_for_units(p, H / 8, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL((combine_rows_kernel<MIX>), grid, dim3(kCombineThreads), 0, stream, p, (const u32x4 *)y_bf16,
-                       y_rows, topk_weights, (u32x4 *)out_bf16);
+    const int nvec = H / 8;
+    const int64_t wide_units = (int64_t)T * ((nvec + kWave * kCombineVecsWide - 1) / (kWave * kCombineVecsWide));
+    if (wide_units >= kCombineWideMinUnits) {
+      if (!grid_for_units(p, nvec, kCombineVecsWide, kCombineThreads, grid)) return HM_ERR_SHAPE;
+      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecsWide>), grid, dim3(kCombineThreads), 0, stream, p,
+                         (const u32x4 *)y_bf16, y_rows, topk_weights, (u32x4 *)out_bf16);
+    } else {
+      if (!grid_for_units(p, nvec, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
+      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs>), grid, dim3(kCombineThreads), 0, stream, p,
+                         (const u32x4 *)y_bf16, y_rows, topk_weights, (u32x4 *)out_bf16);
+    }
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
     hipLaunchKernelGGL((combine_elems_kernel<MIX>), grid, dim3(kElemThreads), 0, stream, p, H, (const uint16_t *)y_bf16,

@@ -102,6 +102,15 @@ def test_full_size_layers(hw, oracle, name):
         _run_layer(hw, oracle, wl, wl.T, wl.H, level, check_transpose=(name == "dsv3"))
 
 
+def test_combine_with_wide_segments(hw, oracle):
+    """Launches with at least 65536 seven-KiB segments take the wide combine kernel: a ragged row
+    length (two segments, the second mostly empty) with scaled experts, element by element."""
+    import dataclasses
+    wl = dataclasses.replace(W.WORKLOADS["skew"], name="wide", K=4, E=32, nodes=2, ranks_per_node=4, seed=77)
+    for level in (GPU, NODE):
+        _run_layer(hw, oracle, wl, 33001, 8 * 517, level)
+
+
 def test_full_size_skew_both_placements(hw, oracle):
     import torch
     from paper_2508_09591_amd import binding as B

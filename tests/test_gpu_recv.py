@@ -109,7 +109,8 @@ def test_plan_mapped_parity(hw, oracle, rows, K, E, nd):
         _assert_mapped_equal(host, st, total, ora, "bad entries")
 
 
-@pytest.mark.parametrize("rows,K,H", [(500, 8, 512), (300, 4, 1000), (129, 6, 100), (64, 8, 7168)])
+@pytest.mark.parametrize("rows,K,H", [(500, 8, 512), (300, 4, 1000), (129, 6, 100), (64, 8, 7168),
+                                       (66000, 3, 520)])       # the last one is large enough for the wide segments
 def test_combine_mix_parity(hw, oracle, rows, K, H):
     import torch
     from paper_2508_09591_amd import binding as B
