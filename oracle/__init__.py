@@ -142,6 +142,26 @@ def combine(y_bf16: np.ndarray, topk_weights, slot_row) -> np.ndarray:
     return out
 
 
+def combine_f32(y_f32: np.ndarray, topk_weights, slot_row) -> np.ndarray:
+    """out[t] = float32(sum_k w[t,k] * Y[slot_row[t,k]]) in binary64; y and out are float32."""
+    lib = _load()
+    y = _c(y_f32, np.float32)
+    w = _c(topk_weights, np.float32)
+    sr = _c(slot_row, np.int32)
+    T, K = sr.shape
+    H = y.shape[1]
+    out = np.empty((T, H), np.float32)
+    if out.size == 0:
+        return out
+    if y.shape[0] == 0:
+        y = np.zeros((1, H), np.float32)     # never read: every slot_row is negative
+    rc = lib.hmo_combine_f32(_p(y), ctypes.c_int64(y.shape[0]), _p(w), _p(sr), ctypes.c_int64(T), ctypes.c_int32(K),
+                             ctypes.c_int64(H), _p(out))
+    if rc != 0:
+        raise ValueError("hmo_combine_f32: argument error %d" % rc)
+    return out
+
+
 def combine_transpose(gout: np.ndarray, row_token, row_weight) -> np.ndarray:
     """gy[row] = row_weight[row] * gout[row_token[row]] (fp32)."""
     lib = _load()

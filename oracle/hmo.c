@@ -230,6 +230,32 @@ int hmo_combine(const uint16_t *y, int64_t y_rows, const float *topk_weights, co
 }
 
 /*
+ * hmo_combine_f32 -- hmo_combine for rows kept in binary32 (the element width of a row is free in
+ * the paper: its cost model carries it as the `v` bytes per element of Section II-B):
+ *     out[t][j] = (float)( sum_k  w[t,k] * Y[slot_row[t,k]][j] ),   sum in binary64, ascending k.
+ * Every product of two binary32 values is exact in binary64; the K-term sum carries an error of at
+ * most K * 2^-53 * sum_k |w*Y| before the single rounding to binary32 (K * 2^-29 of a binary32 ulp
+ * at that magnitude, far inside the kernel tolerance).
+ */
+int hmo_combine_f32(const float *y, int64_t y_rows, const float *topk_weights, const int32_t *slot_row,
+                    int64_t T, int32_t K, int64_t H, float *out)
+{
+    if (!y || !topk_weights || !slot_row || !out || T < 0 || K <= 0 || H <= 0) return HMO_ERR_ARG;
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t j = 0; j < H; ++j) {
+            double acc = 0.0;
+            for (int32_t k = 0; k < K; ++k) {
+                const int64_t row = slot_row[t * K + k];
+                if (row < 0) continue;
+                if (row >= y_rows) return HMO_ERR_ARG;
+                acc += (double)topk_weights[t * K + k] * (double)y[row * H + j];
+            }
+            out[t * H + j] = (float)acc;
+        }
+    return HMO_OK;
+}
+
+/*
  * hmo_combine_transpose -- adjoint of hmo_combine with respect to Y: the gradient of packed row
  * `row` is the row's aggregated router weight times the output gradient of its token,
  *     gy[row][j] = row_weight[row] * gout[row_token[row]][j]     (one binary32 multiply).

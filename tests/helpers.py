@@ -155,3 +155,25 @@ def brute_plan_mapped(ids, w, dest_map, num_dest, dedup):
         mask[i] |= 1 << dest(i, k)
     return dict(dest_count=dest_count, row_token=[r[1] for r in rows], slot_row=slot_row, slot_keep=slot_keep,
                 row_weight=row_weight, dest_mask=mask)
+
+
+def exact_round_to_f32(q: Fraction) -> float:
+    """Nearest binary32 value of the rational q (normal range only), ties to even, in integer
+    arithmetic: no floating-point rounding involved."""
+    if q == 0:
+        return 0.0
+    sign = -1 if q < 0 else 1
+    a = -q if q < 0 else q
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1
+    assert Fraction(2) ** e <= a < Fraction(2) ** (e + 1) and -126 <= e <= 127
+    scaled = a / Fraction(2) ** (e - 23)                  # in [2^23, 2^24)
+    n, rem = divmod(scaled.numerator, scaled.denominator)
+    twice = 2 * rem
+    if twice > scaled.denominator or (twice == scaled.denominator and (n & 1)):
+        n += 1
+    v = Fraction(n) * Fraction(2) ** (e - 23)
+    out = float(v)                                        # exact: at most 24 significant bits
+    assert Fraction(out) == v
+    return sign * out

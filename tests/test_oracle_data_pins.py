@@ -10,7 +10,7 @@ from fractions import Fraction
 import numpy as np
 import pytest
 
-from helpers import GPU, NODE, NONE, bf16_ulp_distance, exact_round_to_bf16
+from helpers import GPU, NODE, NONE, bf16_ulp_distance, exact_round_to_bf16, exact_round_to_f32
 from paper_2508_09591_amd import workloads as W
 
 
@@ -118,6 +118,70 @@ def test_combine_level_none_is_plain_moe_weighted_sum(oracle):
     # einsum's fp64 summation order may differ in the last bit of the double: allow 1 ulp there
     assert bf16_ulp_distance(out[:16], ref_bits).max() <= 1
     assert np.abs(W.bf16_bits_to_f64(out) - ref).max() <= 2.0 ** -8 * np.abs(ref).max()
+
+
+# ---- combine on binary32 rows ---------------------------------------------------------------------
+def test_exact_f32_rounding_helper():
+    assert exact_round_to_f32(Fraction(1, 3)) == float(np.float32(1.0) / np.float32(3.0))
+    assert exact_round_to_f32(Fraction(1) + Fraction(1, 2 ** 24)) == 1.0                  # tie -> even
+    assert exact_round_to_f32(Fraction(1) + Fraction(3, 2 ** 24)) == 1.0 + 2.0 ** -22      # tie -> even (up)
+    assert exact_round_to_f32(-(Fraction(1) + Fraction(1, 2 ** 24) + Fraction(1, 2 ** 60))) == -(1.0 + 2.0 ** -23)
+
+
+def test_combine_f32_exact_rational_small(oracle):
+    rng = np.random.default_rng(31)
+    T, K, H, E = 6, 3, 5, 6
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)
+    w = rng.random((T, K), dtype=np.float32)
+    e2r = np.array([0, 0, 1, 1, 2, 3], np.int32)
+    for level in (NONE, GPU, NODE):
+        p = oracle.plan(ids, w, e2r, 2, 2, level)
+        y = (rng.standard_normal((p.total_rows, H)) * 3).astype(np.float32)
+        out = oracle.combine_f32(y, w, p.slot_row)
+        assert out.dtype == np.float32 and out.shape == (T, H)
+        for t in range(T):
+            for j in range(H):
+                q = sum(Fraction(float(w[t, k])) * Fraction(float(y[p.slot_row[t, k], j])) for k in range(K))
+                assert float(out[t, j]) == exact_round_to_f32(q), (level, t, j)
+
+
+def test_combine_f32_accumulates_beyond_binary32(oracle):
+    """1 + 2^-24 + 2^-30: a binary32 accumulator stops at the tie 1 + 2^-24 -> 1 and then loses the
+    last term; the exact sum lies above the tie and rounds up."""
+    ids = np.array([[0, 1, 2]], np.int32)
+    e2r = np.array([0, 1, 2], np.int32)
+    w = np.array([[1.0, 2.0 ** -24, 2.0 ** -30]], np.float32)
+    p = oracle.plan(ids, w, e2r, 3, 1, GPU)
+    assert p.total_rows == 3
+    y = np.ones((3, 4), np.float32)
+    out = oracle.combine_f32(y, w, p.slot_row)
+    assert out.tolist() == [[1.0 + 2.0 ** -23] * 4]
+    w[0, 2] = 0.0                                       # the exact tie: to even, down
+    assert oracle.combine_f32(y, w, p.slot_row).tolist() == [[1.0] * 4]
+    w[0, 1] = -(2.0 ** -25)                             # 1 - 2^-25: a tie below 1 (spacing 2^-24), to even = 1
+    assert oracle.combine_f32(y, w, p.slot_row).tolist() == [[1.0] * 4]
+
+
+def test_combine_f32_is_plain_weighted_sum_and_agrees_with_bf16_combine(oracle):
+    wl = W.WORKLOADS["qwen3"]
+    r = W.make_routing(wl, T=200)
+    rng = np.random.default_rng(19)
+    for level in (NONE, NODE):
+        p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        yb = W.f32_to_bf16_bits(rng.standard_normal((p.total_rows, 48)).astype(np.float32))
+        y = W.bf16_bits_to_f32(yb)
+        out = oracle.combine_f32(y, r.topk_weights, p.slot_row)
+        ref = np.einsum("tk,tkh->th", r.topk_weights.astype(np.float64), y.astype(np.float64)[p.slot_row])
+        assert np.abs(out.astype(np.float64) - ref).max() <= 2.0 ** -23 * np.abs(ref).max()
+        # the same rows through the bf16 path: its result is this one rounded once more to bf16
+        ob = oracle.combine(yb, r.topk_weights, p.slot_row)
+        assert bf16_ulp_distance(ob, W.f32_to_bf16_bits(out)).max() <= 1
+    # dropped slots contribute nothing
+    sr = p.slot_row.copy()
+    sr[:, 1:] = -1
+    out = oracle.combine_f32(y, r.topk_weights, sr)
+    want = (r.topk_weights[:, :1].astype(np.float64) * y.astype(np.float64)[sr[:, 0]]).astype(np.float32)
+    assert np.array_equal(out, want)
 
 
 @pytest.mark.parametrize("name", ["tiny", "dsv3"])
