@@ -64,6 +64,7 @@ def main() -> int:
                     help="call hm_expert_load as its own pair of launches instead of letting hm_plan fill the loads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
+    ap.add_argument("--with-f32", action="store_true", help="also time hm_combine_f32 on fp32 rows (stderr only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB device copy a few times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -207,6 +208,24 @@ def main() -> int:
         tb = (1 + c) * T * 4 * H
         log("hm_combine_transpose: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
             % (tms, tb / (tms * 1e-3) / 1e9, 100 * tb / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
+
+    if args.with_f32:
+        y32 = torch.randn((total_rows, H), dtype=torch.float32, device="cuda")
+        o32 = torch.empty((T, H), dtype=torch.float32, device="cuda")
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        with torch.cuda.stream(stream):
+            for i in range(args.warmup):
+                B.hm_combine_f32(y32, w_d, plan, o32, stream=stream)
+            for a, b in evs:
+                a.record(stream)
+                B.hm_combine_f32(y32, w_d, plan, o32, stream=stream)
+                b.record(stream)
+        torch.cuda.synchronize()
+        tms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+        tb = (1 + c) * T * 4 * H
+        log("hm_combine_f32: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
+            % (tms, tb / (tms * 1e-3) / 1e9, 100 * tb / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
+        del y32, o32
 
     if args.calibrate_copy:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)      # 1 GiB

@@ -150,6 +150,17 @@ hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weigh
                      int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream);
 
 /*
+ * hm_combine_f32 -- hm_combine for rows kept in binary32 (the element width is free in the paper:
+ * the `v` bytes per element of the cost model in Section II-B):
+ *     out[t,:] = sum_k topk_weights[t,k] * y[slot_row[t,k], :],  an fp32 fma chain over the token's
+ * distinct rows in ascending k of their first slot, merged weights as in hm_combine; the result
+ * differs from the exact sum by at most 2K * 2^-24 * sum_k |w y|.  y [y_rows,H] fp32, out [T,H]
+ * fp32.  Fast path needs H % 4 == 0 and 16-byte aligned y / out.  Errors as hm_combine.
+ */
+hm_status hm_combine_f32(const float *y, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
+                         int32_t H, const hm_plan_out *plan, float *out, void *hip_stream);
+
+/*
  * hm_combine_transpose -- adjoint of hm_combine with respect to y (the gradient that travels
  * back through the dispatch layout): for every kept slot,
  *     gy[row,:] = row_weight[row] * gout[t,:],   row = slot_row[t,k]   (one fp32 multiply).

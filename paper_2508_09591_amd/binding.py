@@ -26,7 +26,7 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_combine_transpose", "hm_expert_load", "hm_status_string", "hm_recv_dest_map",
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
-           "hm_swap_select", "hm_level_dest_map")
+           "hm_swap_select", "hm_level_dest_map", "hm_combine_f32")
 
 
 class hm_topology(ctypes.Structure):
@@ -72,6 +72,8 @@ def lib():
         L.hm_dispatch_pack.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
         L.hm_combine.restype = ctypes.c_int
         L.hm_combine.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
+        L.hm_combine_f32.restype = ctypes.c_int
+        L.hm_combine_f32.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
         L.hm_combine_transpose.restype = ctypes.c_int
         L.hm_combine_transpose.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
         L.hm_expert_load.restype = ctypes.c_int
@@ -234,6 +236,14 @@ def hm_combine(y: torch.Tensor, topk_weights: torch.Tensor, plan: Plan, out: tor
     rc = lib().hm_combine(_dev(y, torch.bfloat16, "y"), y.shape[0], _dev(topk_weights, torch.float32, "topk_weights"),
                           T, plan.K, H, plan.ref(), _dev(out, torch.bfloat16, "out"), _stream(stream))
     _check("hm_combine", rc)
+    return out
+
+
+def hm_combine_f32(y: torch.Tensor, topk_weights: torch.Tensor, plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
+    T, H = out.shape
+    rc = lib().hm_combine_f32(_dev(y, torch.float32, "y"), y.shape[0], _dev(topk_weights, torch.float32, "topk_weights"),
+                              T, plan.K, H, plan.ref(), _dev(out, torch.float32, "out"), _stream(stream))
+    _check("hm_combine_f32", rc)
     return out
 
 

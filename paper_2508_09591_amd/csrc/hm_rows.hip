@@ -116,10 +116,51 @@ __device__ __forceinline__ uint64_t merge_slots(int K, int my_row, float my_w, f
   return __ballot(first);
 }
 
+// Element type of a row as the combine kernels see it: how many values a 16-byte vector holds,
+// how they enter the fp32 fma chain and how the fp32 sums are stored.
+struct RowBf16 {
+  typedef uint16_t elem;
+  static constexpr int kPerVec = 8;
+  static __device__ __forceinline__ void fma_into(float *acc, float a, u32x4 r) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc[2 * e] = __builtin_fmaf(a, bf16_lo(r[e]), acc[2 * e]);
+      acc[2 * e + 1] = __builtin_fmaf(a, bf16_hi(r[e]), acc[2 * e + 1]);
+    }
+  }
+  static __device__ __forceinline__ u32x4 pack(const float *acc) {
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[2 * e], acc[2 * e + 1]);
+    return o;
+  }
+  static __device__ __forceinline__ float widen(elem v) { return __builtin_bit_cast(float, (uint32_t)v << 16); }
+  static __device__ __forceinline__ elem narrow(float f) { return (elem)f32_to_bf16(f); }
+};
+struct RowF32 {
+  typedef float elem;
+  static constexpr int kPerVec = 4;
+  static __device__ __forceinline__ void fma_into(float *acc, float a, u32x4 r) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t w = r[e];   // a copy first: a bit cast applied to the vector element itself reads element 0
+      acc[e] = __builtin_fmaf(a, __builtin_bit_cast(float, w), acc[e]);
+    }
+  }
+  static __device__ __forceinline__ u32x4 pack(const float *acc) {
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = __builtin_bit_cast(uint32_t, acc[e]);
+    return o;
+  }
+  static __device__ __forceinline__ float widen(elem v) { return v; }
+  static __device__ __forceinline__ elem narrow(float f) { return f; }
+};
+
 // MIX = false: hm_combine.  MIX = true: hm_combine_mix, the sum times the reciprocal of the sum of
 // the merged weights (added in ascending k of each row's first slot); zero for a row without a
 // valid slot.  (A true division per element made the kernel ALU-bound: 8 divisions per 16 bytes.)
-template <bool MIX, int U>
+template <bool MIX, int U, typename ROW>
 __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
                                                                        int64_t y_rows, const float *__restrict__ topk_weights,
                                                                        u32x4 *__restrict__ out) {
@@ -151,11 +192,12 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
 
   constexpr int R = kCombineRows;
   const int v0 = seg * (kWave * U) + lane;   // this lane's vectors: v0, v0+64, ...
-  float acc[U][8];
+  constexpr int E = ROW::kPerVec;
+  float acc[U][E];
 #pragma unroll
   for (int i = 0; i < U; ++i)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[i][e] = 0.0f;
+    for (int e = 0; e < E; ++e) acc[i][e] = 0.0f;
 
   while (todo) {
     // issue the loads of up to R rows, then consume them in the same (ascending k) order
@@ -183,12 +225,7 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
     for (int j = 0; j < R; ++j) {
       if (have[j]) {
 #pragma unroll
-        for (int i = 0; i < U; ++i)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            acc[i][2 * e] = __builtin_fmaf(a[j], bf16_lo(r[j][i][e]), acc[i][2 * e]);
-            acc[i][2 * e + 1] = __builtin_fmaf(a[j], bf16_hi(r[j][i][e]), acc[i][2 * e + 1]);
-          }
+        for (int i = 0; i < U; ++i) ROW::fma_into(acc[i], a[j], r[j][i]);
       }
     }
   }
@@ -198,22 +235,20 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
     if (v0 + i * kWave < p.nvec) {
       if (MIX) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[i][e] = acc[i][e] * inv_wsum;
+        for (int e = 0; e < E; ++e) acc[i][e] = acc[i][e] * inv_wsum;
       }
-      u32x4 o;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = pack_bf16x2(acc[i][2 * e], acc[i][2 * e + 1]);
-      store_stream(dst + v0 + i * kWave, o);
+      store_stream(dst + v0 + i * kWave, ROW::pack(acc[i]));
     }
   }
 }
 
 // Any H / alignment: one thread per (token, element); same merge order and the same fma chain
 // as the vector kernel, so both give identical bits.
-template <bool MIX>
-__global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p, int32_t H, const uint16_t *__restrict__ y,
+template <bool MIX, typename ROW>
+__global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p, int32_t H,
+                                                                    const typename ROW::elem *__restrict__ y,
                                                                     int64_t y_rows, const float *__restrict__ topk_weights,
-                                                                    uint16_t *__restrict__ out) {
+                                                                    typename ROW::elem *__restrict__ out) {
   const int64_t i = (int64_t)blockIdx.x * kElemThreads + threadIdx.x;
   if (i >= (int64_t)p.T * H) return;
   const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
@@ -233,12 +268,11 @@ __global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p
     float agg = 0.0f;
     for (int k1 = 0; k1 < p.K; ++k1)
       if (rows[k1] == row) agg = agg + w[k1];
-    const float yv = __builtin_bit_cast(float, (uint32_t)y[(int64_t)row * H + j] << 16);
-    acc = __builtin_fmaf(agg, yv, acc);
+    acc = __builtin_fmaf(agg, ROW::widen(y[(int64_t)row * H + j]), acc);
     wsum = wsum + agg;
   }
   if (MIX) acc = acc * (wsum != 0.0f ? 1.0f / wsum : 0.0f);   // same reciprocal-multiply as the vector kernel
-  out[i] = (uint16_t)f32_to_bf16(acc);
+  out[i] = ROW::narrow(acc);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -365,15 +399,16 @@ extern "C" hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, 
   return hm_launch_status();
 }
 
-template <bool MIX>
-static hm_status launch_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
-                                int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
+template <bool MIX, typename ROW>
+static hm_status launch_combine(const void *y, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
+                                int32_t H, const hm_plan_out *plan, void *out, void *hip_stream) {
   using namespace hm;
+  typedef typename ROW::elem elem;
   hm_status st = check_rows_args(T, K, H, plan, false);
   if (st != HM_OK) return st;
   if (y_rows < 0) return HM_ERR_SHAPE;
   if (T == 0) return HM_OK;
-  if (!topk_weights || !out_bf16 || (!y_bf16 && y_rows > 0)) return HM_ERR_NULL;
+  if (!topk_weights || !out || (!y && y_rows > 0)) return HM_ERR_NULL;
   hipStream_t stream = (hipStream_t)hip_stream;
   RowParams p;
   p.T = T;
@@ -382,34 +417,39 @@ static hm_status launch_combine(const void *y_bf16, int64_t y_rows, const float 
   p.slot_keep = plan->slot_keep;
   p.status = plan->status;
   dim3 grid;
-  if (H % 8 == 0 && aligned16(y_bf16) && aligned16(out_bf16)) {
-    const int nvec = H / 8;
+  if (H % ROW::kPerVec == 0 && aligned16(y) && aligned16(out)) {
+    const int nvec = H / ROW::kPerVec;
     const int64_t wide_units = (int64_t)T * ((nvec + kWave * kCombineVecsWide - 1) / (kWave * kCombineVecsWide));
     if (wide_units >= kCombineWideMinUnits) {
       if (!grid_for_units(p, nvec, kCombineVecsWide, kCombineThreads, grid)) return HM_ERR_SHAPE;
-      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecsWide>), grid, dim3(kCombineThreads), 0, stream, p,
-                         (const u32x4 *)y_bf16, y_rows, topk_weights, (u32x4 *)out_bf16);
+      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecsWide, ROW>), grid, dim3(kCombineThreads), 0, stream, p,
+                         (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
     } else {
       if (!grid_for_units(p, nvec, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
-      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs>), grid, dim3(kCombineThreads), 0, stream, p,
-                         (const u32x4 *)y_bf16, y_rows, topk_weights, (u32x4 *)out_bf16);
+      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, ROW>), grid, dim3(kCombineThreads), 0, stream, p,
+                         (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
     }
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL((combine_elems_kernel<MIX>), grid, dim3(kElemThreads), 0, stream, p, H, (const uint16_t *)y_bf16,
-                       y_rows, topk_weights, (uint16_t *)out_bf16);
+    hipLaunchKernelGGL((combine_elems_kernel<MIX, ROW>), grid, dim3(kElemThreads), 0, stream, p, H, (const elem *)y,
+                       y_rows, topk_weights, (elem *)out);
   }
   return hm_launch_status();
 }
 
 extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
                                 int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
-  return launch_combine<false>(y_bf16, y_rows, topk_weights, T, K, H, plan, out_bf16, hip_stream);
+  return launch_combine<false, hm::RowBf16>(y_bf16, y_rows, topk_weights, T, K, H, plan, out_bf16, hip_stream);
+}
+
+extern "C" hm_status hm_combine_f32(const float *y, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
+                                    int32_t H, const hm_plan_out *plan, float *out, void *hip_stream) {
+  return launch_combine<false, hm::RowF32>(y, y_rows, topk_weights, T, K, H, plan, out, hip_stream);
 }
 
 extern "C" hm_status hm_combine_mix(const void *y_bf16, int64_t y_rows, const float *row_weights, int32_t T, int32_t K,
                                     int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
-  return launch_combine<true>(y_bf16, y_rows, row_weights, T, K, H, plan, out_bf16, hip_stream);
+  return launch_combine<true, hm::RowBf16>(y_bf16, y_rows, row_weights, T, K, H, plan, out_bf16, hip_stream);
 }
 
 extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,

@@ -21,7 +21,7 @@ def B():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "hiermoe.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(hm_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(hm_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_function(B):
@@ -93,6 +93,9 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_combine(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
     assert L.hm_combine(fake, 8, fake, 4, 0, 64, ref, fake, None) == B.HM_ERR_SHAPE
     assert L.hm_combine(fake, 8, fake, 4, 2, 64, ref, None, None) == B.HM_ERR_NULL
+    assert L.hm_combine_f32(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
+    assert L.hm_combine_f32(fake, -2, fake, 4, 2, 64, ref, fake, None) == B.HM_ERR_SHAPE
+    assert L.hm_combine_f32(fake, 8, fake, 0, 2, 64, ref, fake, None) == B.HM_OK          # T = 0: nothing to do
     assert L.hm_combine_transpose(None, 4, 2, 64, ref, fake, 8, None) == B.HM_ERR_NULL
     assert L.hm_combine_transpose(fake, 4, 2, -5, ref, fake, 8, None) == B.HM_ERR_SHAPE
     assert L.hm_expert_load(fake, None, 4, 2, 8, topo, fake, fake, fake, None, None) == B.HM_ERR_NULL

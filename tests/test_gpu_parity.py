@@ -508,6 +508,40 @@ def test_dispatch_packs_rows_of_any_element_type(hw, oracle):
         assert np.array_equal(got, want), host.dtype
 
 
+@pytest.mark.parametrize("name,T,H", [("tiny", 1024, 256), ("qwen3", 1500, 2048), ("dsv3", 700, 7168),
+                                      ("skew", 2049, 1030), ("skew", 300, 77)])
+def test_combine_on_binary32_rows(hw, oracle, name, T, H):
+    """hm_combine_f32 against the oracle's binary64 sum: within the bound of a K-term fp32 fma
+    chain with merged weights, 2K * 2^-24 * sum_k |w y| (vector kernel, the ragged-H vector case
+    and the element-wise kernel for H % 4 != 0)."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS[name]
+    r = W.make_routing(wl, T=T)
+    rng = np.random.default_rng(T + H)
+    for level in (NONE, GPU, NODE):
+        ctx = "f32 %s T=%d H=%d level=%s" % (name, T, H, LEVEL[level])
+        print("case:", ctx, flush=True)
+        ora = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        y = rng.standard_normal((ora.total_rows, H)).astype(np.float32)
+        out_d = torch.full((T, H), float("nan"), dtype=torch.float32, device="cuda")
+        B.hm_combine_f32(hw.dev(y), g.w_d, g.plan, out_d)
+        got = out_d.cpu().numpy()
+        ref = oracle.combine_f32(y, r.topk_weights, ora.slot_row)
+        mag = np.einsum("tk,tkh->th", np.abs(r.topk_weights).astype(np.float64), np.abs(y).astype(np.float64)[ora.slot_row])
+        err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+        assert (err <= 2 * wl.K * 2.0 ** -24 * mag + 1e-45).all(), (ctx, float((err / np.maximum(mag, 1e-30)).max()))
+        assert float((got == ref).mean()) > 0.25, ctx         # a good share of the elements round identically
+        st, _ = B.hm_plan_status(g.plan)
+        assert st == 0
+    # a row index beyond the caller's buffer is skipped and flagged, as in hm_combine
+    out_d.fill_(float("nan"))
+    B.hm_combine_f32(hw.dev(y)[:ora.total_rows - 3], g.w_d, g.plan, out_d)
+    st, _ = B.hm_plan_status(g.plan)
+    assert st == B.HM_ERR_CAPACITY and not torch.isnan(out_d).any()
+
+
 def test_step_under_hip_graph_capture(hw, oracle):
     """The entry points only enqueue kernels (no allocation, no memset, no synchronisation), so a
     whole step can be captured in a HIP graph and replayed: every replay, with fresh routing and
