@@ -64,6 +64,8 @@ def main() -> int:
                     help="call hm_expert_load as its own pair of launches instead of letting hm_plan fill the loads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
+    ap.add_argument("--no-warm-leg", action="store_true",
+                    help="skip the extra warm (single buffer set) timing, so that a kernel trace holds cold launches only")
     ap.add_argument("--with-f32", action="store_true", help="also time hm_combine_f32 on fp32 rows (stderr only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB device copy a few times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -175,15 +177,17 @@ def main() -> int:
     # the same two kernels back to back on ONE buffer set (inputs may sit in the 256 MB Infinity
     # Cache): reported beside the cold figures, never used for `value` or the roofline fraction
     wev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for e in wev:
+    for e in (wev if not args.no_warm_leg else []):
         e[0].record(stream)
         B.hm_dispatch_pack(xs[0], plan, packs[0], stream=stream)
         e[1].record(stream)
         B.hm_combine(packs[0], w_d, plan, outs[0], stream=stream)
         e[2].record(stream)
     torch.cuda.synchronize()
-    warm_ms = {"hm_dispatch_pack": sorted(e[0].elapsed_time(e[1]) for e in wev)[len(wev) // 2],
-               "hm_combine": sorted(e[1].elapsed_time(e[2]) for e in wev)[len(wev) // 2]}
+    warm_ms = {"hm_dispatch_pack": None, "hm_combine": None}
+    if not args.no_warm_leg:
+        warm_ms = {"hm_dispatch_pack": sorted(e[0].elapsed_time(e[1]) for e in wev)[len(wev) // 2],
+                   "hm_combine": sorted(e[1].elapsed_time(e[2]) for e in wev)[len(wev) // 2]}
 
     # correctness of what was timed: identity experts + weights summing to 1 -> output == input
     assert torch.equal(outs[(args.steps - 1) % nsets], xs[(args.steps - 1) % nsets]), "round trip failed"
@@ -198,7 +202,7 @@ def main() -> int:
     for n in ("hm_dispatch_pack", "hm_combine"):
         gbs = alg_bytes[n] / (avg_ms[n] * 1e-3) / 1e9
         kern[n] = {"avg_ms": round(avg_ms[n], 5), "median_ms": round(med_ms[n], 5), "min_ms": round(min_ms[n], 5),
-                   "warm_single_set_median_ms": round(warm_ms[n], 5), "alg_bytes": int(alg_bytes[n]),
+                   "warm_single_set_median_ms": None if warm_ms[n] is None else round(warm_ms[n], 5), "alg_bytes": int(alg_bytes[n]),
                    "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
                    "traffic": measured_traffic(wl.name, level_name, n)}
         if kern[n]["traffic"]:      # HBM bytes the counters saw per launch over this run's launch time
@@ -207,7 +211,8 @@ def main() -> int:
     pair_ms = avg_ms["hm_dispatch_pack"] + avg_ms["hm_combine"]
     pair_gbs = (alg_bytes["hm_dispatch_pack"] + alg_bytes["hm_combine"]) / (pair_ms * 1e-3) / 1e9
     log("per-call (HIP events, avg/median/min ms): " + ", ".join("%s %.4f/%.4f/%.4f" % (n, avg_ms[n], med_ms[n], min_ms[n]) for n in names))
-    log("warm, one buffer set (median ms): dispatch %.4f, combine %.4f" % (warm_ms["hm_dispatch_pack"], warm_ms["hm_combine"]))
+    if not args.no_warm_leg:
+        log("warm, one buffer set (median ms): dispatch %.4f, combine %.4f" % (warm_ms["hm_dispatch_pack"], warm_ms["hm_combine"]))
     log("dispatch+combine: %.4f ms -> %.1f GB/s algorithmic = %.1f%% of %.0f GB/s; %.2f M tokens/s (pair only)"
         % (pair_ms, pair_gbs, 100 * pair_gbs / HBM_PEAK_GBS, HBM_PEAK_GBS, T / (pair_ms * 1e-3) / 1e6))
 
