@@ -251,14 +251,25 @@ def main() -> int:
             % (tms, tb / (tms * 1e-3) / 1e9, 100 * tb / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
         del y32, o32
 
-    if args.calibrate_copy:
+    # ---- context for the roofline fraction: the runtime's own device-to-device copy of 1 GiB -------
+    # (also the known-size launch the rocprofv3 counter runs are scaled by: --calibrate-copy)
+    copy_ref = None
+    if args.calibrate_copy or not args.no_warm_leg:
         src = torch.empty(1 << 29, dtype=torch.bfloat16, device="cuda").fill_(1.0)      # 1 GiB
         dst = torch.empty_like(src)
+        cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
         with torch.cuda.stream(stream):
-            for _ in range(5):
+            dst.copy_(src)
+            for a, b in cev:
+                a.record(stream)
                 dst.copy_(src)
+                b.record(stream)
         torch.cuda.synchronize()
-        log("calibration: 5 plain copies of %d bytes launched" % (src.numel() * 2))
+        cms = sorted(a.elapsed_time(b) for a, b in cev)[len(cev) // 2]
+        cgbs = 2 * src.numel() * 2 / (cms * 1e-3) / 1e9
+        copy_ref = {"what": "torch copy_ of 1 GiB, device to device (1 read + 1 write stream)", "median_ms": round(cms, 4),
+                    "achieved_GBps": round(cgbs, 1), "frac": round(cgbs / HBM_PEAK_GBS, 4)}
+        log("reference: plain 1 GiB device copy %.4f ms -> %.1f GB/s = %.1f%% of peak" % (cms, cgbs, 100 * cgbs / HBM_PEAK_GBS))
         del src, dst
 
     # ---- the oracle on this machine's host cores (reported baseline, not the target) ---------------
@@ -310,6 +321,7 @@ def main() -> int:
         "pair": {"ms": round(pair_ms, 5), "achieved_GBps": round(pair_gbs, 1), "frac": round(pair_gbs / HBM_PEAK_GBS, 4),
                  "tokens_per_s": round(T / (pair_ms * 1e-3), 1)},
         "plan_ms": round(avg_ms["hm_plan"], 5),
+        "device_copy_reference": copy_ref,
         "expert_load_ms": None if fused else round(avg_ms["hm_expert_load"], 5),
     }
     print(json.dumps(result), flush=True)

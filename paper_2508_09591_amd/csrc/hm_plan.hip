@@ -9,6 +9,10 @@
 //   plan_count_kernel  per-workgroup, per-destination counts of kept slots -> workspace
 //   plan_write_kernel  every workgroup re-reads the (small) count matrix to get its own base
 //                      rows and the destination totals, then writes the index maps.
+// Re-reading the matrix costs workgroups^2 * destinations loads in total, so beyond
+// kPlanScanMinEntries entries a third launch in between (plan_scan_kernel, one workgroup per
+// destination) turns the matrix into exclusive prefixes plus a row of totals and the write
+// kernel reads just its own row: linear in the number of slots at any size.
 // Both first stage the rank and destination of their 1024 slots, plus a halo of K-1 slots on
 // either side (the rest of the first and last token), in LDS: each expert id is looked up once
 // and all "same destination as an earlier / later slot of my token" questions become LDS reads.
@@ -21,6 +25,7 @@ constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kPlanHalo = 63;                              // K - 1 <= 63
 constexpr int kPlanStaged = kPlanThreads + 2 * kPlanHalo;
 constexpr int kPlanHist = 8192;                            // experts histogrammed in LDS for the fused loads
+constexpr int64_t kPlanScanMinEntries = 16384;             // count-matrix entries from which the scan launch pays
 
 struct PlanParams {
   const int32_t *ids;
@@ -29,8 +34,9 @@ struct PlanParams {
   const int32_t *dest_map;  // non-null: destinations come from this table (hm_plan_mapped)
   int32_t T, K, E, G, R, Dn, level;
   int32_t nslots, nblocks;
+  int32_t scanned;  // counts holds exclusive prefixes over workgroups and the totals in row nblocks
   int64_t row_capacity;
-  int32_t *counts;  // workspace [nblocks][Dn]
+  int32_t *counts;  // workspace [nblocks + 1][Dn]
   int32_t *dest_count, *dest_offset, *row_token, *slot_row;
   uint8_t *slot_keep;
   float *row_weight;
@@ -128,6 +134,38 @@ __global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanParams p) 
   }
 }
 
+// Column d of the count matrix -> exclusive prefix over the workgroups, in place; total -> row nblocks.
+__global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(PlanParams p) {
+  __shared__ int32_t wave_tot[kPlanWaves];
+  __shared__ int32_t carry;
+  const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
+  const int d = blockIdx.x;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int b0 = 0; b0 < p.nblocks; b0 += kPlanThreads) {
+    const int b = b0 + (int)threadIdx.x;
+    const int v = b < p.nblocks ? p.counts[(int64_t)b * p.Dn + d] : 0;
+    int incl = v;
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int u = __shfl_up(incl, off, kWave);
+      if (lane >= off) incl += u;
+    }
+    if (lane == kWave - 1) wave_tot[wv] = incl;
+    __syncthreads();
+    int base = carry;
+    for (int w = 0; w < wv; ++w) base += wave_tot[w];
+    if (b < p.nblocks) p.counts[(int64_t)b * p.Dn + d] = base + incl - v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int tot = 0;
+      for (int w = 0; w < kPlanWaves; ++w) tot += wave_tot[w];
+      carry += tot;
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) p.counts[(int64_t)p.nblocks * p.Dn + d] = carry;
+}
+
 __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) {
   __shared__ int8_t s_rank[kPlanStaged];
   __shared__ int8_t s_dest[kPlanStaged];
@@ -151,7 +189,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   // earlier ones (this workgroup's base).  Wave wv takes rows wv, wv+16, ...
   {
     int tot = 0, pre = 0;
-    if (lane < p.Dn) {
+    if (p.scanned) {
+      if (wv == 0 && lane < p.Dn) {
+        tot = p.counts[(int64_t)p.nblocks * p.Dn + lane];
+        pre = p.counts[(int64_t)blockIdx.x * p.Dn + lane];
+      }
+    } else if (lane < p.Dn) {
       for (int b = wv; b < p.nblocks; b += kPlanWaves) {
         const int c = p.counts[(int64_t)b * p.Dn + lane];
         tot += c;
@@ -272,9 +315,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   if ((int)threadIdx.x < nodes && blk_node[threadIdx.x]) atomicAdd(&p.load_node[threadIdx.x], blk_node[threadIdx.x]);
 }
 
-// Destination table of a receiver stage: one workgroup walks the E experts in chunks of 1024 and
-// numbers the experts placed on `my_rank` with a ballot scan, so local indices ascend with the
-// expert id.
 // Table of one hop for a (parent, child) pair of group cuts: purely elementwise.
 __global__ __launch_bounds__(kPlanThreads) void level_dest_map_kernel(const int32_t *__restrict__ expert_to_rank, int E,
                                                                        int G, int my_rank, int ranks_per_parent,
@@ -292,6 +332,9 @@ __global__ __launch_bounds__(kPlanThreads) void level_dest_map_kernel(const int3
   dest_map[e] = v;
 }
 
+// Destination table of a receiver stage: one workgroup walks the E experts in chunks of 1024 and
+// numbers the experts placed on `my_rank` with a ballot scan, so local indices ascend with the
+// expert id.
 __global__ __launch_bounds__(kPlanThreads) void recv_dest_map_kernel(const int32_t *__restrict__ expert_to_rank, int E,
                                                                       int G, int R, int my_rank, int stage,
                                                                       int32_t *__restrict__ dest_map,
@@ -337,13 +380,30 @@ static inline int32_t plan_blocks(int64_t nslots) {
   return (int32_t)(b < 1 ? 1 : b);
 }
 
+static inline size_t plan_workspace(int64_t nslots, int Dn) {
+  return ((size_t)plan_blocks(nslots) + 1) * (size_t)Dn * sizeof(int32_t);
+}
+
+// count -> (scan) -> write on `stream`; p.nblocks, p.Dn and p.counts are set.
+static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
+  p.scanned = (int64_t)p.nblocks * p.Dn >= kPlanScanMinEntries ? 1 : 0;
+  hipLaunchKernelGGL(plan_count_kernel, dim3(p.nblocks), dim3(kPlanThreads), 0, stream, p);
+  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  if (p.scanned) {
+    hipLaunchKernelGGL(plan_scan_kernel, dim3(p.Dn), dim3(kPlanThreads), 0, stream, p);
+    if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  }
+  hipLaunchKernelGGL(plan_write_kernel, dim3(p.nblocks), dim3(kPlanThreads), 0, stream, p);
+  return hm_launch_status();
+}
+
 }  // namespace hm
 
 extern "C" size_t hm_plan_workspace_bytes(int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level) {
   if (E < 1 || hm_check_tk(T, K) != HM_OK || hm_check_topology(topo) != HM_OK) return 0;
   if (level != HM_DEDUP_NONE && level != HM_DEDUP_GPU && level != HM_DEDUP_NODE) return 0;
   const int Dn = level == HM_DEDUP_NODE ? topo.nodes : topo.nodes * topo.ranks_per_node;
-  return (size_t)hm::plan_blocks((int64_t)T * K) * (size_t)Dn * sizeof(int32_t);
+  return hm::plan_workspace((int64_t)T * K, Dn);
 }
 
 extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
@@ -394,16 +454,12 @@ extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights,
   p.load_node = out->load_node;
   out->num_dest = p.Dn;
 
-  hipStream_t stream = (hipStream_t)hip_stream;
-  hipLaunchKernelGGL(hm::plan_count_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
-  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
-  hipLaunchKernelGGL(hm::plan_write_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
-  return hm_launch_status();
+  return hm::launch_plan(p, (hipStream_t)hip_stream);
 }
 
 extern "C" size_t hm_plan_mapped_workspace_bytes(int32_t rows, int32_t K, int32_t num_dest) {
   if (hm_check_tk(rows, K) != HM_OK || num_dest < 1 || num_dest > 64) return 0;
-  return (size_t)hm::plan_blocks((int64_t)rows * K) * (size_t)num_dest * sizeof(int32_t);
+  return hm::plan_workspace((int64_t)rows * K, num_dest);
 }
 
 extern "C" hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_weights, const int32_t *dest_map,
@@ -448,11 +504,7 @@ extern "C" hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_wei
   p.load_expert = p.load_rank = p.load_node = nullptr;   // the fused loads need the rank placement
   out->num_dest = num_dest;
 
-  hipStream_t stream = (hipStream_t)hip_stream;
-  hipLaunchKernelGGL(hm::plan_count_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
-  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
-  hipLaunchKernelGGL(hm::plan_write_kernel, dim3(p.nblocks), dim3(hm::kPlanThreads), 0, stream, p);
-  return hm_launch_status();
+  return hm::launch_plan(p, (hipStream_t)hip_stream);
 }
 
 extern "C" hm_status hm_recv_dest_map(const int32_t *expert_to_rank, int32_t E, hm_topology topo, int32_t my_rank,

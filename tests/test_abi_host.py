@@ -39,9 +39,9 @@ def test_status_strings(B):
 
 
 def test_workspace_query(B):
-    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_NODE) == 64 * 4 * 4
-    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_GPU) == 64 * 32 * 4
-    assert B.hm_plan_workspace_bytes(0, 8, 256, 4, 8, B.HM_DEDUP_GPU) == 32 * 4
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_NODE) == (64 + 1) * 4 * 4
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_GPU) == (64 + 1) * 32 * 4
+    assert B.hm_plan_workspace_bytes(0, 8, 256, 4, 8, B.HM_DEDUP_GPU) == (1 + 1) * 32 * 4
     assert B.hm_plan_workspace_bytes(8192, 8, 256, 9, 8, B.HM_DEDUP_GPU) == 0      # 72 ranks
     assert B.hm_plan_workspace_bytes(8192, 65, 256, 4, 8, B.HM_DEDUP_GPU) == 0     # K too large
     assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, 3) == 0                   # bad level
@@ -108,7 +108,7 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_recv_dest_map(fake, 0, topo, 0, 0, fake, fake, None) == B.HM_ERR_SHAPE
     assert L.hm_recv_dest_map(fake, 8, topo, 4, 0, fake, fake, None) == B.HM_ERR_TOPOLOGY     # rank 4 of 4
     assert L.hm_recv_dest_map(fake, 8, topo, 0, 2, fake, fake, None) == B.HM_ERR_LEVEL
-    assert L.hm_plan_mapped_workspace_bytes(8192, 8, 8) == 64 * 8 * 4
+    assert L.hm_plan_mapped_workspace_bytes(8192, 8, 8) == (64 + 1) * 8 * 4
     assert L.hm_plan_mapped_workspace_bytes(8192, 8, 65) == 0
 
     def mapped(ids=fake, w=fake, dm=fake, rows=4, K=2, E=8, nd=4, out=ref, ws=fake, ws_bytes=1 << 20):

@@ -428,6 +428,23 @@ def test_fused_loads_with_many_experts(hw, oracle):
     assert np.array_equal(plan.load_node.cpu().numpy(), ln)
 
 
+@pytest.mark.parametrize("T,K,nodes,rpn", [(400000, 8, 8, 8), (70000, 3, 2, 4), (32768, 8, 8, 8), (32640, 8, 8, 8)])
+def test_plan_at_large_token_counts(hw, oracle, T, K, nodes, rpn):
+    """Sizes on both sides of the point where hm_plan inserts its scan launch (count-matrix
+    entries = ceil(T*K/1024) * destinations >= 16384), the whole plan compared with the oracle."""
+    E = 256
+    rng = np.random.default_rng(T % 97)
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)         # repeated ids inside a token are legal
+    w = rng.random((T, K), dtype=np.float32)
+    e2r = W.contiguous_placement(E, nodes * rpn)
+    for level in (NONE, GPU, NODE):
+        ctx = "large plan T=%d K=%d %dx%d level=%s" % (T, K, nodes, rpn, LEVEL[level])
+        print("case:", ctx, flush=True)
+        ora = oracle.plan(ids, w, e2r, nodes, rpn, level)
+        g = hw.GpuPlan(ids, w, e2r, nodes, rpn, level)
+        hw.assert_plan_equal(g, ora, ctx)
+
+
 def test_plan_is_deterministic(hw, oracle):
     import torch
     wl = W.WORKLOADS["dsv3"]
