@@ -60,12 +60,14 @@ struct Slot {
 // slot.  A slot owns its (token, destination) row at level none always, else iff no earlier slot
 // of the token has the same destination: the OR over a group's experts in Eq.(7) leaves one copy
 // per group, and the lowest k keeps it.
-__device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *s_rank, int8_t *s_dest) {
+__device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *s_rank, int8_t *s_dest,
+                                                   float *s_weight = nullptr) {
   const int halo = p.K - 1;
   const int64_t first = (int64_t)blockIdx.x * kPlanThreads;
   for (int i = threadIdx.x; i < kPlanThreads + 2 * halo; i += kPlanThreads) {
     const int64_t s = first - halo + i;
     int r = -1, d = -1;
+    if (s_weight) s_weight[i] = (s >= 0 && s < p.nslots) ? p.weights[s] : 0.0f;   // in flight with the id lookups
     if (s >= 0 && s < p.nslots) {
       if (p.dest_map) {
         const int id = p.ids[s];
@@ -176,6 +178,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   __shared__ int32_t wave_base[kPlanWaves][kWave];  // kept slots in earlier waves of the workgroup
   __shared__ int32_t hist[kPlanHist];               // fused expert load: slots per expert
   __shared__ int32_t blk_rank[kWave], blk_node[kWave];
+  __shared__ float s_weight[kPlanStaged];           // router weights of the staged slots
   const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
   const bool loads = p.load_expert != nullptr;
   const bool lds_hist = p.E <= kPlanHist;
@@ -205,7 +208,10 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
     part_pre[wv][lane] = pre;
   }
 
-  const Slot me = stage_and_classify(p, s_rank, s_dest);   // contains a barrier
+  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
+  int my_id = -1;   // for the expert histogram; fetched now so that it does not cost a round trip later
+  if (loads && s < p.nslots) my_id = p.ids[s];
+  const Slot me = stage_and_classify(p, s_rank, s_dest, s_weight);   // contains a barrier
   const int kept_dest = me.keep ? me.dest : -1;
   for (int d = 0; d < p.Dn; ++d) {
     const uint64_t b = __ballot(kept_dest == d);
@@ -240,7 +246,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   }
   __syncthreads();
 
-  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
   if (me.live) {
     if (me.dest < 0) {
       p.slot_row[s] = -1;
@@ -254,13 +259,12 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
       const int row = block_base[me.dest] + wave_base[wv][me.dest] + pos;
       p.slot_keep[s] = 1;
       p.slot_row[s] = row;
-      float wsum = p.weights[s];
+      float wsum = s_weight[me.tok0 + me.k];
       if (p.level != HM_DEDUP_NONE) {
         for (int k2 = me.k + 1; k2 < p.K; ++k2) {
           if (s_dest[me.tok0 + k2] == me.dest) {
-            const int64_t s2 = s + (k2 - me.k);
-            p.slot_row[s2] = row;
-            wsum = wsum + p.weights[s2];  // ascending k, fp32
+            p.slot_row[s + (k2 - me.k)] = row;
+            wsum = wsum + s_weight[me.tok0 + k2];  // ascending k, fp32
           }
         }
       }
@@ -291,9 +295,8 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   // Fused hm_expert_load: slots per expert, and tokens per rank / node counted once each from the
   // masks above (a ballot per group; lane g keeps the count of group g).
   if (me.live && me.rank >= 0) {
-    const int id = p.ids[s];
-    if (lds_hist) atomicAdd(&hist[id], 1);
-    else atomicAdd(&p.load_expert[id], 1);
+    if (lds_hist) atomicAdd(&hist[my_id], 1);
+    else atomicAdd(&p.load_expert[my_id], 1);
   }
   int my_rank_cnt = 0, my_node_cnt = 0;
   const int nodes = p.G / p.R;
