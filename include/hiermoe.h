@@ -320,6 +320,16 @@ hm_status hm_swap_select(int32_t d, const int32_t *U /* host */, int32_t G, int3
                          double *Q, int32_t *best_pair, double *best_time, void *workspace, size_t workspace_bytes,
                          void *hip_stream);
 
+/*
+ * hm_swap_apply -- carries out the chosen swap (Section IV: the positions of the two selected
+ * experts are exchanged, once per planner step) without a host round trip: the entries
+ * expert_to_rank[best_pair[0]] and expert_to_rank[best_pair[1]] (device int32[E], updated in place;
+ * best_pair device int32[2], as written by hm_swap_select) trade places.  A pair on the diagonal
+ * (the unswapped placement won Eq.(10)) or with an index outside [0,E) changes nothing.  Stream
+ * order makes the next hm_plan / hm_swap_counts on the same stream see the new placement.
+ */
+hm_status hm_swap_apply(int32_t *expert_to_rank, int32_t E, const int32_t *best_pair, void *hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char *hm_status_string(hm_status s);
 

@@ -362,5 +362,16 @@ def swap_select(U, G: int, M: float, v: float, z_inter, z_intra, scale_inter, sc
     return Q, (int(best[0]), int(best[1])), float(bt.value)
 
 
+def swap_apply(expert_to_rank, pair) -> np.ndarray:
+    """A copy of the placement with the entries of experts pair[0] and pair[1] exchanged."""
+    lib = _load()
+    e2r = np.array(expert_to_rank, dtype=np.int32, copy=True)
+    pr = _c(pair, np.int32)
+    rc = lib.hmo_swap_apply(_p(e2r), ctypes.c_int32(e2r.shape[0]), _p(pr))
+    if rc != 0:
+        raise ValueError("hmo_swap_apply: argument error %d" % rc)
+    return e2r
+
+
 def f64_to_bf16(v: float) -> int:
     return int(_load().hmo_f64_to_bf16(float(v)))

@@ -724,5 +724,22 @@ int hmo_swap_select(int32_t d, const int32_t *U, int32_t G, int32_t E, double M,
     return HMO_OK;
 }
 
+/*
+ * hmo_swap_apply -- carry out the chosen swap (Section IV: the positions of the two selected
+ * experts are exchanged, once per planner step): the placement entries of experts pair[0] and
+ * pair[1] trade places.  A pair on the diagonal (the unswapped placement won Eq.(10)) or with an
+ * index outside [0,E) changes nothing.
+ */
+int hmo_swap_apply(int32_t *expert_to_rank, int32_t E, const int32_t *pair)
+{
+    if (!expert_to_rank || !pair || E < 1) return HMO_ERR_ARG;
+    const int32_t r = pair[0], c = pair[1];
+    if (r < 0 || r >= E || c < 0 || c >= E || r == c) return HMO_OK;
+    const int32_t g = expert_to_rank[r];
+    expert_to_rank[r] = expert_to_rank[c];
+    expert_to_rank[c] = g;
+    return HMO_OK;
+}
+
 /* Exposed so tests can pin the rounding routine by itself. */
 uint16_t hmo_f64_to_bf16(double v) { return f64_to_bf16_rne(v); }

@@ -26,7 +26,7 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_combine_transpose", "hm_expert_load", "hm_status_string", "hm_recv_dest_map",
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
-           "hm_swap_select", "hm_level_dest_map", "hm_combine_f32")
+           "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply")
 
 
 class hm_topology(ctypes.Structure):
@@ -72,6 +72,8 @@ def lib():
         L.hm_dispatch_pack.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
         L.hm_combine.restype = ctypes.c_int
         L.hm_combine.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
+        L.hm_swap_apply.restype = ctypes.c_int
+        L.hm_swap_apply.argtypes = [vp, i32, vp, vp]
         L.hm_combine_f32.restype = ctypes.c_int
         L.hm_combine_f32.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
         L.hm_combine_transpose.restype = ctypes.c_int
@@ -365,6 +367,13 @@ def hm_swap_select(U, G: int, M: float, v: float, z_inter, z_intra: torch.Tensor
                               workspace.data_ptr(), workspace.numel() * 8, _stream(stream))
     _check("hm_swap_select", rc)
     return Q, best_pair, best_time
+
+
+def hm_swap_apply(expert_to_rank: torch.Tensor, best_pair: torch.Tensor, stream=None) -> torch.Tensor:
+    rc = lib().hm_swap_apply(_dev(expert_to_rank, torch.int32, "expert_to_rank"), expert_to_rank.shape[0],
+                             _dev(best_pair, torch.int32, "best_pair"), _stream(stream))
+    _check("hm_swap_apply", rc)
+    return expert_to_rank
 
 
 def hm_level_dest_map(expert_to_rank: torch.Tensor, G: int, my_rank: int, parent_groups: int, child_groups: int,

@@ -240,6 +240,17 @@ __global__ __launch_bounds__(kSwapThreads) void swap_argmin_kernel(SelectParams 
   }
 }
 
+// The chosen swap (Section IV): the two placement entries trade places; the diagonal (no swap won
+// Eq.(10)) and out-of-range indices change nothing.
+__global__ void swap_apply_kernel(int32_t *__restrict__ expert_to_rank, int32_t E, const int32_t *__restrict__ pair) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  const int32_t r = pair[0], c = pair[1];
+  if (r < 0 || r >= E || c < 0 || c >= E || r == c) return;
+  const int32_t g = expert_to_rank[r];
+  expert_to_rank[r] = expert_to_rank[c];
+  expert_to_rank[c] = g;
+}
+
 static inline int64_t swap_ws_ints(int64_t E, int64_t ng) { return 64 + 2 * E + E * ng + kSwapCopies * E * E; }
 
 }  // namespace hm
@@ -343,5 +354,13 @@ extern "C" hm_status hm_swap_select(int32_t d, const int32_t *U, int32_t G, int3
   hipLaunchKernelGGL(swap_q_kernel, dim3(p.nblocks), dim3(kSwapThreads), 0, stream, p);
   if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   hipLaunchKernelGGL(swap_argmin_kernel, dim3(1), dim3(kSwapThreads), 0, stream, p);
+  return hm_launch_status();
+}
+
+extern "C" hm_status hm_swap_apply(int32_t *expert_to_rank, int32_t E, const int32_t *best_pair, void *hip_stream) {
+  if (!expert_to_rank || !best_pair) return HM_ERR_NULL;
+  if (E < 1) return HM_ERR_SHAPE;
+  hipLaunchKernelGGL(hm::swap_apply_kernel, dim3(1), dim3(hm::kWave), 0, (hipStream_t)hip_stream, expert_to_rank, E,
+                     best_pair);
   return hm_launch_status();
 }

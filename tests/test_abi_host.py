@@ -154,6 +154,9 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_swap_select(2, i32x(1, 3), 4, 8, 1.0, 1.0, zp, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_TOPOLOGY
     zn = (ctypes.c_void_p * 2)(None, None)
     assert L.hm_swap_select(2, i32x(1, 2), 4, 8, 1.0, 1.0, zn, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
+    assert L.hm_swap_apply(None, 8, fake, None) == B.HM_ERR_NULL
+    assert L.hm_swap_apply(fake, 8, None, None) == B.HM_ERR_NULL
+    assert L.hm_swap_apply(fake, 0, fake, None) == B.HM_ERR_SHAPE
     assert L.hm_swap_select(1, i32x(1), 4, 8, 1.0, 1.0, None, None, None, 1.0, None, None, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
 
 

@@ -95,3 +95,48 @@ def test_swap_select_parity(hw, oracle):
             flat = int(np.argmin(Qg))
             assert pair == (flat // E, flat % E)                               # first minimiser in row-major order
     print("d=4 gamma=5 best pair", pair, "time", float(bt.item()), "no swap", Qg[0, 0])
+
+
+def test_planner_loop_stays_on_the_device(hw, oracle):
+    """(Z, select, apply) repeated on the device with no host step in between; afterwards every
+    iteration is replayed on the oracle.  gamma <= 0 keeps Q bit-exact, so the chosen pairs and
+    the placements must be identical."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["skew"]
+    r = W.make_routing(wl, T=3000)
+    G, E, iters = wl.G, wl.E, 5
+    ids_d = hw.dev(r.topk_ids)
+    e2r_d = hw.dev(r.expert_to_rank.copy())
+    Zn = torch.empty((E, E, wl.nodes), dtype=torch.int32, device="cuda")
+    Zg = torch.empty((E, E, G), dtype=torch.int32, device="cuda")
+    st = torch.zeros(1, dtype=torch.int32, device="cuda")
+    Q = torch.empty((E, E), dtype=torch.float64, device="cuda")
+    pairs = torch.full((iters, 2), -1, dtype=torch.int32, device="cuda")
+    times = torch.zeros(iters, dtype=torch.float64, device="cuda")
+    places = torch.empty((iters, E), dtype=torch.int32, device="cuda")
+    U, M, v = [1, wl.nodes], float(wl.H), 2.0
+    ai, bi, aa, ba = [0, 0.497], [0, 5.29e-7], 0.571, 1.27e-7
+    for it in range(iters):
+        B.hm_swap_counts(ids_d, e2r_d, G, wl.nodes, Zn, st)
+        B.hm_swap_counts(ids_d, e2r_d, G, G, Zg, st)
+        B.hm_swap_select(U, G, M, v, [None, Zn], Zg, [0, 1.0], float(wl.nodes), ai, bi, aa, ba, 0.0, Q, pairs[it], times[it:it + 1])
+        B.hm_swap_apply(e2r_d, pairs[it])
+        places[it].copy_(e2r_d)
+    torch.cuda.synchronize()
+    assert int(st.item()) == 0
+    place = r.expert_to_rank.copy()
+    got_pairs, got_times, got_places = pairs.cpu().numpy(), times.cpu().numpy(), places.cpu().numpy()
+    for it in range(iters):
+        zn, _ = oracle.swap_counts(r.topk_ids, place, G, wl.nodes)
+        zg, _ = oracle.swap_counts(r.topk_ids, place, G, G)
+        _, best, bt = oracle.swap_select(U, G, M, v, [None, zn], zg, [0, 1.0], float(wl.nodes), ai, bi, aa, ba, 0.0)
+        assert tuple(int(x) for x in got_pairs[it]) == best and got_times[it] == bt, it
+        place = oracle.swap_apply(place, best)
+        assert np.array_equal(got_places[it], place), it
+    assert (np.diff(got_times) <= 0).all()
+    # degenerate pairs leave the placement alone
+    before = e2r_d.clone()
+    for pr in ((3, 3), (-1, 2), (0, E)):
+        B.hm_swap_apply(e2r_d, hw.dev(np.array(pr, np.int32)))
+    assert torch.equal(e2r_d, before)

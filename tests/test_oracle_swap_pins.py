@@ -137,3 +137,36 @@ def test_smooth_max_and_selection(oracle):
     assert best == tuple(int(i) for i in np.unravel_index(np.argmin(Q), Q.shape)) and bt == Q[best]
     # the chosen swap does not make things worse than no swap (r == c is always a candidate)
     assert bt <= Q[0, 0]
+
+
+def test_swap_apply_and_the_planner_loop(oracle):
+    """Applying the chosen pair exchanges two placement entries; the load of the new placement is
+    the row Z[r,c,:] that predicted it, and a greedy loop of (Z, select, apply) never raises the
+    estimated time and stops changing the placement once the diagonal wins."""
+    e2r = np.array([0, 0, 1, 1, 2, 3], np.int32)
+    assert oracle.swap_apply(e2r, (1, 4)).tolist() == [0, 2, 1, 1, 0, 3]
+    assert oracle.swap_apply(e2r, (4, 1)).tolist() == [0, 2, 1, 1, 0, 3]
+    for pair in ((2, 2), (-1, 3), (0, 6), (7, 7)):
+        assert oracle.swap_apply(e2r, pair).tolist() == e2r.tolist()
+    assert e2r.tolist() == [0, 0, 1, 1, 2, 3]                           # the wrapper works on a copy
+
+    wl = W.WORKLOADS["skew"]
+    r = W.make_routing(wl, T=512)
+    place = r.expert_to_rank.copy()
+    M, v = 2048.0, 2.0
+    times = []
+    for it in range(6):
+        Zg, _ = oracle.swap_counts(r.topk_ids, place, wl.G, wl.G)
+        Q, best, bt = oracle.swap_select([1], wl.G, M, v, [None], Zg, [0], 1.0, [0], [0], 0.3, 1e-6, 10.0)
+        nxt = oracle.swap_apply(place, best)
+        assert np.array_equal(nxt, _swapped(place, *best))
+        # the prediction Z[r,c,:] is the duplicate-free load of the placement just produced
+        _, lr, _, _ = oracle.expert_load(r.topk_ids, nxt, wl.nodes, wl.ranks_per_node)
+        assert np.array_equal(lr, Zg[best[0], best[1]])
+        smax = lr.max() * ((lr / lr.max()) ** 10.0).sum() ** 0.1         # Eq.(11), gamma = 10: a plain maximum
+        assert abs(bt - (0.3 + wl.G * smax * M * v * 1e-6)) <= 1e-12 * bt   # cannot see past the hottest rank
+        times.append(bt)
+        if best[0] == best[1]:
+            assert np.array_equal(nxt, place)
+        place = nxt
+    assert all(b <= a for a, b in zip(times, times[1:])) and times[-1] < times[0]
