@@ -2,7 +2,7 @@
 //
 // Z[r][c][:] is the vector of duplicate-free per-group token counts after experts r and c trade
 // places.  A swap can only change the two groups involved, and by how much follows from three
-// small co-occurrence tables gathered in one pass over the tokens (one lane per token):
+// small co-occurrence tables gathered in one pass over the tokens (one lane per routing slot):
 //   L0[a]    tokens selecting a                      CG[a][g]  ... that also select something in g
 //   L[a]     tokens where a is alone in its group    C[a][b]   ... that also select b
 // For g_r != g_c:  Z[r][c][g_c] = base[g_c] + (L0[r] - CG[r][g_c]) - (L[c] - C[c][r])   and the same
@@ -13,6 +13,7 @@
 namespace hm {
 
 constexpr int kSwapThreads = 256;
+constexpr int kFactorThreads = 1024;   // the co-occurrence pass: 16 waves share one set of LDS tables
 constexpr int kSwapLds = 12288;   // ints of LDS for L0 + L + CG (48 KiB)
 constexpr int kSwapCopies = 8;    // private copies of C: popular expert pairs would otherwise serialise on one address
 
@@ -20,6 +21,7 @@ struct SwapParams {
   const int32_t *ids;
   const int32_t *expert_to_rank;
   int32_t T, K, E, G, ng, per;
+  int32_t sub;     // lanes per token in the co-occurrence pass: the power of two >= K
   int32_t *base;   // [64]
   int32_t *L0;     // [E]
   int32_t *L;      // [E]
@@ -36,66 +38,78 @@ __global__ __launch_bounds__(kSwapThreads) void swap_clear_kernel(SwapParams p) 
   if (i == 0 && p.status) *p.status = 0;
 }
 
-__global__ __launch_bounds__(kSwapThreads) void swap_factors_kernel(SwapParams p) {
+// One lane per routing slot: the K slots of a token sit in a sub-group of `sub` = 2^ceil(log2 K)
+// consecutive lanes (64 / sub tokens per wave) and learn about each other through shuffles, so the
+// per-token work -- K expert updates, K * groups and up to K * K co-occurrence updates -- is spread
+// over K lanes instead of being a serial loop of one lane.
+__global__ __launch_bounds__(kFactorThreads) void swap_factors_kernel(SwapParams p) {
   __shared__ int32_t lds[kSwapLds];
   __shared__ int32_t base_cnt[kWave];
   const int small = p.E * (p.ng + 2);
   const bool use_lds = small <= kSwapLds;
   int32_t *sL0 = lds, *sL = lds + p.E, *sCG = lds + 2 * p.E;
   if (use_lds)
-    for (int i = threadIdx.x; i < small; i += kSwapThreads) lds[i] = 0;
+    for (int i = threadIdx.x; i < small; i += kFactorThreads) lds[i] = 0;
   if (threadIdx.x < kWave) base_cnt[threadIdx.x] = 0;
   __syncthreads();
 
   const int lane = lane_id();
-  int my_base = 0;
+  const int k = lane & (p.sub - 1);        // my slot in the token
+  const int sub0 = lane & ~(p.sub - 1);    // first lane of my token's sub-group
+  const int tokens_per_wave = kWave / p.sub;
+  const int64_t wave = (int64_t)blockIdx.x * (kFactorThreads / kWave) + (threadIdx.x >> 6);
+  const int64_t nwaves = (int64_t)gridDim.x * (kFactorThreads / kWave);
+  const int64_t per_round = nwaves * tokens_per_wave;
+  const int64_t rounds = ((int64_t)p.T + per_round - 1) / per_round;
   int32_t *myC = p.C + (int64_t)(blockIdx.x % kSwapCopies) * p.E * p.E;
-  const int64_t stride = (int64_t)gridDim.x * kSwapThreads;
-  const int64_t rounds = ((int64_t)p.T + stride - 1) / stride;
+  int my_base = 0;
   for (int64_t it = 0; it < rounds; ++it) {
-    const int64_t t = it * stride + (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
-    uint64_t gm = 0;
-    if (t < p.T) {
-      const int32_t *tok = p.ids + t * p.K;
-      // the selected experts form a set: `firsts` marks the first valid occurrence of each
-      uint64_t firsts = 0;
-      for (int k = 0; k < p.K; ++k) {
-        const int a = tok[k];
-        const int g = rank_of(p.expert_to_rank, p.E, p.G, a);
-        if (g < 0) {
-          if (g == -1) flag(p.status, HM_ERR_BAD_ID);
-          continue;
-        }
-        gm |= 1ull << (g / p.per);
-        bool repeat = false;
-        for (int k1 = 0; k1 < k; ++k1) repeat = repeat || tok[k1] == a;
-        if (!repeat) firsts |= 1ull << k;
-      }
-      for (uint64_t ma = firsts; ma; ma &= ma - 1) {
-        const int a = tok[__builtin_ctzll(ma)];
-        const int ga = p.expert_to_rank[a] / p.per;
-        int in_ga = 0;   // distinct selected experts in a's group
-        for (uint64_t mb = firsts; mb; mb &= mb - 1)
-          in_ga += (p.expert_to_rank[tok[__builtin_ctzll(mb)]] / p.per == ga) ? 1 : 0;
-        const bool alone = in_ga == 1;
-        if (use_lds) {
-          atomicAdd(&sL0[a], 1);
-          if (alone) atomicAdd(&sL[a], 1);
-          for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&sCG[a * p.ng + __builtin_ctzll(m)], 1);
-        } else {
-          atomicAdd(&p.L0[a], 1);
-          if (alone) atomicAdd(&p.L[a], 1);
-          for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&p.CG[(int64_t)a * p.ng + __builtin_ctzll(m)], 1);
-        }
-        if (alone)
-          for (uint64_t mb = firsts; mb; mb &= mb - 1) {
-            const int b = tok[__builtin_ctzll(mb)];
-            if (b != a) atomicAdd(&myC[(int64_t)a * p.E + b], 1);
-          }
+    const int64_t t = (it * nwaves + wave) * tokens_per_wave + lane / p.sub;
+    int a = -1, grp = -1;   // my expert and its group; -1 when the slot is empty, dropped or invalid
+    if (t < p.T && k < p.K) {
+      const int id = p.ids[t * p.K + k];
+      const int g = rank_of(p.expert_to_rank, p.E, p.G, id);
+      if (g == -1) flag(p.status, HM_ERR_BAD_ID);
+      if (g >= 0) {
+        a = id;
+        grp = g / p.per;
       }
     }
+    // the selected experts form a set: `first` marks the first valid occurrence of each
+    bool first = a >= 0;
+    uint64_t gm = 0;
+    for (int k1 = 0; k1 < p.K; ++k1) {
+      const int a1 = __shfl(a, sub0 + k1, kWave);
+      const int g1 = __shfl(grp, sub0 + k1, kWave);
+      if (g1 >= 0) gm |= 1ull << g1;
+      if (k1 < k && a1 == a) first = false;
+    }
+    int in_group = 0;   // distinct selected experts in my expert's group
+    for (int k1 = 0; k1 < p.K; ++k1) {
+      const int f1 = __shfl((int)first, sub0 + k1, kWave);
+      const int g1 = __shfl(grp, sub0 + k1, kWave);
+      in_group += (f1 && g1 == grp) ? 1 : 0;
+    }
+    const bool alone = first && in_group == 1;
+    if (first) {
+      if (use_lds) {
+        atomicAdd(&sL0[a], 1);
+        if (alone) atomicAdd(&sL[a], 1);
+        for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&sCG[a * p.ng + __builtin_ctzll(m)], 1);
+      } else {
+        atomicAdd(&p.L0[a], 1);
+        if (alone) atomicAdd(&p.L[a], 1);
+        for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&p.CG[(int64_t)a * p.ng + __builtin_ctzll(m)], 1);
+      }
+    }
+    for (int k1 = 0; k1 < p.K; ++k1) {
+      const int a1 = __shfl(a, sub0 + k1, kWave);
+      const int f1 = __shfl((int)first, sub0 + k1, kWave);
+      if (alone && f1 && a1 != a) atomicAdd(&myC[(int64_t)a * p.E + a1], 1);
+    }
+    const bool leader = k == 0 && t < p.T;   // one lane per token counts the token's groups
     for (int j = 0; j < p.ng; ++j) {
-      const uint64_t b = __ballot((gm >> j) & 1ull);
+      const uint64_t b = __ballot(leader && ((gm >> j) & 1ull));
       if (lane == j) my_base += __popcll(b);
     }
   }
@@ -103,11 +117,11 @@ __global__ __launch_bounds__(kSwapThreads) void swap_factors_kernel(SwapParams p
   __syncthreads();
   if ((int)threadIdx.x < p.ng && base_cnt[threadIdx.x]) atomicAdd(&p.base[threadIdx.x], base_cnt[threadIdx.x]);
   if (use_lds) {
-    for (int i = threadIdx.x; i < p.E; i += kSwapThreads) {
+    for (int i = threadIdx.x; i < p.E; i += kFactorThreads) {
       if (sL0[i]) atomicAdd(&p.L0[i], sL0[i]);
       if (sL[i]) atomicAdd(&p.L[i], sL[i]);
     }
-    for (int i = threadIdx.x; i < p.E * p.ng; i += kSwapThreads)
+    for (int i = threadIdx.x; i < p.E * p.ng; i += kFactorThreads)
       if (sCG[i]) atomicAdd(&p.CG[i], sCG[i]);
   }
 }
@@ -280,6 +294,8 @@ extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expe
   p.G = G;
   p.ng = ng;
   p.per = G / ng;
+  p.sub = 1;
+  while (p.sub < K) p.sub *= 2;
   p.base = (int32_t *)workspace;
   p.L0 = p.base + 64;
   p.L = p.L0 + E;
@@ -293,9 +309,10 @@ extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expe
                      0, stream, p);
   if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   if (T > 0) {
-    int64_t blocks = ((int64_t)T + kSwapThreads - 1) / kSwapThreads;
-    if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(swap_factors_kernel, dim3((unsigned)blocks), dim3(kSwapThreads), 0, stream, p);
+    const int64_t tokens_per_block = (int64_t)(kFactorThreads / kWave) * (kWave / p.sub);
+    int64_t blocks = ((int64_t)T + tokens_per_block - 1) / tokens_per_block;
+    if (blocks > 256) blocks = 256;   // one per CU; every block flushes its LDS tables with atomics
+    hipLaunchKernelGGL(swap_factors_kernel, dim3((unsigned)blocks), dim3(kFactorThreads), 0, stream, p);
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   }
   const int64_t total = (int64_t)E * E * ng;
