@@ -13,6 +13,7 @@
 namespace hm {
 
 constexpr int kSwapThreads = 256;
+constexpr int kSelectThreads = 64;     // Q per pair: fp64 pow-heavy, so many small workgroups to reach every CU
 constexpr int kFactorThreads = 1024;   // the co-occurrence pass: 16 waves share one set of LDS tables
 constexpr int kSwapLds = 12288;   // ints of LDS for L0 + L + CG (48 KiB)
 constexpr int kSwapCopies = 8;    // private copies of C: popular expert pairs would otherwise serialise on one address
@@ -177,16 +178,32 @@ __device__ __forceinline__ double smooth_max(const int32_t *x, int n, double gam
   for (int i = 0; i < n; ++i) mi = max(mi, x[i]);
   const double m = (double)mi;
   if (gamma <= 0.0 || m == 0.0) return m;
+  // A small whole gamma (the paper uses 10) needs no pow per entry: square-and-multiply gives the
+  // same power to a few ulp, and a thread is otherwise a serial chain of up to 64 pow calls per level.
+  const int whole = (gamma <= 64.0 && gamma == (double)(int)gamma) ? (int)gamma : 0;
+  const double inv_m = 1.0 / m;
   double sum = 0.0;
-  for (int i = 0; i < n; ++i) sum += pow((double)x[i] / m, gamma);
+  for (int i = 0; i < n; ++i) {
+    if (whole) {
+      const double ratio = (double)x[i] * inv_m;   // within an ulp of the quotient
+      double acc = 1.0, sq = ratio;
+      for (int e = whole; e; e >>= 1) {
+        if (e & 1) acc *= sq;
+        sq *= sq;
+      }
+      sum += acc;
+    } else {
+      sum += pow((double)x[i] / m, gamma);
+    }
+  }
   return m * pow(sum, 1.0 / gamma);
 }
 
-__global__ __launch_bounds__(kSwapThreads) void swap_q_kernel(SelectParams p) {
+__global__ __launch_bounds__(kSelectThreads) void swap_q_kernel(SelectParams p) {
 #pragma clang fp contract(off)
-  __shared__ double s_val[kSwapThreads];
-  __shared__ int32_t s_arg[kSwapThreads];
-  const int64_t rc = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
+  __shared__ double s_val[kSelectThreads];
+  __shared__ int32_t s_arg[kSelectThreads];
+  const int64_t rc = (int64_t)blockIdx.x * kSelectThreads + threadIdx.x;
   const int64_t pairs = (int64_t)p.E * p.E;
   double q = 0.0;
   const bool live = rc < pairs;
@@ -202,7 +219,7 @@ __global__ __launch_bounds__(kSwapThreads) void swap_q_kernel(SelectParams p) {
   s_val[threadIdx.x] = q;
   s_arg[threadIdx.x] = live ? (int32_t)rc : -1;
   __syncthreads();
-  for (int off = kSwapThreads / 2; off > 0; off >>= 1) {
+  for (int off = kSelectThreads / 2; off > 0; off >>= 1) {
     if ((int)threadIdx.x < off) {
       const int o = threadIdx.x + off;
       const bool take = s_arg[o] >= 0 && (s_arg[threadIdx.x] < 0 || s_val[o] < s_val[threadIdx.x] ||
@@ -323,7 +340,7 @@ extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expe
 
 extern "C" size_t hm_swap_select_workspace_bytes(int32_t E) {
   if (E < 1) return 0;
-  const int64_t blocks = ((int64_t)E * E + hm::kSwapThreads - 1) / hm::kSwapThreads;
+  const int64_t blocks = ((int64_t)E * E + hm::kSelectThreads - 1) / hm::kSelectThreads;
   return (size_t)blocks * (sizeof(double) + sizeof(int32_t)) + 16;
 }
 
@@ -362,13 +379,13 @@ extern "C" hm_status hm_swap_select(int32_t d, const int32_t *U, int32_t G, int3
   p.alpha_intra = alpha_intra;
   p.beta_intra = beta_intra;
   p.Q = Q;
-  p.nblocks = (int32_t)(((int64_t)E * E + kSwapThreads - 1) / kSwapThreads);
+  p.nblocks = (int32_t)(((int64_t)E * E + kSelectThreads - 1) / kSelectThreads);
   p.block_min = (double *)workspace;
   p.block_arg = (int32_t *)(p.block_min + p.nblocks);
   p.best_pair = best_pair;
   p.best_time = best_time;
   hipStream_t stream = (hipStream_t)hip_stream;
-  hipLaunchKernelGGL(swap_q_kernel, dim3(p.nblocks), dim3(kSwapThreads), 0, stream, p);
+  hipLaunchKernelGGL(swap_q_kernel, dim3(p.nblocks), dim3(kSelectThreads), 0, stream, p);
   if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   hipLaunchKernelGGL(swap_argmin_kernel, dim3(1), dim3(kSwapThreads), 0, stream, p);
   return hm_launch_status();
