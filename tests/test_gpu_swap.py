@@ -47,6 +47,22 @@ def test_swap_counts_small_against_definition(hw, oracle):
         assert np.array_equal(Z.cpu().numpy(), ref) and st == st_ref, (trial, G, ng, E, T, K)
 
 
+@pytest.mark.parametrize("G,ng,E,T,K", [(8, 4, 200, 500, 12), (64, 64, 256, 300, 20), (8, 8, 300, 400, 5),
+                                          (4, 2, 33, 1000, 64), (32, 32, 256, 5000, 8), (16, 8, 96, 4097, 3)])
+def test_swap_counts_other_shapes(hw, oracle, G, ng, E, T, K):
+    """K from 3 to 64 (sub-groups of 4 to 64 lanes per token), several rounds per workgroup, expert
+    counts from 33 to 300, dropped slots: against the oracle's incremental update (itself pinned
+    to the definition)."""
+    rng = np.random.default_rng(G * 1000 + E)
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)
+    ids[rng.random((T, K)) < 0.05] = -1                       # dropped slots
+    e2r = rng.integers(0, G, E).astype(np.int32)
+    ref, st_ref = oracle.swap_counts(ids, e2r, G, ng, "incremental")
+    Z, st = _gpu_z(hw, ids, e2r, G, ng)
+    assert st == st_ref == 0
+    assert np.array_equal(Z.cpu().numpy(), ref), (G, ng, E, T, K)
+
+
 @pytest.mark.parametrize("name,placement", [("qwen3", "contiguous"), ("dsv3", "contiguous"), ("skew", "swapped")])
 def test_swap_counts_full_size(hw, oracle, name, placement):
     wl = W.WORKLOADS[name]
