@@ -62,6 +62,8 @@ def main() -> int:
                          "planner: dimension selection + expert-swap planner; table4: the K/E/G grid of the paper's Table IV")
     ap.add_argument("--separate-load", action="store_true",
                     help="call hm_expert_load as its own pair of launches instead of letting hm_plan fill the loads")
+    ap.add_argument("--separate-cuts", action="store_true",
+                    help="planner path: one hm_swap_counts call per group cut instead of one hm_swap_counts_multi")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
     ap.add_argument("--graph", action="store_true",
@@ -502,6 +504,12 @@ def run_planner(args) -> int:
     cuts = sorted(set(U[1:] + [G]))
     Z = {u: torch.empty((E, E, u), dtype=torch.int32, device="cuda") for u in cuts}
     ws = {u: torch.empty(int(B.lib().hm_swap_workspace_bytes(E, u)) // 4 + 4, dtype=torch.int32, device="cuda") for u in cuts}
+    ws_multi = None
+    if not args.separate_cuts:
+        import ctypes
+        nga = (ctypes.c_int32 * len(cuts))(*cuts)
+        ws_multi = torch.empty(int(B.lib().hm_swap_multi_workspace_bytes(E, G, len(cuts), nga)) // 4 + 4,
+                               dtype=torch.int32, device="cuda")
     Q = torch.empty((E, E), dtype=torch.float64, device="cuda")
     bp = torch.zeros(2, dtype=torch.int32, device="cuda")
     bt = torch.zeros(1, dtype=torch.float64, device="cuda")
@@ -517,8 +525,11 @@ def run_planner(args) -> int:
             p_intra = (own[0:1] * fan_in).contiguous()
         B.hm_alltoall_times(U, G, H, 2.0, own, p_intra, ai, bi, aa, ba, times, best_d, stream=stream)
         if ev: ev[2].record(stream)
-        for u in cuts:
-            B.hm_swap_counts(ids_d, e2r_d, G, u, Z[u], workspace=ws[u], stream=stream)
+        if args.separate_cuts:
+            for u in cuts:
+                B.hm_swap_counts(ids_d, e2r_d, G, u, Z[u], workspace=ws[u], stream=stream)
+        else:                                            # all cuts in one pass over the tokens
+            B.hm_swap_counts_multi(ids_d, e2r_d, G, cuts, [Z[u] for u in cuts], workspace=ws_multi, stream=stream)
         if ev: ev[3].record(stream)
         B.hm_swap_select(U, G, H, 2.0, [None] + [Z[u] for u in U[1:]], Z[G], si, float(U[D - 1]), ai, bi, aa[D - 1],
                          ba[D - 1], 10.0, Q, bp, bt, workspace=ws_sel, stream=stream)
@@ -536,7 +547,8 @@ def run_planner(args) -> int:
     for i in range(args.steps):
         step(events[i])
     torch.cuda.synchronize()
-    names = ["hm_group_counts", "hm_alltoall_times", "hm_swap_counts x%d" % len(cuts), "hm_swap_select"]
+    names = ["hm_group_counts", "hm_alltoall_times",
+             ("hm_swap_counts x%d" if args.separate_cuts else "hm_swap_counts_multi (%d cuts)") % len(cuts), "hm_swap_select"]
     kern = {n: round(sum(e[j].elapsed_time(e[j + 1]) for e in events) / args.steps, 5) for j, n in enumerate(names)}
     log("planner on %s (T=%d K=%d E=%d G=%d, U=%s): %.4f ms per step; " % (wl.name, T, K, E, G, U, ms_per_step)
         + ", ".join("%s %.4f ms" % kv for kv in kern.items()))

@@ -300,6 +300,20 @@ hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank,
                          void *hip_stream);
 
 /*
+ * hm_swap_counts_multi -- hm_swap_counts for up to 4 cuts of the ranks in one pass over the tokens
+ * (Section IV needs Z of every Inter-level cut U[i] and of the G-group cut for one Q): ng (host
+ * array of ncuts group counts, each dividing G) and Z (host array of ncuts device pointers,
+ * Z[c] = int32 [E*E*ng[c]]).  Results, status and error rules are those of ncuts separate
+ * hm_swap_counts calls; the work that does not depend on the cut is done once.
+ * workspace: hm_swap_multi_workspace_bytes(E, G, ncuts, ng) bytes of device scratch.
+ */
+size_t hm_swap_multi_workspace_bytes(int32_t E, int32_t G, int32_t ncuts, const int32_t *ng /* host */);
+hm_status hm_swap_counts_multi(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                               int32_t G, int32_t ncuts, const int32_t *ng /* host */,
+                               int32_t *const *Z /* host array of device pointers */, int32_t *status, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
+
+/*
  * hm_swap_select -- Eq.(8)-(10) for dimension d (1..4): the estimated time Q[r*E + c] (device
  * double[E*E]) of the d-dimensional exchange after swapping experts r and c, and the pair with
  * the smallest time (first in row-major order among equals): best_pair (device int32[2]),

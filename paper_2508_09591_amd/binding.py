@@ -26,7 +26,8 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_combine_transpose", "hm_expert_load", "hm_status_string", "hm_recv_dest_map",
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
-           "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply")
+           "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply",
+           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes")
 
 
 class hm_topology(ctypes.Structure):
@@ -72,6 +73,10 @@ def lib():
         L.hm_dispatch_pack.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
         L.hm_combine.restype = ctypes.c_int
         L.hm_combine.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
+        L.hm_swap_multi_workspace_bytes.restype = ctypes.c_size_t
+        L.hm_swap_multi_workspace_bytes.argtypes = [i32, i32, i32, vp]
+        L.hm_swap_counts_multi.restype = ctypes.c_int
+        L.hm_swap_counts_multi.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.hm_swap_apply.restype = ctypes.c_int
         L.hm_swap_apply.argtypes = [vp, i32, vp, vp]
         L.hm_combine_f32.restype = ctypes.c_int
@@ -343,6 +348,26 @@ def hm_swap_counts(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, G: int,
                               T, K, E, G, ng, _dev(Z, torch.int32, "Z"), _dev(status, torch.int32, "status"),
                               workspace.data_ptr(), workspace.numel() * 4, _stream(stream))
     _check("hm_swap_counts", rc)
+    return Z
+
+
+def hm_swap_counts_multi(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, G: int, ng, Z,
+                         status: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """ng: up to 4 group counts; Z: list of int32 [E,E,ng[c]] GPU tensors, one per cut."""
+    T, K = topk_ids.shape
+    E = expert_to_rank.shape[0]
+    n = len(ng)
+    if len(Z) != n:
+        raise ValueError("one Z tensor per cut")
+    nga = (ctypes.c_int32 * n)(*[int(u) for u in ng])
+    zp = (ctypes.c_void_p * n)(*[_dev(z, torch.int32, "Z") for z in Z])
+    need = int(lib().hm_swap_multi_workspace_bytes(E, G, n, nga))
+    if workspace is None:
+        workspace = torch.empty(need // 4 + 4, dtype=torch.int32, device=Z[0].device)
+    rc = lib().hm_swap_counts_multi(_dev(topk_ids, torch.int32, "topk_ids"), _dev(expert_to_rank, torch.int32, "expert_to_rank"),
+                                    T, K, E, G, n, nga, zp, _dev(status, torch.int32, "status"),
+                                    workspace.data_ptr(), workspace.numel() * 4, _stream(stream))
+    _check("hm_swap_counts_multi", rc)
     return Z
 
 

@@ -15,27 +15,35 @@ namespace hm {
 constexpr int kSwapThreads = 256;
 constexpr int kSelectThreads = 64;     // Q per pair: fp64 pow-heavy, so many small workgroups to reach every CU
 constexpr int kFactorThreads = 1024;   // the co-occurrence pass: 16 waves share one set of LDS tables
-constexpr int kSwapLds = 12288;   // ints of LDS for L0 + L + CG (48 KiB)
+constexpr int kSwapLds = 30720;   // most ints of LDS for L0 and every cut's L + CG (120 KiB); larger sets stay in global memory
 constexpr int kSwapCopies = 8;    // private copies of C: popular expert pairs would otherwise serialise on one address
+constexpr int kMaxCuts = 4;       // group cuts handled by one pass over the tokens
 
+// One pass serves up to kMaxCuts cuts of the ranks into groups: everything that does not depend on
+// the cut (ids, placement lookups, which slots repeat an expert) is done once.
 struct SwapParams {
   const int32_t *ids;
   const int32_t *expert_to_rank;
-  int32_t T, K, E, G, ng, per;
-  int32_t sub;     // lanes per token in the co-occurrence pass: the power of two >= K
-  int32_t *base;   // [64]
-  int32_t *L0;     // [E]
-  int32_t *L;      // [E]
-  int32_t *CG;     // [E][ng]
-  int32_t *C;      // [kSwapCopies][E][E]
+  int32_t T, K, E, G;
+  int32_t sub;      // lanes per token in the co-occurrence pass: the power of two >= K
+  int32_t ncuts;
+  int32_t use_lds;  // L0 / L / CG of all cuts accumulate in LDS
+  int32_t ng[kMaxCuts], per[kMaxCuts];
+  int32_t lds_off[kMaxCuts];   // ints: where cut c's [L (E) | CG (E * ng)] starts in LDS; L0 is at 0
+  int32_t *L0;                 // [E]                                  (workspace, shared by the cuts)
+  int32_t *base[kMaxCuts];     // [64]                                 (workspace, per cut)
+  int32_t *L[kMaxCuts];        // [E]
+  int32_t *CG[kMaxCuts];       // [E][ng]
+  int32_t *C[kMaxCuts];        // [kSwapCopies][E][E]
+  int32_t *Z[kMaxCuts];
+  int32_t *ws;                 // start of the workspace and its size in ints (cleared first)
   int64_t ws_ints;
-  int32_t *Z;
   int32_t *status;
 };
 
 __global__ __launch_bounds__(kSwapThreads) void swap_clear_kernel(SwapParams p) {
   const int64_t i = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
-  if (i < p.ws_ints) p.base[i] = 0;   // the factor tables are contiguous behind base
+  if (i < p.ws_ints) p.ws[i] = 0;
   if (i == 0 && p.status) *p.status = 0;
 }
 
@@ -44,14 +52,18 @@ __global__ __launch_bounds__(kSwapThreads) void swap_clear_kernel(SwapParams p) 
 // per-token work -- K expert updates, K * groups and up to K * K co-occurrence updates -- is spread
 // over K lanes instead of being a serial loop of one lane.
 __global__ __launch_bounds__(kFactorThreads) void swap_factors_kernel(SwapParams p) {
-  __shared__ int32_t lds[kSwapLds];
-  __shared__ int32_t base_cnt[kWave];
-  const int small = p.E * (p.ng + 2);
-  const bool use_lds = small <= kSwapLds;
-  int32_t *sL0 = lds, *sL = lds + p.E, *sCG = lds + 2 * p.E;
-  if (use_lds)
-    for (int i = threadIdx.x; i < small; i += kFactorThreads) lds[i] = 0;
-  if (threadIdx.x < kWave) base_cnt[threadIdx.x] = 0;
+  extern __shared__ int32_t lds[];   // L0 and every cut's L + CG, sized by the launch
+  __shared__ int32_t base_cnt[kMaxCuts][kWave];
+  __shared__ uint8_t group_of[kMaxCuts][kWave];   // rank -> group under each cut
+  if (p.use_lds) {
+    const int used = p.lds_off[p.ncuts - 1] + p.E * (p.ng[p.ncuts - 1] + 1);
+    for (int i = threadIdx.x; i < used; i += kFactorThreads) lds[i] = 0;
+  }
+  if (threadIdx.x < kMaxCuts * kWave) {
+    const int c = threadIdx.x / kWave, r = threadIdx.x % kWave;
+    base_cnt[c][r] = 0;
+    group_of[c][r] = (uint8_t)(c < p.ncuts ? r / p.per[c] : 0);
+  }
   __syncthreads();
 
   const int lane = lane_id();
@@ -62,94 +74,127 @@ __global__ __launch_bounds__(kFactorThreads) void swap_factors_kernel(SwapParams
   const int64_t nwaves = (int64_t)gridDim.x * (kFactorThreads / kWave);
   const int64_t per_round = nwaves * tokens_per_wave;
   const int64_t rounds = ((int64_t)p.T + per_round - 1) / per_round;
-  int32_t *myC = p.C + (int64_t)(blockIdx.x % kSwapCopies) * p.E * p.E;
-  int my_base = 0;
+  const int64_t copy_off = (int64_t)(blockIdx.x % kSwapCopies) * p.E * p.E;
+  int my_base[kMaxCuts] = {0, 0, 0, 0};
   for (int64_t it = 0; it < rounds; ++it) {
     const int64_t t = (it * nwaves + wave) * tokens_per_wave + lane / p.sub;
-    int a = -1, grp = -1;   // my expert and its group; -1 when the slot is empty, dropped or invalid
+    int a = -1, g = -1;   // my expert and its rank; -1 when the slot is empty, dropped or invalid
     if (t < p.T && k < p.K) {
       const int id = p.ids[t * p.K + k];
-      const int g = rank_of(p.expert_to_rank, p.E, p.G, id);
-      if (g == -1) flag(p.status, HM_ERR_BAD_ID);
-      if (g >= 0) {
+      const int r = rank_of(p.expert_to_rank, p.E, p.G, id);
+      if (r == -1) flag(p.status, HM_ERR_BAD_ID);
+      if (r >= 0) {
         a = id;
-        grp = g / p.per;
+        g = r;
       }
     }
     // the selected experts form a set: `first` marks the first valid occurrence of each
     bool first = a >= 0;
-    uint64_t gm = 0;
+    uint64_t gm[kMaxCuts] = {0, 0, 0, 0};   // groups the token touches, per cut
     for (int k1 = 0; k1 < p.K; ++k1) {
       const int a1 = __shfl(a, sub0 + k1, kWave);
-      const int g1 = __shfl(grp, sub0 + k1, kWave);
-      if (g1 >= 0) gm |= 1ull << g1;
+      const int g1 = __shfl(g, sub0 + k1, kWave);
       if (k1 < k && a1 == a) first = false;
+      if (g1 >= 0) {
+#pragma unroll
+        for (int c = 0; c < kMaxCuts; ++c)
+          if (c < p.ncuts) gm[c] |= 1ull << group_of[c][g1];
+      }
     }
-    int in_group = 0;   // distinct selected experts in my expert's group
+    int in_group[kMaxCuts] = {0, 0, 0, 0};   // distinct selected experts in my expert's group
     for (int k1 = 0; k1 < p.K; ++k1) {
       const int f1 = __shfl((int)first, sub0 + k1, kWave);
-      const int g1 = __shfl(grp, sub0 + k1, kWave);
-      in_group += (f1 && g1 == grp) ? 1 : 0;
+      const int g1 = __shfl(g, sub0 + k1, kWave);
+      if (f1 && g >= 0) {
+#pragma unroll
+        for (int c = 0; c < kMaxCuts; ++c)
+          if (c < p.ncuts) in_group[c] += group_of[c][g1] == group_of[c][g] ? 1 : 0;
+      }
     }
-    const bool alone = first && in_group == 1;
+    bool alone[kMaxCuts];
+    bool any_alone = false;
+#pragma unroll
+    for (int c = 0; c < kMaxCuts; ++c) {
+      alone[c] = c < p.ncuts && first && in_group[c] == 1;
+      any_alone = any_alone || alone[c];
+    }
     if (first) {
-      if (use_lds) {
-        atomicAdd(&sL0[a], 1);
-        if (alone) atomicAdd(&sL[a], 1);
-        for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&sCG[a * p.ng + __builtin_ctzll(m)], 1);
-      } else {
-        atomicAdd(&p.L0[a], 1);
-        if (alone) atomicAdd(&p.L[a], 1);
-        for (uint64_t m = gm; m; m &= m - 1) atomicAdd(&p.CG[(int64_t)a * p.ng + __builtin_ctzll(m)], 1);
+      if (p.use_lds) atomicAdd(&lds[a], 1);
+      else atomicAdd(&p.L0[a], 1);
+#pragma unroll
+      for (int c = 0; c < kMaxCuts; ++c) {
+        if (c < p.ncuts) {
+          int32_t *tL = p.use_lds ? lds + p.lds_off[c] : p.L[c];
+          int32_t *tCG = p.use_lds ? lds + p.lds_off[c] + p.E : p.CG[c];
+          if (alone[c]) atomicAdd(&tL[a], 1);
+          for (uint64_t m = gm[c]; m; m &= m - 1) atomicAdd(&tCG[a * p.ng[c] + __builtin_ctzll(m)], 1);
+        }
       }
     }
     for (int k1 = 0; k1 < p.K; ++k1) {
       const int a1 = __shfl(a, sub0 + k1, kWave);
       const int f1 = __shfl((int)first, sub0 + k1, kWave);
-      if (alone && f1 && a1 != a) atomicAdd(&myC[(int64_t)a * p.E + a1], 1);
+      if (any_alone && f1 && a1 != a) {
+#pragma unroll
+        for (int c = 0; c < kMaxCuts; ++c)
+          if (alone[c]) atomicAdd(&p.C[c][copy_off + (int64_t)a * p.E + a1], 1);
+      }
     }
     const bool leader = k == 0 && t < p.T;   // one lane per token counts the token's groups
-    for (int j = 0; j < p.ng; ++j) {
-      const uint64_t b = __ballot(leader && ((gm >> j) & 1ull));
-      if (lane == j) my_base += __popcll(b);
+#pragma unroll
+    for (int c = 0; c < kMaxCuts; ++c) {
+      if (c < p.ncuts) {
+        for (int j = 0; j < p.ng[c]; ++j) {
+          const uint64_t b = __ballot(leader && ((gm[c] >> j) & 1ull));
+          if (lane == j) my_base[c] += __popcll(b);
+        }
+      }
     }
   }
-  if (lane < p.ng && my_base) atomicAdd(&base_cnt[lane], my_base);
+#pragma unroll
+  for (int c = 0; c < kMaxCuts; ++c)
+    if (c < p.ncuts && lane < p.ng[c] && my_base[c]) atomicAdd(&base_cnt[c][lane], my_base[c]);
   __syncthreads();
-  if ((int)threadIdx.x < p.ng && base_cnt[threadIdx.x]) atomicAdd(&p.base[threadIdx.x], base_cnt[threadIdx.x]);
-  if (use_lds) {
-    for (int i = threadIdx.x; i < p.E; i += kFactorThreads) {
-      if (sL0[i]) atomicAdd(&p.L0[i], sL0[i]);
-      if (sL[i]) atomicAdd(&p.L[i], sL[i]);
+  for (int c = 0; c < p.ncuts; ++c) {
+    if ((int)threadIdx.x < p.ng[c] && base_cnt[c][threadIdx.x]) atomicAdd(&p.base[c][threadIdx.x], base_cnt[c][threadIdx.x]);
+    if (p.use_lds) {
+      const int32_t *sL = lds + p.lds_off[c], *sCG = sL + p.E;
+      for (int i = threadIdx.x; i < p.E; i += kFactorThreads)
+        if (sL[i]) atomicAdd(&p.L[c][i], sL[i]);
+      for (int i = threadIdx.x; i < p.E * p.ng[c]; i += kFactorThreads)
+        if (sCG[i]) atomicAdd(&p.CG[c][i], sCG[i]);
     }
-    for (int i = threadIdx.x; i < p.E * p.ng; i += kFactorThreads)
-      if (sCG[i]) atomicAdd(&p.CG[i], sCG[i]);
   }
+  if (p.use_lds)
+    for (int i = threadIdx.x; i < p.E; i += kFactorThreads)
+      if (lds[i]) atomicAdd(&p.L0[i], lds[i]);
 }
 
-// One lane per element of Z.
+// One lane per element of Z; blockIdx.y is the cut.
 __global__ __launch_bounds__(kSwapThreads) void swap_build_kernel(SwapParams p) {
+  const int cut = blockIdx.y;
+  const int ng = p.ng[cut], per = p.per[cut];
   const int64_t i = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
-  const int64_t total = (int64_t)p.E * p.E * p.ng;
+  const int64_t total = (int64_t)p.E * p.E * ng;
   if (i >= total) return;
-  const int j = (int)(i % p.ng);
-  const int64_t rc = i / p.ng;
+  const int j = (int)(i % ng);
+  const int64_t rc = i / ng;
   const int r = (int)(rc / p.E), c = (int)(rc % p.E);
-  int val = p.base[j];
+  int val = p.base[cut][j];
   const int rr = p.expert_to_rank[r], rk = p.expert_to_rank[c];
   const bool valid = (unsigned)rr < (unsigned)p.G && (unsigned)rk < (unsigned)p.G;
   if (!valid) {
     if (j == 0) flag(p.status, HM_ERR_BAD_ID);
   } else {
-    const int gr = rr / p.per, gc = rk / p.per;
+    const int gr = rr / per, gc = rk / per;
     if (gr != gc && (j == gc || j == gr)) {
       const int a = j == gc ? r : c, b = j == gc ? c : r;   // group j gains tokens of a, loses tokens of b
       int cba = 0;
-      for (int k = 0; k < kSwapCopies; ++k) cba += p.C[((int64_t)k * p.E + b) * p.E + a];
-      val += (p.L0[a] - p.CG[(int64_t)a * p.ng + j]) - (p.L[b] - cba);
+      for (int k = 0; k < kSwapCopies; ++k) cba += p.C[cut][((int64_t)k * p.E + b) * p.E + a];
+      val += (p.L0[a] - p.CG[cut][(int64_t)a * ng + j]) - (p.L[cut][b] - cba);
     }
   }
-  p.Z[i] = val;
+  p.Z[cut][i] = val;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -282,26 +327,31 @@ __global__ void swap_apply_kernel(int32_t *__restrict__ expert_to_rank, int32_t 
   expert_to_rank[c] = g;
 }
 
-static inline int64_t swap_ws_ints(int64_t E, int64_t ng) { return 64 + 2 * E + E * ng + kSwapCopies * E * E; }
-
-}  // namespace hm
-
-extern "C" size_t hm_swap_workspace_bytes(int32_t E, int32_t ng) {
-  if (E < 1 || ng < 1 || ng > 64) return 0;
-  return (size_t)hm::swap_ws_ints(E, ng) * sizeof(int32_t);
+// The co-occurrence kernel may use more dynamic LDS than a kernel gets by default (64 KiB); ask
+// once.  False: the tables stay in global memory.
+static bool swap_factors_lds_ready() {
+  static const bool ok = [] {
+    const hipError_t e = hipFuncSetAttribute((const void *)swap_factors_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             kSwapLds * (int)sizeof(int32_t));
+    if (e != hipSuccess) (void)hipGetLastError();   // not sticky: do not let it fail the next launch check
+    return e == hipSuccess;
+  }();
+  return ok;
 }
 
-extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
-                                    int32_t E, int32_t G, int32_t ng, int32_t *Z, int32_t *status, void *workspace,
-                                    size_t workspace_bytes, void *hip_stream) {
-  using namespace hm;
-  if (!expert_to_rank || !Z || !workspace) return HM_ERR_NULL;
-  hm_status st = hm_check_tk(T, K);
-  if (st != HM_OK) return st;
-  if (E < 1 || (int64_t)E * E * 64 > 2147483647LL) return HM_ERR_SHAPE;
-  if (T > 0 && !topk_ids) return HM_ERR_NULL;
-  if (G < 1 || G > 64 || ng < 1 || ng > G || G % ng != 0) return HM_ERR_TOPOLOGY;
-  if (workspace_bytes < hm_swap_workspace_bytes(E, ng)) return HM_ERR_WORKSPACE;
+// Workspace, in ints: L0 [E], then per cut base [64] | L [E] | CG [E * ng] | C [kSwapCopies * E * E].
+static inline int64_t swap_cut_ints(int64_t E, int64_t ng) { return 64 + E + E * ng + kSwapCopies * E * E; }
+
+static inline bool swap_cuts_ok(int32_t G, int32_t ncuts, const int32_t *ng) {
+  if (G < 1 || G > 64 || ncuts < 1 || ncuts > kMaxCuts || !ng) return false;
+  for (int c = 0; c < ncuts; ++c)
+    if (ng[c] < 1 || ng[c] > G || G % ng[c] != 0) return false;
+  return true;
+}
+
+static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                                    int32_t G, int32_t ncuts, const int32_t *ng, int32_t *const *Z, int32_t *status,
+                                    void *workspace, hipStream_t stream) {
   SwapParams p;
   p.ids = topk_ids;
   p.expert_to_rank = expert_to_rank;
@@ -309,19 +359,37 @@ extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expe
   p.K = K;
   p.E = E;
   p.G = G;
-  p.ng = ng;
-  p.per = G / ng;
+  p.ncuts = ncuts;
   p.sub = 1;
   while (p.sub < K) p.sub *= 2;
-  p.base = (int32_t *)workspace;
-  p.L0 = p.base + 64;
-  p.L = p.L0 + E;
-  p.CG = p.L + E;
-  p.C = p.CG + (int64_t)E * ng;
-  p.ws_ints = swap_ws_ints(E, ng);
-  p.Z = Z;
+  p.ws = (int32_t *)workspace;
+  p.L0 = p.ws;
+  int64_t at = E, lds_at = E, max_ng = 1;
+  for (int c = 0; c < kMaxCuts; ++c) {
+    const int cc = c < ncuts ? c : 0;   // unused entries repeat cut 0 so that no pointer is left dangling
+    p.ng[c] = ng[cc];
+    p.per[c] = G / ng[cc];
+    p.Z[c] = Z[cc];
+    if (c < ncuts) {
+      p.base[c] = p.ws + at;
+      p.L[c] = p.base[c] + 64;
+      p.CG[c] = p.L[c] + E;
+      p.C[c] = p.CG[c] + (int64_t)E * ng[c];
+      at += swap_cut_ints(E, ng[c]);
+      p.lds_off[c] = (int32_t)lds_at;
+      lds_at += (int64_t)E * (ng[c] + 1);
+      if (ng[c] > max_ng) max_ng = ng[c];
+    } else {
+      p.base[c] = p.base[0];
+      p.L[c] = p.L[0];
+      p.CG[c] = p.CG[0];
+      p.C[c] = p.C[0];
+      p.lds_off[c] = p.lds_off[0];
+    }
+  }
+  p.ws_ints = at;
+  p.use_lds = (lds_at <= kSwapLds && swap_factors_lds_ready()) ? 1 : 0;
   p.status = status;
-  hipStream_t stream = (hipStream_t)hip_stream;
   hipLaunchKernelGGL(swap_clear_kernel, dim3((unsigned)((p.ws_ints + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads),
                      0, stream, p);
   if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
@@ -329,13 +397,62 @@ extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expe
     const int64_t tokens_per_block = (int64_t)(kFactorThreads / kWave) * (kWave / p.sub);
     int64_t blocks = ((int64_t)T + tokens_per_block - 1) / tokens_per_block;
     if (blocks > 256) blocks = 256;   // one per CU; every block flushes its LDS tables with atomics
-    hipLaunchKernelGGL(swap_factors_kernel, dim3((unsigned)blocks), dim3(kFactorThreads), 0, stream, p);
+    hipLaunchKernelGGL(swap_factors_kernel, dim3((unsigned)blocks), dim3(kFactorThreads),
+                       p.use_lds ? (size_t)lds_at * sizeof(int32_t) : 0, stream, p);
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   }
-  const int64_t total = (int64_t)E * E * ng;
-  hipLaunchKernelGGL(swap_build_kernel, dim3((unsigned)((total + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads), 0,
-                     stream, p);
+  const int64_t total = (int64_t)E * E * max_ng;
+  hipLaunchKernelGGL(swap_build_kernel, dim3((unsigned)((total + kSwapThreads - 1) / kSwapThreads), (unsigned)ncuts),
+                     dim3(kSwapThreads), 0, stream, p);
   return hm_launch_status();
+}
+
+}  // namespace hm
+
+extern "C" size_t hm_swap_multi_workspace_bytes(int32_t E, int32_t G, int32_t ncuts, const int32_t *ng) {
+  if (E < 1 || !hm::swap_cuts_ok(G, ncuts, ng)) return 0;
+  int64_t ints = E;
+  for (int c = 0; c < ncuts; ++c) ints += hm::swap_cut_ints(E, ng[c]);
+  return (size_t)ints * sizeof(int32_t);
+}
+
+extern "C" size_t hm_swap_workspace_bytes(int32_t E, int32_t ng) {
+  if (E < 1 || ng < 1 || ng > 64) return 0;
+  return (size_t)(E + hm::swap_cut_ints(E, ng)) * sizeof(int32_t);
+}
+
+static hm_status swap_counts_checks(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
+                                    const void *workspace) {
+  if (!expert_to_rank || !workspace) return HM_ERR_NULL;
+  hm_status st = hm_check_tk(T, K);
+  if (st != HM_OK) return st;
+  if (E < 1 || (int64_t)E * E * 64 > 2147483647LL) return HM_ERR_SHAPE;
+  if (T > 0 && !topk_ids) return HM_ERR_NULL;
+  return HM_OK;
+}
+
+extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
+                                    int32_t E, int32_t G, int32_t ng, int32_t *Z, int32_t *status, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream) {
+  if (!Z) return HM_ERR_NULL;
+  hm_status st = swap_counts_checks(topk_ids, expert_to_rank, T, K, E, workspace);
+  if (st != HM_OK) return st;
+  if (!hm::swap_cuts_ok(G, 1, &ng)) return HM_ERR_TOPOLOGY;
+  if (workspace_bytes < hm_swap_workspace_bytes(E, ng)) return HM_ERR_WORKSPACE;
+  return hm::swap_counts_launch(topk_ids, expert_to_rank, T, K, E, G, 1, &ng, &Z, status, workspace, (hipStream_t)hip_stream);
+}
+
+extern "C" hm_status hm_swap_counts_multi(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
+                                          int32_t E, int32_t G, int32_t ncuts, const int32_t *ng, int32_t *const *Z,
+                                          int32_t *status, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  if (!Z || !ng) return HM_ERR_NULL;
+  hm_status st = swap_counts_checks(topk_ids, expert_to_rank, T, K, E, workspace);
+  if (st != HM_OK) return st;
+  if (!hm::swap_cuts_ok(G, ncuts, ng)) return HM_ERR_TOPOLOGY;
+  for (int c = 0; c < ncuts; ++c)
+    if (!Z[c]) return HM_ERR_NULL;
+  if (workspace_bytes < hm_swap_multi_workspace_bytes(E, G, ncuts, ng)) return HM_ERR_WORKSPACE;
+  return hm::swap_counts_launch(topk_ids, expert_to_rank, T, K, E, G, ncuts, ng, Z, status, workspace, (hipStream_t)hip_stream);
 }
 
 extern "C" size_t hm_swap_select_workspace_bytes(int32_t E) {

@@ -63,6 +63,36 @@ def test_swap_counts_other_shapes(hw, oracle, G, ng, E, T, K):
     assert np.array_equal(Z.cpu().numpy(), ref), (G, ng, E, T, K)
 
 
+@pytest.mark.parametrize("name,T,cuts", [("skew", 16384, [4, 8, 16, 32]), ("dsv3", 3000, [32, 4]), ("qwen3", 2000, [1, 2, 32]),
+                                         ("stress", 1500, [64, 8, 16, 2])])
+def test_swap_counts_multi_equals_separate_calls(hw, oracle, name, T, cuts):
+    """Several cuts in one pass: every Z must equal the oracle's (and so the single-cut call's)."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS[name]
+    r = W.make_routing(wl, T=T)
+    e2r = r.extras.get("expert_to_rank_swapped", r.expert_to_rank) if hasattr(r, "extras") and r.extras else r.expert_to_rank
+    ids = r.topk_ids.copy()
+    ids[5, 1] = -1                                            # a dropped slot
+    E, G = wl.E, wl.G
+    Z = [torch.full((E, E, u), -9, dtype=torch.int32, device="cuda") for u in cuts]
+    st = torch.full((1,), 5, dtype=torch.int32, device="cuda")
+    B.hm_swap_counts_multi(hw.dev(ids), hw.dev(e2r), G, cuts, Z, st)
+    assert int(st.item()) == 0
+    for u, z in zip(cuts, Z):
+        ref, _ = oracle.swap_counts(ids, e2r, G, u, "incremental")
+        assert np.array_equal(z.cpu().numpy(), ref), (name, u)
+    # an invalid id and an invalid placement entry: flagged, every cut follows the single-cut rule
+    ids[7, 0] = E + 3
+    bad = e2r.copy()
+    bad[2] = G
+    B.hm_swap_counts_multi(hw.dev(ids), hw.dev(bad), G, cuts, Z, st)
+    assert int(st.item()) == B.HM_ERR_BAD_ID
+    for u, z in zip(cuts, Z):
+        ref, st_ref = oracle.swap_counts(ids, bad, G, u, "incremental")
+        assert st_ref == B.HM_ERR_BAD_ID and np.array_equal(z.cpu().numpy(), ref), (name, u, "bad")
+
+
 @pytest.mark.parametrize("name,placement", [("qwen3", "contiguous"), ("dsv3", "contiguous"), ("skew", "swapped")])
 def test_swap_counts_full_size(hw, oracle, name, placement):
     wl = W.WORKLOADS[name]
