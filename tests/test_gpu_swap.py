@@ -48,7 +48,8 @@ def test_swap_counts_small_against_definition(hw, oracle):
 
 
 @pytest.mark.parametrize("G,ng,E,T,K", [(8, 4, 200, 500, 12), (64, 64, 256, 300, 20), (8, 8, 300, 400, 5),
-                                          (4, 2, 33, 1000, 64), (32, 32, 256, 5000, 8), (16, 8, 96, 4097, 3)])
+                                          (4, 2, 33, 1000, 64), (32, 32, 256, 5000, 8), (16, 8, 96, 4097, 3),
+                                          (64, 64, 512, 700, 6)])      # the last: tables too large for LDS
 def test_swap_counts_other_shapes(hw, oracle, G, ng, E, T, K):
     """K from 3 to 64 (sub-groups of 4 to 64 lanes per token), several rounds per workgroup, expert
     counts from 33 to 300, dropped slots: against the oracle's incremental update (itself pinned
