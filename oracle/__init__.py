@@ -179,6 +179,23 @@ def combine_transpose(gout: np.ndarray, row_token, row_weight) -> np.ndarray:
     return gy
 
 
+def combine_transpose_bf16(gout_bf16: np.ndarray, row_token, row_weight) -> np.ndarray:
+    """gy[row] = bf16(row_weight[row] * gout[row_token[row]]), one rounding; uint16 bf16 encodings."""
+    lib = _load()
+    g = _c(gout_bf16, np.uint16)
+    rt = _c(row_token, np.int32)
+    rw = _c(row_weight, np.float32)
+    T, H = g.shape
+    gy = np.empty((rt.shape[0], H), np.uint16)
+    if gy.size == 0:
+        return gy
+    rc = lib.hmo_combine_transpose_bf16(_p(g), ctypes.c_int64(T), ctypes.c_int64(H), _p(rt), _p(rw),
+                                        ctypes.c_int64(rt.shape[0]), _p(gy))
+    if rc != 0:
+        raise ValueError("hmo_combine_transpose_bf16: argument error %d" % rc)
+    return gy
+
+
 def expert_load(topk_ids, expert_to_rank, nodes: int, ranks_per_node: int):
     """(load_expert[E], load_rank[G], load_node[nodes], status)."""
     lib = _load()

@@ -276,6 +276,26 @@ int hmo_combine_transpose(const float *gout, int64_t T, int64_t H, const int32_t
 }
 
 /*
+ * hmo_combine_transpose_bf16 -- the adjoint of hmo_combine for gradients kept in bf16 (the element
+ * width of a row is free in the paper, Section II-B):
+ *     gy[row][j] = bf16( row_weight[row] * gout[row_token[row]][j] ),
+ * the exact product (a binary32 times a bf16 value has at most 32 significant bits: exact in
+ * binary64) rounded once to bf16.
+ */
+int hmo_combine_transpose_bf16(const uint16_t *gout, int64_t T, int64_t H, const int32_t *row_token,
+                               const float *row_weight, int64_t n_rows, uint16_t *gy)
+{
+    if (!gout || !row_token || !row_weight || !gy || T < 0 || H <= 0 || n_rows < 0) return HMO_ERR_ARG;
+    for (int64_t row = 0; row < n_rows; ++row) {
+        const int32_t t = row_token[row];
+        if (t < 0 || t >= T) return HMO_ERR_ARG;
+        for (int64_t j = 0; j < H; ++j)
+            gy[row * H + j] = f64_to_bf16_rne((double)row_weight[row] * bf16_to_f64(gout[(int64_t)t * H + j]));
+    }
+    return HMO_OK;
+}
+
+/*
  * hmo_expert_load -- the counts an expert-swap planner consumes (Section IV): the raw number of
  * slots per expert (what duplicate-unaware planners count) and the duplicate-free number of tokens
  * per rank, p^(1,G), and per node, p^(1,U[1]), of Eq.(7).  Written from the set definition: a

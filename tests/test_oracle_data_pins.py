@@ -250,3 +250,53 @@ def test_transpose_is_adjoint_and_one_multiply(oracle, level):
     np.add.at(rw64, p.slot_row.reshape(-1), r.topk_weights.astype(np.float64).reshape(-1))
     rhs64 = float((y * (rw64[:, None] * gout.astype(np.float64)[p.row_token])).sum())
     assert abs(lhs - rhs64) <= 1e-12 * scale
+
+
+def test_transpose_bf16_exact_products_and_double_rounding_trap(oracle):
+    """Gradients in bf16: the product is rounded ONCE to bf16.  Checked against exact rational
+    arithmetic on a plan with merged rows, on a weight of one (bit copy), and on a product whose
+    binary32 rounding lands on a bf16 tie, so that rounding twice gives the other neighbour."""
+    wl = W.WORKLOADS["qwen3"]
+    T, H = 40, 9
+    r = W.make_routing(wl, T=T)
+    rng = np.random.default_rng(23)
+    for level in (NONE, NODE):
+        p = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        g = W.f32_to_bf16_bits((rng.standard_normal((T, H)) * 1e-2).astype(np.float32))
+        gy = oracle.combine_transpose_bf16(g, p.row_token, p.row_weight)
+        assert gy.shape == (p.total_rows, H) and gy.dtype == np.uint16
+        gf = W.bf16_bits_to_f64(g)
+        for row in range(0, p.total_rows, 7):
+            for j in range(H):
+                q = Fraction(float(p.row_weight[row])) * Fraction(float(gf[p.row_token[row], j]))
+                assert int(gy[row, j]) == exact_round_to_bf16(q), (level, row, j)
+    # weight one: the row comes back bit for bit
+    ones = np.ones(p.total_rows, np.float32)
+    assert np.array_equal(oracle.combine_transpose_bf16(g, p.row_token, ones), g[p.row_token])
+    # w = 1 + 2^-8 + 2^-17 (24 significant bits), g = 1 + 2^-7: the product is
+    # 1 + 2^-7 + 2^-8 + 2^-15 + 2^-17 + 2^-24, above the bf16 tie 1 + 2^-7 + 2^-8 -> rounds up to
+    # 1 + 2^-6; with w = 1 + 2^-8 exactly the product is 1 + 2^-7 + 2^-8 + 2^-15: still above the tie.
+    # Below the tie: w = 1 + 2^-8 - 2^-14 gives 1 + 2^-7 + 2^-8 - 2^-14 + ... -> rounds down.
+    one_p = W.f32_to_bf16_bits(np.array([[1.0 + 2.0 ** -7]], np.float32))
+    for w, want in ((1.0 + 2.0 ** -8 + 2.0 ** -17, 1.0 + 2.0 ** -6), (1.0 + 2.0 ** -8 - 2.0 ** -14, 1.0 + 2.0 ** -7)):
+        wv = np.array([w], np.float32)
+        assert float(wv[0]) == w
+        out = oracle.combine_transpose_bf16(one_p, np.array([0], np.int32), wv)
+        q = Fraction(w) * Fraction(1.0 + 2.0 ** -7)
+        assert exact_round_to_bf16(q) == int(W.f32_to_bf16_bits(np.array([want], np.float32))[0])
+        assert int(out[0, 0]) == exact_round_to_bf16(q)
+    # the double-rounding trap proper: the exact product lies just above a bf16 tie but its
+    # binary32 rounding lands ON the tie, whose even neighbour is the lower one
+    # (around w * g = 1 + 2^-6 + 2^-8, the tie between an even and an odd bf16 value)
+    found = 0
+    gb = W.f32_to_bf16_bits(np.array([[1.0 + 2.0 ** -7]], np.float32))
+    for n in range(97000, 98100):
+        w = np.float32(1.0 + n * 2.0 ** -23)
+        q = Fraction(float(w)) * Fraction(1.0 + 2.0 ** -7)
+        once = exact_round_to_bf16(q)
+        twice = int(W.f32_to_bf16_bits(np.array([np.float32(float(w) * (1.0 + 2.0 ** -7))], np.float32))[0])
+        if once != twice:
+            found += 1
+            out = oracle.combine_transpose_bf16(gb, np.array([0], np.int32), np.array([w], np.float32))
+            assert int(out[0, 0]) == once
+    assert found > 0

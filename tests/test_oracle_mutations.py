@@ -49,6 +49,10 @@ MUTATIONS = [
      "volatile float p = row_weight[row] * gout[(int64_t)t * H + j];",
      "volatile float p = row_weight[t % n_rows] * gout[(int64_t)t * H + j];",
      [("test_oracle_data_pins:test_transpose_is_adjoint_and_one_multiply", dict(level=1))]),
+    ("bf16 transpose rounds twice (binary32, then bf16)",
+     "gy[row * H + j] = f64_to_bf16_rne((double)row_weight[row] * bf16_to_f64(gout[(int64_t)t * H + j]));",
+     "gy[row * H + j] = f64_to_bf16_rne((double)(float)((double)row_weight[row] * bf16_to_f64(gout[(int64_t)t * H + j])));",
+     ["test_oracle_data_pins:test_transpose_bf16_exact_products_and_double_rounding_trap"]),
     ("load_rank counts slots, not tokens",
      "in_rank[rank] = 1;", "in_rank[rank] += 1;",
      [("test_oracle_plan_pins:test_level_invariants", dict(name="qwen3"))]),
