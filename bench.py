@@ -249,6 +249,21 @@ def main() -> int:
         tb = (1 + c) * T * 4 * H
         log("hm_combine_transpose: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
             % (tms, tb / (tms * 1e-3) / 1e9, 100 * tb / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
+        del gy
+        gout16 = gout.to(torch.bfloat16)
+        gy16 = torch.empty((total_rows, H), dtype=torch.bfloat16, device="cuda")
+        with torch.cuda.stream(stream):
+            for i in range(args.warmup):
+                B.hm_combine_transpose_bf16(gout16, plan, gy16, stream=stream)
+            for a, b in evs:
+                a.record(stream)
+                B.hm_combine_transpose_bf16(gout16, plan, gy16, stream=stream)
+                b.record(stream)
+        torch.cuda.synchronize()
+        tms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+        log("hm_combine_transpose_bf16: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
+            % (tms, tb / 2 / (tms * 1e-3) / 1e9, 100 * tb / 2 / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
+        del gout16, gy16
 
     if args.with_f32:
         y32 = torch.randn((total_rows, H), dtype=torch.float32, device="cuda")

@@ -170,6 +170,17 @@ hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t 
                                float *gy, int64_t gy_rows, void *hip_stream);
 
 /*
+ * hm_combine_transpose_bf16 -- hm_combine_transpose for gradients kept in bf16 (the element
+ * width of a row is free in the paper: the `v` of Section II-B):
+ *     gy[row,:] = bf16( row_weight[row] * gout[t,:] ),  the exact product rounded once (the fp32
+ * product's own rounding error, recovered with one fma, settles the cases where rounding twice
+ * would differ).  gout [T,H] bf16, gy [gy_rows,H] bf16; fast path needs H % 8 == 0 and 16-byte
+ * aligned buffers.  Errors as hm_combine_transpose.
+ */
+hm_status hm_combine_transpose_bf16(const void *gout_bf16, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
+                                    void *gy_bf16, int64_t gy_rows, void *hip_stream);
+
+/*
  * hm_expert_load -- the counts the expert-swap planner of Section IV consumes:
  *   load_expert[E]   slots per expert (duplicate-unaware, what SmartMoE-style planners count)
  *   load_rank [G]    tokens per rank after deduplication  = p^(1,G)    of Eq.(7)

@@ -27,7 +27,7 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
            "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply",
-           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes")
+           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16")
 
 
 class hm_topology(ctypes.Structure):
@@ -83,6 +83,8 @@ def lib():
         L.hm_combine_f32.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
         L.hm_combine_transpose.restype = ctypes.c_int
         L.hm_combine_transpose.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
+        L.hm_combine_transpose_bf16.restype = ctypes.c_int
+        L.hm_combine_transpose_bf16.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
         L.hm_expert_load.restype = ctypes.c_int
         L.hm_expert_load.argtypes = [vp, vp, i32, i32, i32, hm_topology, vp, vp, vp, vp, vp]
         L.hm_recv_dest_map.restype = ctypes.c_int
@@ -259,6 +261,14 @@ def hm_combine_transpose(gout: torch.Tensor, plan: Plan, gy: torch.Tensor, strea
     rc = lib().hm_combine_transpose(_dev(gout, torch.float32, "gout"), T, plan.K, H, plan.ref(),
                                     _dev(gy, torch.float32, "gy"), gy.shape[0], _stream(stream))
     _check("hm_combine_transpose", rc)
+    return gy
+
+
+def hm_combine_transpose_bf16(gout: torch.Tensor, plan: Plan, gy: torch.Tensor, stream=None) -> torch.Tensor:
+    T, H = gout.shape
+    rc = lib().hm_combine_transpose_bf16(_dev(gout, torch.bfloat16, "gout"), T, plan.K, H, plan.ref(),
+                                         _dev(gy, torch.bfloat16, "gy"), gy.shape[0], _stream(stream))
+    _check("hm_combine_transpose_bf16", rc)
     return gy
 
 

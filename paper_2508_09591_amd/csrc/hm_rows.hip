@@ -136,6 +136,31 @@ struct RowBf16 {
   }
   static __device__ __forceinline__ float widen(elem v) { return __builtin_bit_cast(float, (uint32_t)v << 16); }
   static __device__ __forceinline__ elem narrow(float f) { return (elem)f32_to_bf16(f); }
+  // bf16(a * g) with ONE rounding.  The fp32 product p is already rounded; a second rounding to
+  // bf16 differs from the exact one only when p sits exactly on a bf16 tie, and there the sign of
+  // the product's rounding error e = fma(a, g, -p) (exact) says on which side the true value lies.
+  static __device__ __forceinline__ uint32_t scale1(float a, float g) {
+    const float p = a * g;
+    const float e = __builtin_fmaf(a, g, -p);
+    const uint32_t u = __builtin_bit_cast(uint32_t, p);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;   // NaN
+    // round to nearest: add 0x7FFF plus a tie bit -- the kept lsb (ties to even) in general, but on
+    // an exact tie of p with e != 0 the side the true product lies on
+    const bool tie = (u & 0xFFFFu) == 0x8000u && e != 0.0f;
+    const uint32_t away = ((__builtin_bit_cast(uint32_t, e) ^ u) >> 31) ^ 1u;   // e and p have the same sign
+    const uint32_t tie_bit = tie ? away : ((u >> 16) & 1u);
+    return (u + 0x7FFFu + tie_bit) >> 16;
+  }
+  static __device__ __forceinline__ elem scale(float a, elem g) { return (elem)scale1(a, widen(g)); }
+  static __device__ __forceinline__ u32x4 scale(float a, u32x4 r) {
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t w = r[e];
+      o[e] = scale1(a, bf16_lo(w)) | (scale1(a, bf16_hi(w)) << 16);
+    }
+    return o;
+  }
 };
 struct RowF32 {
   typedef float elem;
@@ -155,6 +180,16 @@ struct RowF32 {
   }
   static __device__ __forceinline__ float widen(elem v) { return v; }
   static __device__ __forceinline__ elem narrow(float f) { return f; }
+  static __device__ __forceinline__ elem scale(float a, elem g) { return a * g; }   // one IEEE multiply
+  static __device__ __forceinline__ u32x4 scale(float a, u32x4 r) {
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const uint32_t w = r[e];
+      o[e] = __builtin_bit_cast(uint32_t, a * __builtin_bit_cast(float, w));
+    }
+    return o;
+  }
 };
 
 // MIX = false: hm_combine.  MIX = true: hm_combine_mix, the sum times the reciprocal of the sum of
@@ -278,16 +313,17 @@ __global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p
 // ---------------------------------------------------------------------------------------------
 // transpose: gy[slot_row[t,k], :] = row_weight[row] * gout[t, :] for kept slots (fp32)
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kCopyThreads) void transpose_rows_kernel(RowParams p, const f32x4 *__restrict__ gout,
+template <typename ROW>
+__global__ __launch_bounds__(kCopyThreads) void transpose_rows_kernel(RowParams p, const u32x4 *__restrict__ gout,
                                                                       const float *__restrict__ row_weight,
-                                                                      int64_t weight_rows, f32x4 *__restrict__ gy,
+                                                                      int64_t weight_rows, u32x4 *__restrict__ gy,
                                                                       int64_t gy_rows) {
   int t, seg;
   if (!unit_of_wave<kCopyThreads>(p, t, seg)) return;
   const int lane = lane_id();
   const int v = seg * kWave + lane;
   const bool in_row = v < p.nvec;
-  f32x4 r = {0.0f, 0.0f, 0.0f, 0.0f};
+  u32x4 r = {0u, 0u, 0u, 0u};
   if (in_row) r = gout[(int64_t)t * p.nvec + v];
   int my_row = -1;
   float my_w = 0.0f;
@@ -309,30 +345,25 @@ __global__ __launch_bounds__(kCopyThreads) void transpose_rows_kernel(RowParams 
     todo &= todo - 1;
     const int row = read_lane(my_row, k);
     const float a = read_lane(my_w, k);
-    if (in_row) {
-      f32x4 o;
-      o.x = a * r.x;
-      o.y = a * r.y;
-      o.z = a * r.z;
-      o.w = a * r.w;
-      store_stream(gy + (int64_t)row * p.nvec + v, o);
-    }
+    if (in_row) store_stream(gy + (int64_t)row * p.nvec + v, ROW::scale(a, r));
   }
 }
 
-__global__ __launch_bounds__(kElemThreads) void transpose_elems_kernel(RowParams p, int32_t H, const float *__restrict__ gout,
+template <typename ROW>
+__global__ __launch_bounds__(kElemThreads) void transpose_elems_kernel(RowParams p, int32_t H,
+                                                                      const typename ROW::elem *__restrict__ gout,
                                                                       const float *__restrict__ row_weight,
-                                                                      int64_t weight_rows, float *__restrict__ gy,
+                                                                      int64_t weight_rows, typename ROW::elem *__restrict__ gy,
                                                                       int64_t gy_rows) {
   const int64_t i = (int64_t)blockIdx.x * kElemThreads + threadIdx.x;
   if (i >= (int64_t)p.T * H) return;
   const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
-  const float g = gout[i];
+  const typename ROW::elem g = gout[i];
   for (int k = 0; k < p.K; ++k) {
     const int64_t s = (int64_t)t * p.K + k;
     const int row = p.slot_row[s];
     if (!p.slot_keep[s] || row < 0) continue;
-    if (row < gy_rows && row < weight_rows) gy[(int64_t)row * H + j] = row_weight[row] * g;
+    if (row < gy_rows && row < weight_rows) gy[(int64_t)row * H + j] = ROW::scale(row_weight[row], g);
     else if (j == 0) flag(p.status, HM_ERR_CAPACITY);
   }
 }
@@ -452,9 +483,11 @@ extern "C" hm_status hm_combine_mix(const void *y_bf16, int64_t y_rows, const fl
   return launch_combine<true, hm::RowBf16>(y_bf16, y_rows, row_weights, T, K, H, plan, out_bf16, hip_stream);
 }
 
-extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
-                                          float *gy, int64_t gy_rows, void *hip_stream) {
+template <typename ROW>
+static hm_status launch_transpose(const void *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan, void *gy,
+                                  int64_t gy_rows, void *hip_stream) {
   using namespace hm;
+  typedef typename ROW::elem elem;
   hm_status st = check_rows_args(T, K, H, plan, true);
   if (st != HM_OK) return st;
   if (!plan->row_weight) return HM_ERR_NULL;
@@ -469,14 +502,24 @@ extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t 
   p.slot_keep = plan->slot_keep;
   p.status = plan->status;
   dim3 grid;
-  if (H % 4 == 0 && aligned16(gout) && aligned16(gy)) {
-    if (!grid_for_units(p, H / 4, 1, kCopyThreads, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(transpose_rows_kernel, grid, dim3(kCopyThreads), 0, stream, p, (const f32x4 *)gout, plan->row_weight,
-                       plan->row_capacity, (f32x4 *)gy, gy_rows);
+  if (H % ROW::kPerVec == 0 && aligned16(gout) && aligned16(gy)) {
+    if (!grid_for_units(p, H / ROW::kPerVec, 1, kCopyThreads, grid)) return HM_ERR_SHAPE;
+    hipLaunchKernelGGL((transpose_rows_kernel<ROW>), grid, dim3(kCopyThreads), 0, stream, p, (const u32x4 *)gout,
+                       plan->row_weight, plan->row_capacity, (u32x4 *)gy, gy_rows);
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(transpose_elems_kernel, grid, dim3(kElemThreads), 0, stream, p, H, gout, plan->row_weight,
-                       plan->row_capacity, gy, gy_rows);
+    hipLaunchKernelGGL((transpose_elems_kernel<ROW>), grid, dim3(kElemThreads), 0, stream, p, H, (const elem *)gout,
+                       plan->row_weight, plan->row_capacity, (elem *)gy, gy_rows);
   }
   return hm_launch_status();
+}
+
+extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
+                                          float *gy, int64_t gy_rows, void *hip_stream) {
+  return launch_transpose<hm::RowF32>(gout, T, K, H, plan, gy, gy_rows, hip_stream);
+}
+
+extern "C" hm_status hm_combine_transpose_bf16(const void *gout_bf16, int32_t T, int32_t K, int32_t H,
+                                               const hm_plan_out *plan, void *gy_bf16, int64_t gy_rows, void *hip_stream) {
+  return launch_transpose<hm::RowBf16>(gout_bf16, T, K, H, plan, gy_bf16, gy_rows, hip_stream);
 }

@@ -98,6 +98,8 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_combine_f32(fake, 8, fake, 0, 2, 64, ref, fake, None) == B.HM_OK          # T = 0: nothing to do
     assert L.hm_combine_transpose(None, 4, 2, 64, ref, fake, 8, None) == B.HM_ERR_NULL
     assert L.hm_combine_transpose(fake, 4, 2, -5, ref, fake, 8, None) == B.HM_ERR_SHAPE
+    assert L.hm_combine_transpose_bf16(None, 4, 2, 64, ref, fake, 8, None) == B.HM_ERR_NULL
+    assert L.hm_combine_transpose_bf16(fake, 4, 2, 64, ref, fake, -1, None) == B.HM_ERR_SHAPE
     assert L.hm_expert_load(fake, None, 4, 2, 8, topo, fake, fake, fake, None, None) == B.HM_ERR_NULL
     assert L.hm_expert_load(fake, fake, 4, 2, 8, B.hm_topology(8, 9), fake, fake, fake, None, None) == B.HM_ERR_TOPOLOGY
     assert L.hm_expert_load(fake, fake, 4, 99, 8, topo, fake, fake, fake, None, None) == B.HM_ERR_SHAPE

@@ -559,6 +559,44 @@ def test_combine_on_binary32_rows(hw, oracle, name, T, H):
     assert st == B.HM_ERR_CAPACITY and not torch.isnan(out_d).any()
 
 
+@pytest.mark.parametrize("name,T,H", [("tiny", 1024, 256), ("qwen3", 1500, 2048), ("stress", 600, 7168), ("skew", 777, 90),
+                                      ("skew", 300, 77)])
+def test_transpose_on_bf16_gradients(hw, oracle, name, T, H):
+    """hm_combine_transpose_bf16: the exact product rounded once, so bit for bit against the oracle
+    (vector kernel, ragged H, and the element-wise kernel), including products that land on bf16
+    ties after the binary32 rounding."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS[name]
+    r = W.make_routing(wl, T=T)
+    gout = W.f32_to_bf16_bits(W.make_output_grads(wl, T=T, H=H))
+    for level in (NONE, GPU, NODE):
+        ctx = "transpose bf16 %s T=%d H=%d level=%s" % (name, T, H, LEVEL[level])
+        print("case:", ctx, flush=True)
+        ora = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        gy_d = torch.full((max(ora.total_rows, 1), H), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.hm_combine_transpose_bf16(hw.to_dev_bf16(gout), g.plan, gy_d[:ora.total_rows])
+        ref = oracle.combine_transpose_bf16(gout, ora.row_token, ora.row_weight)
+        assert np.array_equal(hw.bf16_to_host(gy_d[:ora.total_rows]), ref), ctx
+        st, _ = B.hm_plan_status(g.plan)
+        assert st == 0
+    # weights chosen so that the fp32 product sits exactly on a bf16 tie while the true product does not
+    n_w = 1100
+    w = (1.0 + np.arange(97000, 97000 + n_w) * 2.0 ** -23).astype(np.float32).reshape(n_w, 1)
+    ids = np.zeros((n_w, 1), np.int32)
+    e2r = np.zeros(1, np.int32)
+    ora = oracle.plan(ids, w, e2r, 1, 1, GPU)
+    g = hw.GpuPlan(ids, w, e2r, 1, 1, GPU)
+    gg = W.f32_to_bf16_bits(np.full((n_w, 8), 1.0 + 2.0 ** -7, np.float32))
+    gy_d = torch.zeros((n_w, 8), dtype=torch.bfloat16, device="cuda")
+    B.hm_combine_transpose_bf16(hw.to_dev_bf16(gg), g.plan, gy_d)
+    ref = oracle.combine_transpose_bf16(gg, ora.row_token, ora.row_weight)
+    twice = W.f32_to_bf16_bits((w * np.float32(1.0 + 2.0 ** -7)).astype(np.float32))      # rounded twice
+    assert (ref[:, :1] != twice).any()                     # the family does contain such traps
+    assert np.array_equal(hw.bf16_to_host(gy_d), ref)
+
+
 def test_combine_with_cancelling_terms(hw, oracle):
     """Independent random-sign Y rows: the K terms of an output element can cancel, and an fp32
     accumulator is then only accurate relative to sum_k |w y|, not to the (tiny) result.  Bar: within
