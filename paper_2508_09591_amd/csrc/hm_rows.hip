@@ -14,7 +14,9 @@
 // read-heavy, did best with 4 KiB segments (4 vectors per lane) and the loads of up to four rows
 // issued before the first use; from about 32 Ki tokens of that shape on, the ramp-up and the
 // tail no longer matter and 7 KiB segments are faster (2.5 % at 32 Ki tokens, 5.5 % at 64 Ki;
-// 1.8 % slower at 8 Ki), so the launcher picks the width from the number of segments.  Every row-sized stream is read and written with non-temporal
+// 1.8 % slower at 8 Ki), so the launcher picks the width from the number of segments -- and from
+// the rows per token the caller's buffer implies: with about one row per token (the local-expert
+// stage of a receiver) four rows in flight are never used and the wide kernel only has fewer waves.  Every row-sized stream is read and written with non-temporal
 // accesses: rows are touched once per kernel, and output lines left dirty in the caches were
 // measured to slow the next kernel down by about 10 %.
 #include "hm_device.h"
@@ -451,7 +453,8 @@ static hm_status launch_combine(const void *y, int64_t y_rows, const float *topk
   if (H % ROW::kPerVec == 0 && aligned16(y) && aligned16(out)) {
     const int nvec = H / ROW::kPerVec;
     const int64_t wide_units = (int64_t)T * ((nvec + kWave * kCombineVecsWide - 1) / (kWave * kCombineVecsWide));
-    if (wide_units >= kCombineWideMinUnits) {
+    // (the wide kernel keeps four rows in flight: with about one row per token it only has fewer waves)
+    if (wide_units >= kCombineWideMinUnits && y_rows >= 2 * (int64_t)T) {
       if (!grid_for_units(p, nvec, kCombineVecsWide, kCombineThreads, grid)) return HM_ERR_SHAPE;
       hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecsWide, ROW>), grid, dim3(kCombineThreads), 0, stream, p,
                          (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);

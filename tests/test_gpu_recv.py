@@ -110,7 +110,8 @@ def test_plan_mapped_parity(hw, oracle, rows, K, E, nd):
 
 
 @pytest.mark.parametrize("rows,K,H", [(500, 8, 512), (300, 4, 1000), (129, 6, 100), (64, 8, 7168),
-                                       (66000, 3, 520)])       # the last one is large enough for the wide segments
+                                       (66000, 6, 520),        # enough segments and rows per token for the wide kernel
+                                       (66000, 2, 520)])       # as many segments, about one row per token: the narrow one
 def test_combine_mix_parity(hw, oracle, rows, K, H):
     import torch
     from paper_2508_09591_amd import binding as B
