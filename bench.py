@@ -142,18 +142,20 @@ def main() -> int:
     torch.cuda.synchronize()
 
     def step(i, ev=None):
+        # ev: a start and a stop event per call, each pair recorded around its own call only, so that
+        # the marker between two calls is charged to neither
         s = i % nsets
         ys = (s + y_shift) % nsets
         if ev: ev[0].record(stream)
         B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan, stream=stream)
-        if ev: ev[1].record(stream)
+        if ev: ev[1].record(stream); ev[2].record(stream)
         if not fused:        # otherwise hm_plan has already produced the three load arrays
             B.hm_expert_load(ids_d, e2r_d, wl.nodes, wl.ranks_per_node, le, lr, ln, stream=stream)
-        if ev: ev[2].record(stream)
+        if ev: ev[3].record(stream); ev[4].record(stream)
         B.hm_dispatch_pack(xs[s], plan, packs[s], stream=stream)
-        if ev: ev[3].record(stream)
+        if ev: ev[5].record(stream); ev[6].record(stream)
         B.hm_combine(packs[ys], w_d, plan, outs[s], stream=stream)     # identity experts: Y = packed rows
-        if ev: ev[4].record(stream)
+        if ev: ev[7].record(stream)
 
     # ---- warm-up, then the timed region: exactly `steps` steps between two synchronisations ----
     run = step
@@ -181,12 +183,12 @@ def main() -> int:
     tokens_per_s = T / (elapsed / args.steps)
 
     # ---- per-kernel durations: the same steps again with HIP events on the launch stream ------
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
     for i in range(args.steps):
         step(i, events[i])
     torch.cuda.synchronize()
     names = ["hm_plan", "hm_expert_load", "hm_dispatch_pack", "hm_combine"]
-    per_call = {n: sorted(e[j].elapsed_time(e[j + 1]) for e in events) for j, n in enumerate(names)}
+    per_call = {n: sorted(e[2 * j].elapsed_time(e[2 * j + 1]) for e in events) for j, n in enumerate(names)}
     avg_ms = {n: sum(v) / len(v) for n, v in per_call.items()}
     min_ms = {n: v[0] for n, v in per_call.items()}
     med_ms = {n: v[len(v) // 2] for n, v in per_call.items()}

@@ -14,9 +14,9 @@
 // read-heavy, did best with 4 KiB segments (4 vectors per lane) and the loads of up to four rows
 // issued before the first use; from about 32 Ki tokens of that shape on, the ramp-up and the
 // tail no longer matter and 7 KiB segments are faster (2.5 % at 32 Ki tokens, 5.5 % at 64 Ki;
-// 1.8 % slower at 8 Ki), so the launcher picks the width from the number of segments -- and from
-// the rows per token the caller's buffer implies: with about one row per token (the local-expert
-// stage of a receiver) four rows in flight are never used and the wide kernel only has fewer waves.  Every row-sized stream is read and written with non-temporal
+// 1.8 % slower at 8 Ki), so the launcher picks the width from the number of segments -- and the
+// rows in flight from the rows per token the caller's buffer implies: with about one row per token
+// (the local-expert stage of a receiver) four rows in flight are never used, and two do better.  Every row-sized stream is read and written with non-temporal
 // accesses: rows are touched once per kernel, and output lines left dirty in the caches were
 // measured to slow the next kernel down by about 10 %.
 #include "hm_device.h"
@@ -29,7 +29,8 @@ constexpr int kCombineThreads = 256;
 constexpr int kCombineVecs = 4;     // combine: 16-byte vectors per lane (4 KiB segments) ...
 constexpr int kCombineVecsWide = 7; // ... or 7 KiB segments once the launch has this many of them:
 constexpr int64_t kCombineWideMinUnits = 65536;
-constexpr int kCombineRows = 4;     // combine: rows whose loads are in flight together
+constexpr int kCombineRows = 4;     // combine: rows whose loads are in flight together ...
+constexpr int kCombineRowsFew = 2;  // ... or two, when the tokens have about one row each
 
 struct RowParams {
   int32_t T, K;
@@ -197,7 +198,7 @@ struct RowF32 {
 // MIX = false: hm_combine.  MIX = true: hm_combine_mix, the sum times the reciprocal of the sum of
 // the merged weights (added in ascending k of each row's first slot); zero for a row without a
 // valid slot.  (A true division per element made the kernel ALU-bound: 8 divisions per 16 bytes.)
-template <bool MIX, int U, typename ROW>
+template <bool MIX, int U, int R, typename ROW>
 __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
                                                                        int64_t y_rows, const float *__restrict__ topk_weights,
                                                                        u32x4 *__restrict__ out) {
@@ -227,7 +228,6 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
     inv_wsum = wsum != 0.0f ? 1.0f / wsum : 0.0f;
   }
 
-  constexpr int R = kCombineRows;
   const int v0 = seg * (kWave * U) + lane;   // this lane's vectors: v0, v0+64, ...
   constexpr int E = ROW::kPerVec;
   float acc[U][E];
@@ -453,15 +453,20 @@ static hm_status launch_combine(const void *y, int64_t y_rows, const float *topk
   if (H % ROW::kPerVec == 0 && aligned16(y) && aligned16(out)) {
     const int nvec = H / ROW::kPerVec;
     const int64_t wide_units = (int64_t)T * ((nvec + kWave * kCombineVecsWide - 1) / (kWave * kCombineVecsWide));
-    // (the wide kernel keeps four rows in flight: with about one row per token it only has fewer waves)
-    if (wide_units >= kCombineWideMinUnits && y_rows >= 2 * (int64_t)T) {
+    if (y_rows < 2 * (int64_t)T) {
+      // about one row per token (the local-expert stage of a receiver): four rows in flight are
+      // never used, two leave room for more waves (0.31 -> 0.28 ms on that stage)
+      if (!grid_for_units(p, nvec, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
+      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, kCombineRowsFew, ROW>), grid, dim3(kCombineThreads), 0,
+                         stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
+    } else if (wide_units >= kCombineWideMinUnits) {
       if (!grid_for_units(p, nvec, kCombineVecsWide, kCombineThreads, grid)) return HM_ERR_SHAPE;
-      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecsWide, ROW>), grid, dim3(kCombineThreads), 0, stream, p,
-                         (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
+      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecsWide, kCombineRows, ROW>), grid, dim3(kCombineThreads), 0,
+                         stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
     } else {
       if (!grid_for_units(p, nvec, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
-      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, ROW>), grid, dim3(kCombineThreads), 0, stream, p,
-                         (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
+      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, kCombineRows, ROW>), grid, dim3(kCombineThreads), 0,
+                         stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
     }
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
