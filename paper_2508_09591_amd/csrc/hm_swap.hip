@@ -16,7 +16,7 @@ constexpr int kSwapThreads = 256;
 constexpr int kSelectThreads = 64;     // Q per pair: fp64 pow-heavy, so many small workgroups to reach every CU
 constexpr int kFactorThreads = 1024;   // the co-occurrence pass: 16 waves share one set of LDS tables
 constexpr int kSwapLds = 30720;   // most ints of LDS for L0 and every cut's L + CG (120 KiB); larger sets stay in global memory
-constexpr int kSwapCopies = 8;    // private copies of C: popular expert pairs would otherwise serialise on one address
+constexpr int kSwapCopiesMax = 32;   // private copies of C: popular expert pairs would otherwise serialise on one address
 constexpr int kMaxCuts = 4;       // group cuts handled by one pass over the tokens
 
 // One pass serves up to kMaxCuts cuts of the ranks into groups: everything that does not depend on
@@ -28,13 +28,14 @@ struct SwapParams {
   int32_t sub;      // lanes per token in the co-occurrence pass: the power of two >= K
   int32_t ncuts;
   int32_t use_lds;  // L0 / L / CG of all cuts accumulate in LDS
+  int32_t copies;   // private copies of each C
   int32_t ng[kMaxCuts], per[kMaxCuts];
   int32_t lds_off[kMaxCuts];   // ints: where cut c's [L (E) | CG (E * ng)] starts in LDS; L0 is at 0
   int32_t *L0;                 // [E]                                  (workspace, shared by the cuts)
   int32_t *base[kMaxCuts];     // [64]                                 (workspace, per cut)
   int32_t *L[kMaxCuts];        // [E]
   int32_t *CG[kMaxCuts];       // [E][ng]
-  int32_t *C[kMaxCuts];        // [kSwapCopies][E][E]
+  int32_t *C[kMaxCuts];        // [copies][E][E]
   int32_t *Z[kMaxCuts];
   int32_t *ws;                 // start of the workspace and its size in ints (cleared first)
   int64_t ws_ints;
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(kFactorThreads) void swap_factors_kernel(SwapParams
   const int64_t nwaves = (int64_t)gridDim.x * (kFactorThreads / kWave);
   const int64_t per_round = nwaves * tokens_per_wave;
   const int64_t rounds = ((int64_t)p.T + per_round - 1) / per_round;
-  const int64_t copy_off = (int64_t)(blockIdx.x % kSwapCopies) * p.E * p.E;
+  const int64_t copy_off = (int64_t)(blockIdx.x & (p.copies - 1)) * p.E * p.E;
   int my_base[kMaxCuts] = {0, 0, 0, 0};
   for (int64_t it = 0; it < rounds; ++it) {
     const int64_t t = (it * nwaves + wave) * tokens_per_wave + lane / p.sub;
@@ -112,12 +113,8 @@ __global__ __launch_bounds__(kFactorThreads) void swap_factors_kernel(SwapParams
       }
     }
     bool alone[kMaxCuts];
-    bool any_alone = false;
 #pragma unroll
-    for (int c = 0; c < kMaxCuts; ++c) {
-      alone[c] = c < p.ncuts && first && in_group[c] == 1;
-      any_alone = any_alone || alone[c];
-    }
+    for (int c = 0; c < kMaxCuts; ++c) alone[c] = c < p.ncuts && first && in_group[c] == 1;
     if (first) {
       if (p.use_lds) atomicAdd(&lds[a], 1);
       else atomicAdd(&p.L0[a], 1);
@@ -131,13 +128,19 @@ __global__ __launch_bounds__(kFactorThreads) void swap_factors_kernel(SwapParams
         }
       }
     }
+    // C[a1][b] += 1 for every expert a1 of the token that is alone in its group and every other
+    // selected expert b.  The lane of b issues the update, so the lanes of a token hit one row of
+    // C per step (a few cache lines) rather than one column (a line per lane).
+    int alone_mask = 0;
+#pragma unroll
+    for (int c = 0; c < kMaxCuts; ++c) alone_mask |= alone[c] ? 1 << c : 0;
     for (int k1 = 0; k1 < p.K; ++k1) {
       const int a1 = __shfl(a, sub0 + k1, kWave);
-      const int f1 = __shfl((int)first, sub0 + k1, kWave);
-      if (any_alone && f1 && a1 != a) {
+      const int m1 = __shfl(alone_mask, sub0 + k1, kWave);
+      if (first && m1 && a1 != a) {
 #pragma unroll
         for (int c = 0; c < kMaxCuts; ++c)
-          if (alone[c]) atomicAdd(&p.C[c][copy_off + (int64_t)a * p.E + a1], 1);
+          if (m1 & (1 << c)) atomicAdd(&p.C[c][copy_off + (int64_t)a1 * p.E + a], 1);
       }
     }
     const bool leader = k == 0 && t < p.T;   // one lane per token counts the token's groups
@@ -190,7 +193,8 @@ __global__ __launch_bounds__(kSwapThreads) void swap_build_kernel(SwapParams p) 
     if (gr != gc && (j == gc || j == gr)) {
       const int a = j == gc ? r : c, b = j == gc ? c : r;   // group j gains tokens of a, loses tokens of b
       int cba = 0;
-      for (int k = 0; k < kSwapCopies; ++k) cba += p.C[cut][((int64_t)k * p.E + b) * p.E + a];
+#pragma unroll 8
+      for (int k = 0; k < p.copies; ++k) cba += p.C[cut][((int64_t)k * p.E + b) * p.E + a];
       val += (p.L0[a] - p.CG[cut][(int64_t)a * ng + j]) - (p.L[cut][b] - cba);
     }
   }
@@ -339,8 +343,16 @@ static bool swap_factors_lds_ready() {
   return ok;
 }
 
-// Workspace, in ints: L0 [E], then per cut base [64] | L [E] | CG [E * ng] | C [kSwapCopies * E * E].
-static inline int64_t swap_cut_ints(int64_t E, int64_t ng) { return 64 + E + E * ng + kSwapCopies * E * E; }
+// Private copies of C: as many as fit 2 MiB per cut, at most kSwapCopiesMax (32 for E <= 128, 8 for
+// E = 256): more copies spread the atomics of popular pairs, but each is cleared and summed again.
+static inline int64_t swap_copies(int64_t E) {
+  int64_t n = kSwapCopiesMax;   // a power of two, so that a workgroup finds its copy with a mask
+  while (n > 1 && n * E * E > (int64_t)(1 << 19)) n /= 2;
+  return n;
+}
+
+// Workspace, in ints: L0 [E], then per cut base [64] | L [E] | CG [E * ng] | C [copies * E * E].
+static inline int64_t swap_cut_ints(int64_t E, int64_t ng) { return 64 + E + E * ng + swap_copies(E) * E * E; }
 
 static inline bool swap_cuts_ok(int32_t G, int32_t ncuts, const int32_t *ng) {
   if (G < 1 || G > 64 || ncuts < 1 || ncuts > kMaxCuts || !ng) return false;
@@ -360,6 +372,7 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
   p.E = E;
   p.G = G;
   p.ncuts = ncuts;
+  p.copies = (int32_t)swap_copies(E);
   p.sub = 1;
   while (p.sub < K) p.sub *= 2;
   p.ws = (int32_t *)workspace;

@@ -158,7 +158,7 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_swap_select(2, i32x(1, 2), 4, 8, 1.0, 1.0, zn, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
     ng2 = i32x(2, 4)
     zz = (ctypes.c_void_p * 2)(fake, fake)
-    assert L.hm_swap_multi_workspace_bytes(16, 4, 2, ng2) == (16 + 2 * (64 + 16 + 8 * 16 * 16) + 16 * 2 + 16 * 4) * 4
+    assert L.hm_swap_multi_workspace_bytes(16, 4, 2, ng2) == (16 + 2 * (64 + 16 + 32 * 16 * 16) + 16 * 2 + 16 * 4) * 4
     assert L.hm_swap_multi_workspace_bytes(16, 4, 5, ng2) == 0 and L.hm_swap_multi_workspace_bytes(16, 6, 2, ng2) == 0
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 4, 2, ng2, zz, None, fake, 8, None) == B.HM_ERR_WORKSPACE
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 6, 2, ng2, zz, None, fake, big, None) == B.HM_ERR_TOPOLOGY
