@@ -306,6 +306,33 @@ def main() -> int:
         log("reference: plain 1 GiB device copy %.4f ms -> %.1f GB/s = %.1f%% of peak" % (cms, cgbs, 100 * cgbs / HBM_PEAK_GBS))
         del src, dst
 
+    # ---- context: flat streams with the same read : write mix and no indirection ------------------
+    stream_ref = None
+    if copy_ref is not None:
+        stream_ref = {}
+        cr = max(1, min(16, int(round(c))))
+        mixes = [(1, 1), (1, cr), (cr, 1)] if cr > 1 else [(1, 1)]    # a plain copy, dispatch's mix, combine's mix
+        total_vec = int(alg_bytes["hm_dispatch_pack"]) // 16            # the bytes one row kernel moves
+        for nr, nw in mixes:
+            n = total_vec // (nr + nw)
+            srcs = [torch.empty((nr, n, 4), dtype=torch.int32, device="cuda").fill_(7) for _ in range(nsets)]
+            dsts = [torch.empty((nw, n, 4), dtype=torch.int32, device="cuda") for _ in range(nsets)]
+            pev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
+            for i in range(8):
+                B.hm_stream_probe(srcs[i % nsets], nr, dsts[i % nsets], nw, stream=stream)
+            for i, (a, b) in enumerate(pev):
+                a.record(stream)
+                B.hm_stream_probe(srcs[i % nsets], nr, dsts[i % nsets], nw, stream=stream)
+                b.record(stream)
+            torch.cuda.synchronize()
+            pms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
+            gbs = (nr + nw) * n * 16 / (pms * 1e-3) / 1e9
+            stream_ref["%dr+%dw" % (nr, nw)] = {"median_ms": round(pms, 5), "achieved_GBps": round(gbs, 1),
+                                                 "frac": round(gbs / HBM_PEAK_GBS, 4)}
+            del srcs, dsts
+        log("reference: flat streams of %d MB, no indirection (hm_stream_probe): " % (total_vec * 16 // 1000000)
+            + ", ".join("%s %.1f%%" % (k, 100 * v["frac"]) for k, v in stream_ref.items()))
+
     # ---- the oracle on this machine's host cores (reported baseline, not the target) ---------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -357,6 +384,7 @@ def main() -> int:
                  "tokens_per_s": round(T / (pair_ms * 1e-3), 1)},
         "plan_ms": round(avg_ms["hm_plan"], 5),
         "device_copy_reference": copy_ref,
+        "flat_stream_reference": stream_ref,
         "expert_load_ms": None if fused else round(avg_ms["hm_expert_load"], 5),
     }
     print(json.dumps(result), flush=True)

@@ -355,6 +355,18 @@ hm_status hm_swap_select(int32_t d, const int32_t *U /* host */, int32_t G, int3
  */
 hm_status hm_swap_apply(int32_t *expert_to_rank, int32_t E, const int32_t *best_pair, void *hip_stream);
 
+/*
+ * hm_stream_probe -- a measurement aid, not part of the paper's method: a flat stream with
+ * read_streams contiguous inputs and write_streams contiguous outputs of vectors_per_stream
+ * 16-byte vectors each (src holds the inputs back to back, dst the outputs; both device, 16-byte
+ * aligned; 1..16 streams each way), no indirection: every output vector is the XOR of the input
+ * vectors at its index.  Launch shape, vector width and cache hints are those of the row kernels,
+ * so its rate is what the memory system gives for the mix of hm_dispatch_pack (1 read, c writes)
+ * or hm_combine (c reads, 1 write).
+ */
+hm_status hm_stream_probe(const void *src, int32_t read_streams, void *dst, int32_t write_streams,
+                          int64_t vectors_per_stream, void *hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char *hm_status_string(hm_status s);
 

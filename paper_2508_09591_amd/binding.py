@@ -27,7 +27,7 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
            "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply",
-           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16")
+           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16", "hm_stream_probe")
 
 
 class hm_topology(ctypes.Structure):
@@ -77,6 +77,8 @@ def lib():
         L.hm_swap_multi_workspace_bytes.argtypes = [i32, i32, i32, vp]
         L.hm_swap_counts_multi.restype = ctypes.c_int
         L.hm_swap_counts_multi.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.hm_stream_probe.restype = ctypes.c_int
+        L.hm_stream_probe.argtypes = [vp, i32, vp, i32, i64, vp]
         L.hm_swap_apply.restype = ctypes.c_int
         L.hm_swap_apply.argtypes = [vp, i32, vp, vp]
         L.hm_combine_f32.restype = ctypes.c_int
@@ -402,6 +404,19 @@ def hm_swap_select(U, G: int, M: float, v: float, z_inter, z_intra: torch.Tensor
                               workspace.data_ptr(), workspace.numel() * 8, _stream(stream))
     _check("hm_swap_select", rc)
     return Q, best_pair, best_time
+
+
+def hm_stream_probe(src: torch.Tensor, read_streams: int, dst: torch.Tensor, write_streams: int, stream=None):
+    """src: [read_streams, n] and dst: [write_streams, n] of 16-byte vectors (any dtype, contiguous)."""
+    nbytes = src.numel() * src.element_size()
+    n = nbytes // (16 * read_streams)
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise TypeError("src and dst must be contiguous GPU tensors")
+    if nbytes != n * 16 * read_streams or dst.numel() * dst.element_size() != n * 16 * write_streams:
+        raise ValueError("src / dst sizes do not match the stream counts")
+    rc = lib().hm_stream_probe(src.data_ptr(), read_streams, dst.data_ptr(), write_streams, n, _stream(stream))
+    _check("hm_stream_probe", rc)
+    return dst
 
 
 def hm_swap_apply(expert_to_rank: torch.Tensor, best_pair: torch.Tensor, stream=None) -> torch.Tensor:

@@ -166,6 +166,11 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 4, 2, None, zz, None, fake, big, None) == B.HM_ERR_NULL
     zn2 = (ctypes.c_void_p * 2)(fake, None)
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 4, 2, ng2, zn2, None, fake, big, None) == B.HM_ERR_NULL
+    assert L.hm_stream_probe(None, 1, fake, 1, 64, None) == B.HM_ERR_NULL
+    assert L.hm_stream_probe(fake, 0, fake, 1, 64, None) == B.HM_ERR_SHAPE
+    assert L.hm_stream_probe(fake, 1, fake, 17, 64, None) == B.HM_ERR_SHAPE
+    assert L.hm_stream_probe(fake, 1, ctypes.c_void_p(0x1008), 1, 64, None) == B.HM_ERR_SHAPE      # misaligned
+    assert L.hm_stream_probe(fake, 1, fake, 1, 0, None) == B.HM_OK
     assert L.hm_swap_apply(None, 8, fake, None) == B.HM_ERR_NULL
     assert L.hm_swap_apply(fake, 8, None, None) == B.HM_ERR_NULL
     assert L.hm_swap_apply(fake, 0, fake, None) == B.HM_ERR_SHAPE

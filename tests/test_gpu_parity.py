@@ -630,6 +630,21 @@ def test_combine_with_cancelling_terms(hw, oracle):
         assert (dist <= 1).mean() > 0.999
 
 
+def test_stream_probe_moves_what_it_says(hw):
+    """The measurement aid: every output stream is the XOR of the input streams, ragged tail included."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(3)
+    for nr, nw, n in ((1, 1, 64), (1, 3, 1000), (3, 1, 4097), (7, 2, 130), (16, 16, 65)):
+        src = rng.integers(-2 ** 31, 2 ** 31 - 1, (nr, n, 4), dtype=np.int64).astype(np.int32)
+        dst_d = torch.full((nw, n, 4), 77, dtype=torch.int32, device="cuda")
+        B.hm_stream_probe(hw.dev(src), nr, dst_d, nw)
+        want = np.bitwise_xor.reduce(src, axis=0)
+        got = dst_d.cpu().numpy()
+        for j in range(nw):
+            assert np.array_equal(got[j], want), (nr, nw, n, j)
+
+
 def test_step_under_hip_graph_capture(hw, oracle):
     """The entry points only enqueue kernels (no allocation, no memset, no synchronisation), so a
     whole step can be captured in a HIP graph and replayed: every replay, with fresh routing and
