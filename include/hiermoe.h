@@ -25,7 +25,8 @@
  *   - Row and token indices are int32; byte offsets inside the kernels are 64-bit.
  *   - Limits: nodes*ranks_per_node <= 64, nodes <= 32 (bit masks), 1 <= K <= 64,
  *     T*K <= 2^31-1.
- *   - Re-entrant per (plan buffers, workspace, stream); no global state.
+ *   - Re-entrant per (plan buffers, workspace, stream); no global state (hm_swap_counts sets one
+ *     kernel attribute, its dynamic LDS limit, the first time it runs).
  */
 #ifndef HIERMOE_H
 #define HIERMOE_H
@@ -81,7 +82,7 @@ typedef struct {
  *   status     [1]            0, or HM_ERR_BAD_ID / HM_ERR_CAPACITY as stored by the kernels (the more
  *                             negative code wins when both occur, whatever the order of the waves)
  *   load_expert [E], load_rank [G], load_node [nodes]   optional, all three or none: when given,
- *                             hm_plan also produces the counts of hm_expert_load, in the same two
+ *                             hm_plan also produces the counts of hm_expert_load, in the same
  *                             launches (the planner of Section IV needs them every iteration).
  *                             hm_plan_mapped ignores them.
  */
