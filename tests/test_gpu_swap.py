@@ -94,6 +94,26 @@ def test_swap_counts_multi_equals_separate_calls(hw, oracle, name, T, cuts):
         assert st_ref == B.HM_ERR_BAD_ID and np.array_equal(z.cpu().numpy(), ref), (name, u, "bad")
 
 
+@pytest.mark.parametrize("G,E,T,K,cuts", [(12, 48, 900, 5, [4, 6, 12]),      # cuts that do not refine one another
+                                          (12, 60, 700, 4, [6, 2, 12, 3]),
+                                          (16, 64, 800, 6, [8, 8]),           # the same cut twice
+                                          (24, 96, 1000, 8, [12, 2, 24, 4])]) # nested, given out of order
+def test_swap_counts_multi_any_set_of_cuts(hw, oracle, G, E, T, K, cuts):
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(G + E)
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)
+    ids[rng.random((T, K)) < 0.05] = -1
+    e2r = rng.integers(0, G, E).astype(np.int32)
+    Z = [torch.full((E, E, u), -9, dtype=torch.int32, device="cuda") for u in cuts]
+    st = torch.full((1,), 5, dtype=torch.int32, device="cuda")
+    B.hm_swap_counts_multi(hw.dev(ids), hw.dev(e2r), G, cuts, Z, st)
+    assert int(st.item()) == 0
+    for u, z in zip(cuts, Z):
+        ref, _ = oracle.swap_counts(ids, e2r, G, u, "naive" if E <= 60 else "incremental")
+        assert np.array_equal(z.cpu().numpy(), ref), (G, E, cuts, u)
+
+
 @pytest.mark.parametrize("name,placement", [("qwen3", "contiguous"), ("dsv3", "contiguous"), ("skew", "swapped")])
 def test_swap_counts_full_size(hw, oracle, name, placement):
     wl = W.WORKLOADS[name]
