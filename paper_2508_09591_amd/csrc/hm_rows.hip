@@ -156,13 +156,31 @@ struct RowBf16 {
     return (u + 0x7FFFu + tie_bit) >> 16;
   }
   static __device__ __forceinline__ elem scale(float a, elem g) { return (elem)scale1(a, widen(g)); }
+  // Eight at once: the common path rounds the fp32 products to nearest even and only notes whether
+  // any of them sits on a bf16 tie (1 in 65536); the exact treatment runs for those alone.
   static __device__ __forceinline__ u32x4 scale(float a, u32x4 r) {
-    u32x4 o;
+    float g[8];
+    uint32_t h[8];
+    bool any_tie = false;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const uint32_t w = r[e];
-      o[e] = scale1(a, bf16_lo(w)) | (scale1(a, bf16_hi(w)) << 16);
+      g[2 * e] = bf16_lo(w);
+      g[2 * e + 1] = bf16_hi(w);
     }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float p = a * g[i];
+      h[i] = f32_to_bf16(p);
+      any_tie = any_tie || (__builtin_bit_cast(uint32_t, p) & 0xFFFFu) == 0x8000u;
+    }
+    if (__builtin_expect(any_tie, 0)) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) h[i] = scale1(a, g[i]);
+    }
+    u32x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = h[2 * e] | (h[2 * e + 1] << 16);
     return o;
   }
 };
