@@ -44,7 +44,7 @@ typedef enum {
   HM_ERR_SHAPE = -2,     /* T < 0, K/E/H out of range, T*K overflows int32                */
   HM_ERR_TOPOLOGY = -3,  /* nodes or ranks_per_node < 1, more than 64 ranks or 32 nodes   */
   HM_ERR_LEVEL = -4,     /* dedup level is not one of hm_dedup_level                      */
-  HM_ERR_WORKSPACE = -5, /* workspace smaller than hm_plan_workspace_bytes                */
+  HM_ERR_WORKSPACE = -5, /* workspace smaller than needed (hm_plan_static: than its maximum) */
   HM_ERR_CAPACITY = -6,  /* a row index does not fit the caller's row buffers (device)    */
   HM_ERR_BAD_ID = -7,    /* expert id or rank out of range (device-detected)              */
   HM_ERR_HIP = -8        /* a HIP runtime call failed                                     */
@@ -128,6 +128,23 @@ hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int3
  */
 hm_status hm_plan_status(const hm_plan_out *plan /* host struct */, int64_t *total_rows /* host */,
                          void *hip_stream);
+
+/*
+ * hm_plan_static -- hm_plan for callers that cannot allocate or pass a workspace: code recorded
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * and results as hm_plan without the workspace pair; the scratch (the per-workgroup count matrix)
+ * is a static device array inside the library, hm_plan_static_max_bytes() = 1 MiB on every GPU
+ * the library runs on, held until the process ends.  The call allocates and frees nothing (the
+ * first call on a device looks the array's address up once).  Sizes that need more, i.e.
+ * hm_plan_workspace_bytes(...) > hm_plan_static_max_bytes() (about 4 Mi routing slots at 64
+ * destinations), are rejected with HM_ERR_WORKSPACE before anything is launched.  All calls on
+ * one GPU share the array: calls that may overlap there (different streams, several threads)
+ * race and must be serialised by the caller; nothing in it has to be cleared between calls.
+ */
+size_t hm_plan_static_max_bytes(void);
+hm_status hm_plan_static(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+                         int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
+                         hm_plan_out *out /* host struct */, void *hip_stream);
 
 /*
  * hm_dispatch_pack -- the deduplicated send buffers (Section III-A, Fig.5): for every kept slot,

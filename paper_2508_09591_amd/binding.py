@@ -27,7 +27,8 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
            "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply",
-           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16", "hm_stream_probe")
+           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16", "hm_stream_probe",
+           "hm_plan_static", "hm_plan_static_max_bytes")
 
 
 class hm_topology(ctypes.Structure):
@@ -67,6 +68,11 @@ def lib():
         L.hm_plan.restype = ctypes.c_int
         L.hm_plan.argtypes = [vp, vp, vp, i32, i32, i32, hm_topology, ctypes.c_int,
                               ctypes.POINTER(hm_plan_out), vp, ctypes.c_size_t, vp]
+        L.hm_plan_static_max_bytes.restype = ctypes.c_size_t
+        L.hm_plan_static_max_bytes.argtypes = []
+        L.hm_plan_static.restype = ctypes.c_int
+        L.hm_plan_static.argtypes = [vp, vp, vp, i32, i32, i32, hm_topology, ctypes.c_int,
+                                     ctypes.POINTER(hm_plan_out), vp]
         L.hm_plan_status.restype = ctypes.c_int
         L.hm_plan_status.argtypes = [ctypes.POINTER(hm_plan_out), ctypes.POINTER(i64), vp]
         L.hm_dispatch_pack.restype = ctypes.c_int
@@ -223,6 +229,20 @@ def hm_plan(topk_ids: torch.Tensor, topk_weights: torch.Tensor, expert_to_rank: 
                        hm_topology(nodes, ranks_per_node), level, plan.ref(),
                        plan.workspace.data_ptr(), plan.workspace.numel() * 4, _stream(stream))
     _check("hm_plan", rc)
+    plan.num_dest = int(plan.c.num_dest)
+    return plan
+
+
+def hm_plan_static(topk_ids: torch.Tensor, topk_weights: torch.Tensor, expert_to_rank: torch.Tensor,
+                   nodes: int, ranks_per_node: int, level: int, plan: Plan, stream=None) -> Plan:
+    """hm_plan on the library's static scratch: `plan` must be allocated by the caller beforehand
+    (alloc_plan); the call itself allocates nothing."""
+    T, K = topk_ids.shape
+    E = expert_to_rank.shape[0]
+    rc = lib().hm_plan_static(_dev(topk_ids, torch.int32, "topk_ids"), _dev(topk_weights, torch.float32, "topk_weights"),
+                              _dev(expert_to_rank, torch.int32, "expert_to_rank"), T, K, E,
+                              hm_topology(nodes, ranks_per_node), level, plan.ref(), _stream(stream))
+    _check("hm_plan_static", rc)
     plan.num_dest = int(plan.c.num_dest)
     return plan
 

@@ -18,6 +18,8 @@
 // and all "same destination as an earlier / later slot of my token" questions become LDS reads.
 #include "hm_device.h"
 
+#include <mutex>
+
 namespace hm {
 
 constexpr int kPlanThreads = 1024;
@@ -409,24 +411,11 @@ extern "C" size_t hm_plan_workspace_bytes(int32_t T, int32_t K, int32_t E, hm_to
   return hm::plan_workspace((int64_t)T * K, Dn);
 }
 
-extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
-                             int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
-                             hm_plan_out *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
-  if (!out || !expert_to_rank || !workspace) return HM_ERR_NULL;
-  if (!out->dest_count || !out->dest_offset || !out->row_token || !out->slot_row || !out->slot_keep ||
-      !out->row_weight || !out->status)
-    return HM_ERR_NULL;
-  hm_status st = hm_check_tk(T, K);
-  if (st != HM_OK) return st;
-  if (E < 1 || out->row_capacity < 0) return HM_ERR_SHAPE;
-  if (T > 0 && (!topk_ids || !topk_weights)) return HM_ERR_NULL;
-  if (out->load_expert && (!out->load_rank || !out->load_node)) return HM_ERR_NULL;
-  if (!out->load_expert && (out->load_rank || out->load_node)) return HM_ERR_NULL;
-  st = hm_check_topology(topo);
-  if (st != HM_OK) return st;
-  if (level != HM_DEDUP_NONE && level != HM_DEDUP_GPU && level != HM_DEDUP_NODE) return HM_ERR_LEVEL;
-  if (workspace_bytes < hm_plan_workspace_bytes(T, K, E, topo, level)) return HM_ERR_WORKSPACE;
-
+// Argument checks and launches of hm_plan; `counts` is the count matrix (caller's workspace or the
+// library's static scratch), already known to be large enough.
+static hm_status plan_on_counts(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+                                int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level, hm_plan_out *out,
+                                int32_t *counts, void *hip_stream) {
   hm::PlanParams p;
   p.ids = topk_ids;
   p.weights = topk_weights;
@@ -442,7 +431,7 @@ extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights,
   p.nslots = (int32_t)((int64_t)T * K);
   p.nblocks = hm::plan_blocks(p.nslots);
   p.row_capacity = out->row_capacity;
-  p.counts = (int32_t *)workspace;
+  p.counts = counts;
   p.dest_count = out->dest_count;
   p.dest_offset = out->dest_offset;
   p.row_token = out->row_token;
@@ -456,8 +445,78 @@ extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights,
   p.load_rank = out->load_rank;
   p.load_node = out->load_node;
   out->num_dest = p.Dn;
-
   return hm::launch_plan(p, (hipStream_t)hip_stream);
+}
+
+static hm_status check_plan_args(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+                                 int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
+                                 const hm_plan_out *out) {
+  if (!out || !expert_to_rank) return HM_ERR_NULL;
+  if (!out->dest_count || !out->dest_offset || !out->row_token || !out->slot_row || !out->slot_keep ||
+      !out->row_weight || !out->status)
+    return HM_ERR_NULL;
+  hm_status st = hm_check_tk(T, K);
+  if (st != HM_OK) return st;
+  if (E < 1 || out->row_capacity < 0) return HM_ERR_SHAPE;
+  if (T > 0 && (!topk_ids || !topk_weights)) return HM_ERR_NULL;
+  if (out->load_expert && (!out->load_rank || !out->load_node)) return HM_ERR_NULL;
+  if (!out->load_expert && (out->load_rank || out->load_node)) return HM_ERR_NULL;
+  st = hm_check_topology(topo);
+  if (st != HM_OK) return st;
+  if (level != HM_DEDUP_NONE && level != HM_DEDUP_GPU && level != HM_DEDUP_NODE) return HM_ERR_LEVEL;
+  return HM_OK;
+}
+
+extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+                             int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
+                             hm_plan_out *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  if (!workspace) return HM_ERR_NULL;
+  hm_status st = check_plan_args(topk_ids, topk_weights, expert_to_rank, T, K, E, topo, level, out);
+  if (st != HM_OK) return st;
+  if (workspace_bytes < hm_plan_workspace_bytes(T, K, E, topo, level)) return HM_ERR_WORKSPACE;
+  return plan_on_counts(topk_ids, topk_weights, expert_to_rank, T, K, E, topo, level, out, (int32_t *)workspace,
+                        hip_stream);
+}
+
+// ---- hm_plan_static: hm_plan for callers that cannot hand over (or allocate) a workspace ----------
+// The count matrix lives in a file-scope device array.  In host code the array's name is only a
+// stand-in for the symbol: its device address is looked up once per device and that pointer is
+// what the kernels receive.
+namespace hm {
+constexpr size_t kPlanStaticBytes = (size_t)1 << 20;   // 1 MiB per GPU, held until the process ends
+constexpr int kPlanStaticDevices = 64;
+static __device__ __align__(256) unsigned char plan_static_scratch[kPlanStaticBytes];
+static std::mutex plan_static_lock;
+static void *plan_static_ptr[kPlanStaticDevices];   // device address of the array on each GPU, 0 = not asked yet
+
+// Device address of the current GPU's copy of the scratch array (nullptr on a HIP error).
+static void *plan_static_address() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kPlanStaticDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(plan_static_lock);
+  if (!plan_static_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(plan_static_scratch)) != hipSuccess) return nullptr;
+    plan_static_ptr[dev] = ptr;
+  }
+  return plan_static_ptr[dev];
+}
+}  // namespace hm
+
+extern "C" size_t hm_plan_static_max_bytes(void) { return hm::kPlanStaticBytes; }
+
+extern "C" hm_status hm_plan_static(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
+                                    int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
+                                    hm_plan_out *out, void *hip_stream) {
+  hm_status st = check_plan_args(topk_ids, topk_weights, expert_to_rank, T, K, E, topo, level, out);
+  if (st != HM_OK) return st;
+  if (hm_plan_workspace_bytes(T, K, E, topo, level) > hm::kPlanStaticBytes) return HM_ERR_WORKSPACE;
+  void *counts = hm::plan_static_address();
+  if (!counts) return HM_ERR_HIP;
+  // Nothing in the matrix has to start at zero: the count kernel overwrites every entry the later
+  // kernels read, so the previous call's contents are harmless.
+  return plan_on_counts(topk_ids, topk_weights, expert_to_rank, T, K, E, topo, level, out, (int32_t *)counts,
+                        hip_stream);
 }
 
 extern "C" size_t hm_plan_mapped_workspace_bytes(int32_t rows, int32_t K, int32_t num_dest) {
@@ -561,7 +620,7 @@ extern "C" const char *hm_status_string(hm_status s) {
     case HM_ERR_SHAPE: return "bad shape";
     case HM_ERR_TOPOLOGY: return "bad topology (need 1..32 nodes, at most 64 ranks)";
     case HM_ERR_LEVEL: return "bad dedup level";
-    case HM_ERR_WORKSPACE: return "workspace too small";
+    case HM_ERR_WORKSPACE: return "workspace too small (hm_plan_static: sizes beyond its static scratch)";
     case HM_ERR_CAPACITY: return "row index beyond the caller's row buffers";
     case HM_ERR_BAD_ID: return "expert id or rank out of range";
     case HM_ERR_HIP: return "HIP runtime error";

@@ -97,6 +97,21 @@ def test_argument_errors_are_reported_before_any_launch(B):
     broken.slot_row = None
     assert plan(out=ctypes.byref(broken)) == B.HM_ERR_NULL
 
+    # the variant on the library's static scratch: same checks, and a size limit instead of a workspace
+    def static(ids=fake, w=fake, e2r=fake, T=4, K=2, E=8, topo=topo, level=B.HM_DEDUP_GPU, out=ref):
+        return L.hm_plan_static(ids, w, e2r, T, K, E, topo, level, out, None)
+
+    assert L.hm_plan_static_max_bytes() == 1 << 20
+    assert static(out=None) == B.HM_ERR_NULL
+    assert static(w=None) == B.HM_ERR_NULL
+    assert static(K=65) == B.HM_ERR_SHAPE
+    assert static(topo=B.hm_topology(9, 8)) == B.HM_ERR_TOPOLOGY
+    assert static(level=-1) == B.HM_ERR_LEVEL
+    assert static(out=ctypes.byref(broken)) == B.HM_ERR_NULL
+    big = B.hm_topology(8, 8)
+    assert L.hm_plan_workspace_bytes(600000, 8, 256, big, B.HM_DEDUP_GPU) > 1 << 20
+    assert static(T=600000, K=8, E=256, topo=big) == B.HM_ERR_WORKSPACE
+
     assert L.hm_dispatch_pack(fake, 4, 2, 64, None, fake, 8, None) == B.HM_ERR_NULL
     assert L.hm_dispatch_pack(None, 4, 2, 64, ref, fake, 8, None) == B.HM_ERR_NULL
     assert L.hm_dispatch_pack(fake, 4, 2, 0, ref, fake, 8, None) == B.HM_ERR_SHAPE
