@@ -3,15 +3,19 @@
 
 A step is one pass of the whole forward path over one batch of synthetic routing and
 activations already resident in HBM:
-    hm_plan -> hm_expert_load -> hm_dispatch_pack -> (identity experts) -> hm_combine
-Default workload: the DeepSeek-V3-shaped layer (T=8192, H=7168, E=256, top-8 group-limited,
-4 nodes x 8 ranks, node-level dedup).  Prints ONE JSON line on stdout; details go to stderr.
+    hm_plan (+ the expert-load counts) -> hm_dispatch_pack -> (identity experts) -> hm_combine
+Headline workload: the DeepSeek-V3-shaped layer (T=8192, H=7168, E=256, top-8 group-limited,
+4 nodes x 8 ranks, node-level dedup).  The default run then times every other workload / dedup
+level of the benchmark set the same way and adds them as the `configs` table of the ONE JSON line
+it prints on stdout; details go to stderr.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dsv3] [--level node]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dsv3] [--level node] [--no-table]
 """
 from __future__ import annotations
 
 import argparse
+import ctypes
+import hashlib
 import json
 import os
 import sys
@@ -23,25 +27,311 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 LEVELS = {"none": 0, "gpu": 1, "node": 2}
+# every other configuration of the benchmark set, timed after the headline one
+TABLE = [("tiny", "none"), ("tiny", "gpu"), ("tiny", "node"), ("qwen3", "gpu"), ("qwen3", "node"),
+         ("dsv3", "gpu"), ("dsv3", "none"), ("skew", "gpu"), ("skew", "node"), ("skew-swapped", "gpu"),
+         ("skew-swapped", "node"), ("stress", "node"), ("stress", "gpu")]
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def rows_source_digest() -> str:
+    """Identifies the row kernels a counter summary was taken on: the first 16 hex digits of the
+    SHA-256 of their source file."""
+    path = os.path.join(ROOT, "paper_2508_09591_amd", "csrc", "hm_rows.hip")
+    return hashlib.sha256(open(path, "rb").read()).hexdigest()[:16]
+
+
 def measured_traffic(workload: str, level: str, kernel: str):
-    """HBM bytes per launch from the committed rocprofv3 counter summaries (None if not measured)."""
+    """HBM bytes per launch from the committed rocprofv3 counter summaries: lines
+    `traffic <workload> <level> <entry point> <bytes> <digest of hm_rows.hip>` under profiles/.
+    A figure taken on other kernel sources than the ones in the tree is not used (None)."""
     pdir = os.path.join(ROOT, "profiles")
     if not os.path.isdir(pdir):
         return None
+    digest = rows_source_digest()
     for name in sorted(os.listdir(pdir)):
         if not name.endswith(".txt"):
             continue
         for line in open(os.path.join(pdir, name)):
             f = line.split()
-            if len(f) == 5 and f[0] == "traffic" and f[1:4] == [workload, level, kernel]:
+            if len(f) == 6 and f[0] == "traffic" and f[1:4] == [workload, level, kernel] and f[5] == digest:
                 return int(f[4])
     return None
+
+
+_probe = None
+
+
+def stream_probe(src, read_streams, dst, write_streams, block_threads=64, waves_per_cu=32, stream=None):
+    """Flat-stream reference kernel of libhmprobe.so (built beside the library, used by this
+    benchmark only): dst[j] = XOR_i src[i] over 16-byte vectors, with the given launch shape."""
+    global _probe
+    import torch
+    if _probe is None:
+        path = os.path.join(ROOT, "paper_2508_09591_amd", "libhmprobe.so")
+        if not os.path.exists(path):
+            raise RuntimeError("libhmprobe.so is not built (run __graft_entry__.build())")
+        _probe = ctypes.CDLL(path)
+        _probe.bench_stream_probe.restype = ctypes.c_int
+        _probe.bench_stream_probe.argtypes = [ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+                                              ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p]
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise TypeError("src and dst must be contiguous GPU tensors")
+    nbytes = src.numel() * src.element_size()
+    n = nbytes // (16 * read_streams)
+    if nbytes != n * 16 * read_streams or dst.numel() * dst.element_size() != n * 16 * write_streams:
+        raise ValueError("src / dst sizes do not match the stream counts")
+    s = torch.cuda.current_stream() if stream is None else stream
+    rc = _probe.bench_stream_probe(src.data_ptr(), read_streams, dst.data_ptr(), write_streams, n, block_threads,
+                                   waves_per_cu, s.cuda_stream or None)
+    if rc != 0:
+        raise RuntimeError("bench_stream_probe failed: %d" % rc)
+    return dst
+
+
+def get_workload(name):
+    """A workload of the benchmark set plus the placement to use: `skew-swapped` is the skew layer
+    under its seeded random expert placement."""
+    from paper_2508_09591_amd import workloads as W
+    if name == "skew-swapped":
+        return W.WORKLOADS["skew"], "expert_to_rank_swapped"
+    return W.WORKLOADS[name], None
+
+
+def time_send(wl, level, steps, warmup, nsets, *, label=None, placement_key=None, host_x=True, fused=True,
+              explicit_weights=False, warm_y=False, graph=False, warm_leg=False, transposes=False, with_f32=False):
+    """Times `steps` steps of the send path on one workload / level.  Returns a dict with the step
+    time, the per-call HIP-event times, algorithmic bytes and rates, and what is needed for a CPU
+    baseline (`routing`, `x_host`)."""
+    import numpy as np
+    import torch
+    from paper_2508_09591_amd import binding as B
+    from paper_2508_09591_amd import workloads as W
+
+    level_name = W.LEVEL_NAMES[level]
+    label = label or wl.name
+    T, K, H, E = wl.T, wl.K, wl.H, wl.E
+    t0 = time.time()
+    r = W.make_routing(wl)
+    e2r = r.extras[placement_key] if placement_key else r.expert_to_rank
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    ids_d, w_d, e2r_d = dev(r.topk_ids), dev(r.topk_weights), dev(e2r)
+    x = None
+    if host_x:      # the seeded activations of the workload (what the CPU baseline also uses)
+        x = W.make_activations(wl)
+        x0 = dev(x.view(np.int16)).view(torch.bfloat16)
+    else:           # same distribution, drawn on the GPU: the table rows do not feed a CPU run
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1234 + wl.seed)
+        x0 = torch.randn((T, H), dtype=torch.float32, device="cuda", generator=gen).to(torch.bfloat16)
+    log("%s level %s: inputs ready in %.1f s" % (label, level_name, time.time() - t0))
+
+    stream = torch.cuda.Stream()          # default priority
+    cw_d = w_d if explicit_weights else None      # None: hm_combine takes the weights hm_plan merged
+    plan = B.alloc_plan(T, K, E, wl.nodes, wl.ranks_per_node, level, loads=fused)
+    with torch.cuda.stream(stream):
+        B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan)
+        st, total_rows = B.hm_plan_status(plan)
+    assert st == 0, B.status_string(st)
+    c = total_rows / T
+    nsets = max(1, nsets)
+    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
+    packs = [torch.empty((total_rows, H), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
+    outs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
+    le = torch.empty(E, dtype=torch.int32, device="cuda")
+    lr = torch.empty(wl.G, dtype=torch.int32, device="cuda")
+    ln = torch.empty(wl.nodes, dtype=torch.int32, device="cuda")
+    log("workload %s level %s: T=%d H=%d K=%d E=%d %dx%d ranks, rows=%d (c=%.3f), %d buffer sets = %.2f GB"
+        % (label, level_name, T, H, K, E, wl.nodes, wl.ranks_per_node, total_rows, c, nsets,
+           nsets * (2 * T + total_rows) * H * 2 / 1e9))
+
+    # Expert outputs arrive from the exchange, not from this GPU's caches: combine therefore reads
+    # the pack buffer written sets/2 steps earlier.  With identity experts and identical X copies
+    # it holds the same rows as the one dispatch has just written.
+    y_shift = 0 if warm_y else nsets // 2
+    with torch.cuda.stream(stream):
+        for s in range(nsets):
+            B.hm_dispatch_pack(xs[s], plan, packs[s], stream=stream)
+    torch.cuda.synchronize()
+
+    def step(i, ev=None):
+        # ev: a start and a stop event per call, each pair recorded around its own call only, so that
+        # the marker between two calls is charged to neither
+        s = i % nsets
+        ys = (s + y_shift) % nsets
+        if ev: ev[0].record(stream)
+        B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan, stream=stream)
+        if ev: ev[1].record(stream); ev[2].record(stream)
+        if not fused:        # otherwise hm_plan has already produced the three load arrays
+            B.hm_expert_load(ids_d, e2r_d, wl.nodes, wl.ranks_per_node, le, lr, ln, stream=stream)
+        if ev: ev[3].record(stream); ev[4].record(stream)
+        B.hm_dispatch_pack(xs[s], plan, packs[s], stream=stream)
+        if ev: ev[5].record(stream); ev[6].record(stream)
+        B.hm_combine(packs[ys], cw_d, plan, outs[s], stream=stream)     # identity experts: Y = packed rows
+        if ev: ev[7].record(stream)
+
+    # ---- warm-up, then the timed region: exactly `steps` steps between two synchronisations ----
+    run = step
+    if graph:
+        # The entry points only enqueue kernels, so a step records into a HIP graph as it is.
+        for i in range(nsets):
+            step(i)
+        torch.cuda.synchronize()
+        graphs = []
+        for i in range(nsets):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=stream):
+                step(i)
+            graphs.append(g)
+        run = lambda i: graphs[i % nsets].replay()
+    for i in range(warmup):
+        run(i)
+    torch.cuda.synchronize()
+    t_begin = time.perf_counter()
+    for i in range(steps):
+        run(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_begin
+    ms_per_step = elapsed * 1e3 / steps
+
+    # ---- per-kernel durations: the same steps again with HIP events on the launch stream ------
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(steps)]
+    for i in range(steps):
+        step(i, events[i])
+    torch.cuda.synchronize()
+    names = ["hm_plan", "hm_expert_load", "hm_dispatch_pack", "hm_combine"]
+    per_call = {n: sorted(e[2 * j].elapsed_time(e[2 * j + 1]) for e in events) for j, n in enumerate(names)}
+    avg_ms = {n: sum(v) / len(v) for n, v in per_call.items()}
+    min_ms = {n: v[0] for n, v in per_call.items()}
+    med_ms = {n: v[len(v) // 2] for n, v in per_call.items()}
+
+    # the same two kernels back to back on ONE buffer set (inputs may sit in the 256 MB Infinity
+    # Cache): reported beside the cold figures, never used for `value` or the roofline fraction
+    warm_ms = {"hm_dispatch_pack": None, "hm_combine": None}
+    if warm_leg:
+        wev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        for e in wev:
+            e[0].record(stream)
+            B.hm_dispatch_pack(xs[0], plan, packs[0], stream=stream)
+            e[1].record(stream)
+            B.hm_combine(packs[0], cw_d, plan, outs[0], stream=stream)
+            e[2].record(stream)
+        torch.cuda.synchronize()
+        warm_ms = {"hm_dispatch_pack": sorted(e[0].elapsed_time(e[1]) for e in wev)[len(wev) // 2],
+                   "hm_combine": sorted(e[1].elapsed_time(e[2]) for e in wev)[len(wev) // 2]}
+
+    # correctness of what was timed: identity experts + weights summing to 1 -> output == input
+    assert torch.equal(outs[(steps - 1) % nsets], xs[(steps - 1) % nsets]), "round trip failed"
+    st, tr = B.hm_plan_status(plan, stream=stream)
+    assert st == 0 and tr == total_rows
+    loads = (plan.load_expert, plan.load_rank, plan.load_node) if fused else (le, lr, ln)
+    assert int(loads[0].sum().item()) == T * K and int(loads[2].sum().item()) >= T
+
+    row_bytes = 2 * H
+    alg_bytes = {"hm_dispatch_pack": (1 + c) * T * row_bytes, "hm_combine": (c + 1) * T * row_bytes}
+    kern = {}
+    for n in ("hm_dispatch_pack", "hm_combine"):
+        gbs = alg_bytes[n] / (avg_ms[n] * 1e-3) / 1e9
+        kern[n] = {"avg_ms": round(avg_ms[n], 5), "median_ms": round(med_ms[n], 5), "min_ms": round(min_ms[n], 5),
+                   "warm_single_set_median_ms": None if warm_ms[n] is None else round(warm_ms[n], 5), "alg_bytes": int(alg_bytes[n]),
+                   "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
+                   "traffic": measured_traffic(label, level_name, n)}
+        if kern[n]["traffic"]:      # HBM bytes the counters saw per launch over this run's launch time
+            kern[n]["counter_GBps"] = round(kern[n]["traffic"] / (avg_ms[n] * 1e-3) / 1e9, 1)
+            kern[n]["traffic_over_algorithmic"] = round(kern[n]["traffic"] / alg_bytes[n], 4)
+    pair_ms = avg_ms["hm_dispatch_pack"] + avg_ms["hm_combine"]
+    pair_gbs = (alg_bytes["hm_dispatch_pack"] + alg_bytes["hm_combine"]) / (pair_ms * 1e-3) / 1e9
+    log("per-call (HIP events, avg/median/min ms): " + ", ".join("%s %.4f/%.4f/%.4f" % (n, avg_ms[n], med_ms[n], min_ms[n]) for n in names))
+    if warm_leg:
+        log("warm, one buffer set (median ms): dispatch %.4f, combine %.4f" % (warm_ms["hm_dispatch_pack"], warm_ms["hm_combine"]))
+    log("dispatch+combine: %.4f ms -> %.1f GB/s algorithmic = %.1f%% of %.0f GB/s; %.2f M tokens/s (pair only); step %.4f ms"
+        % (pair_ms, pair_gbs, 100 * pair_gbs / HBM_PEAK_GBS, HBM_PEAK_GBS, T / (pair_ms * 1e-3) / 1e6, ms_per_step))
+
+    def timed(fn, nbytes, what):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        with torch.cuda.stream(stream):
+            for i in range(max(2, warmup)):
+                fn()
+            for a, b in evs:
+                a.record(stream)
+                fn()
+                b.record(stream)
+        torch.cuda.synchronize()
+        tms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
+        gbs = nbytes / (tms * 1e-3) / 1e9
+        log("%s: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)" % (what, tms, gbs, 100 * gbs / HBM_PEAK_GBS))
+        return {"avg_ms": round(tms, 5), "alg_bytes": int(nbytes), "achieved_GBps": round(gbs, 1),
+                "frac": round(gbs / HBM_PEAK_GBS, 4)}
+
+    extra = {}
+    if transposes:      # the backward row of the 64 Ki-token layer: gradients back to the packed layout
+        gout = torch.randn((T, H), dtype=torch.float32, device="cuda") * 1e-2
+        gy = torch.empty((total_rows, H), dtype=torch.float32, device="cuda")
+        tb = (1 + c) * T * 4 * H
+        extra["hm_combine_transpose"] = timed(lambda: B.hm_combine_transpose(gout, plan, gy, stream=stream), tb,
+                                              "hm_combine_transpose")
+        del gy
+        gout16 = gout.to(torch.bfloat16)
+        gy16 = torch.empty((total_rows, H), dtype=torch.bfloat16, device="cuda")
+        extra["hm_combine_transpose_bf16"] = timed(lambda: B.hm_combine_transpose_bf16(gout16, plan, gy16, stream=stream),
+                                                   tb / 2, "hm_combine_transpose_bf16")
+        del gout, gout16, gy16
+    if with_f32:
+        y32 = torch.randn((total_rows, H), dtype=torch.float32, device="cuda")
+        o32 = torch.empty((T, H), dtype=torch.float32, device="cuda")
+        extra["hm_combine_f32"] = timed(lambda: B.hm_combine_f32(y32, cw_d, plan, o32, stream=stream),
+                                        (1 + c) * T * 4 * H, "hm_combine_f32")
+        del y32, o32
+
+    res = {"label": label, "level": level_name, "T": T, "H": H, "K": K, "E": E, "nodes": wl.nodes, "rpn": wl.ranks_per_node,
+           "total_rows": total_rows, "c": c, "nsets": nsets, "y_shift": y_shift, "ms_per_step": ms_per_step,
+           "tokens_per_s": T / (elapsed / steps), "kern": kern, "pair_ms": pair_ms, "pair_gbs": pair_gbs,
+           "plan_ms": avg_ms["hm_plan"], "expert_load_ms": None if fused else avg_ms["hm_expert_load"],
+           "alg_bytes": alg_bytes, "extra": extra, "routing": r, "e2r": e2r, "x_host": x, "stream": stream}
+    del xs, packs, outs
+    torch.cuda.empty_cache()
+    return res
+
+
+def flat_stream_references(c, total_bytes, nsets, stream):
+    """Context for the roofline fractions: flat streams with the read : write mix of the two row
+    kernels and NO indirection, at the same total bytes.  For every mix the probe kernel's launch
+    shape (workgroup size, cap on resident waves per CU) is swept and the best median is kept."""
+    import torch
+    cr = max(1, min(16, int(round(c))))
+    mixes = [(1, 1), (1, cr), (cr, 1)] if cr > 1 else [(1, 1)]    # a plain copy, dispatch's mix, combine's mix
+    shapes = [(b, w) for b in (64, 256) for w in (32, 24, 20, 16, 12, 8)]
+    total_vec = int(total_bytes) // 16
+    out = {}
+    for nr, nw in mixes:
+        n = total_vec // (nr + nw)
+        srcs = [torch.empty((nr, n, 4), dtype=torch.int32, device="cuda").fill_(7) for _ in range(nsets)]
+        dsts = [torch.empty((nw, n, 4), dtype=torch.int32, device="cuda") for _ in range(nsets)]
+        best = None
+        for block, waves in shapes:
+            pev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(12)]
+            for i in range(3):
+                stream_probe(srcs[i % nsets], nr, dsts[i % nsets], nw, block, waves, stream=stream)
+            for i, (a, b) in enumerate(pev):
+                a.record(stream)
+                stream_probe(srcs[i % nsets], nr, dsts[i % nsets], nw, block, waves, stream=stream)
+                b.record(stream)
+            torch.cuda.synchronize()
+            pms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
+            if best is None or pms < best[0]:
+                best = (pms, block, waves)
+        pms, block, waves = best
+        gbs = (nr + nw) * n * 16 / (pms * 1e-3) / 1e9
+        out["%dr+%dw" % (nr, nw)] = {"median_ms": round(pms, 5), "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
+                                     "best_shape": {"block_threads": block, "waves_per_cu": waves}}
+        del srcs, dsts
+    log("reference: flat streams of %d MB, no indirection, best of %d launch shapes each: " % (total_vec * 16 // 1000000, len(shapes))
+        + ", ".join("%s %.1f%% (%d threads, %d waves/CU)" % (k, 100 * v["frac"], v["best_shape"]["block_threads"],
+                                                            v["best_shape"]["waves_per_cu"]) for k, v in out.items()))
+    return out
 
 
 def main() -> int:
@@ -64,13 +354,23 @@ def main() -> int:
                     help="call hm_expert_load as its own pair of launches instead of letting hm_plan fill the loads")
     ap.add_argument("--separate-cuts", action="store_true",
                     help="planner path: one hm_swap_counts call per group cut instead of one hm_swap_counts_multi")
+    ap.add_argument("--monitored", action="store_true",
+                    help="planner path: feed the time model with the row counts the receiver-stage plans produce "
+                         "(the monitored quantities of Alg.1) next to the fan-in proxy")
+    ap.add_argument("--explicit-weights", action="store_true",
+                    help="pass the router weights to hm_combine (every wave merges the K slots itself) instead of "
+                         "letting it use the weights hm_plan merged")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose (stderr only)")
+    ap.add_argument("--no-table", action="store_true",
+                    help="send path: time the named workload only, not the table of all configurations")
+    ap.add_argument("--table-steps", type=int, default=30, help="timed steps per row of the configurations table")
+    ap.add_argument("--with-transpose", action="store_true", help="also time hm_combine_transpose on the named workload")
     ap.add_argument("--graph", action="store_true",
                     help="send path: capture one step per buffer set in a HIP graph and time graph replays")
     ap.add_argument("--no-warm-leg", action="store_true",
-                    help="skip the extra warm (single buffer set) timing, so that a kernel trace holds cold launches only")
-    ap.add_argument("--with-f32", action="store_true", help="also time hm_combine_f32 on fp32 rows (stderr only)")
+                    help="skip the extra warm (single buffer set) timing and the reference streams, so that a kernel "
+                         "trace holds cold launches of the library's kernels only")
+    ap.add_argument("--with-f32", action="store_true", help="also time hm_combine_f32 on fp32 rows")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 1 GiB device copy a few times (reference for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -80,10 +380,8 @@ def main() -> int:
               "no collectives and no sharding) -- rerun with --gpus 1", file=sys.stderr)
         return 2
 
-    import numpy as np
     import torch
     from paper_2508_09591_amd import binding as B
-    from paper_2508_09591_amd import workloads as W
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; there is no CPU path", file=sys.stderr)
@@ -96,194 +394,24 @@ def main() -> int:
         return run_planner(args)
     if args.path == "table4":
         return run_table4(args)
-    wl = W.WORKLOADS[args.workload]
+    return run_send(args)
+
+
+def run_send(args) -> int:
+    import dataclasses
+    import torch
+    wl, placement_key = get_workload(args.workload)
+    label = args.workload
     if args.tokens and args.tokens != wl.T:
-        import dataclasses
-        wl = dataclasses.replace(wl, T=args.tokens, name="%s@T=%d" % (wl.name, args.tokens))   # no stored traffic figures
+        wl = dataclasses.replace(wl, T=args.tokens)
+        label = "%s@T=%d" % (label, args.tokens)     # no stored traffic figures for such a size
     level = LEVELS[args.level] if args.level else wl.levels[0]
-    level_name = W.LEVEL_NAMES[level]
-    T, K, H, E = wl.T, wl.K, wl.H, wl.E
-
-    # ---- inputs, resident in HBM before anything is timed ------------------------------------
-    t0 = time.time()
-    r = W.make_routing(wl)
-    x = W.make_activations(wl)
-    log("inputs generated in %.1f s" % (time.time() - t0))
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    ids_d, w_d, e2r_d = dev(r.topk_ids), dev(r.topk_weights), dev(r.expert_to_rank)
-    x0 = dev(x.view(np.int16)).view(torch.bfloat16)
-
-    stream = torch.cuda.Stream()          # default priority
-    fused = not args.separate_load
-    plan = B.alloc_plan(T, K, E, wl.nodes, wl.ranks_per_node, level, loads=fused)
-    with torch.cuda.stream(stream):
-        B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan)
-        st, total_rows = B.hm_plan_status(plan)
-    assert st == 0, B.status_string(st)
-    c = total_rows / T
-    nsets = max(1, args.sets)
-    xs = [x0] + [x0.clone() for _ in range(nsets - 1)]
-    packs = [torch.empty((total_rows, H), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
-    outs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(nsets)]
-    le = torch.empty(E, dtype=torch.int32, device="cuda")
-    lr = torch.empty(wl.G, dtype=torch.int32, device="cuda")
-    ln = torch.empty(wl.nodes, dtype=torch.int32, device="cuda")
-    log("workload %s level %s: T=%d H=%d K=%d E=%d %dx%d ranks, rows=%d (c=%.3f), %d buffer sets = %.2f GB"
-        % (wl.name, level_name, T, H, K, E, wl.nodes, wl.ranks_per_node, total_rows, c, nsets,
-           nsets * (2 * T + total_rows) * H * 2 / 1e9))
-
-    # Expert outputs arrive from the exchange, not from this GPU's caches: combine therefore reads
-    # the pack buffer written sets/2 steps earlier.  With identity experts and identical X copies
-    # it holds the same rows as the one dispatch has just written.
-    y_shift = 0 if args.warm_y else nsets // 2
-    with torch.cuda.stream(stream):
-        for s in range(nsets):
-            B.hm_dispatch_pack(xs[s], plan, packs[s], stream=stream)
-    torch.cuda.synchronize()
-
-    def step(i, ev=None):
-        # ev: a start and a stop event per call, each pair recorded around its own call only, so that
-        # the marker between two calls is charged to neither
-        s = i % nsets
-        ys = (s + y_shift) % nsets
-        if ev: ev[0].record(stream)
-        B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan, stream=stream)
-        if ev: ev[1].record(stream); ev[2].record(stream)
-        if not fused:        # otherwise hm_plan has already produced the three load arrays
-            B.hm_expert_load(ids_d, e2r_d, wl.nodes, wl.ranks_per_node, le, lr, ln, stream=stream)
-        if ev: ev[3].record(stream); ev[4].record(stream)
-        B.hm_dispatch_pack(xs[s], plan, packs[s], stream=stream)
-        if ev: ev[5].record(stream); ev[6].record(stream)
-        B.hm_combine(packs[ys], w_d, plan, outs[s], stream=stream)     # identity experts: Y = packed rows
-        if ev: ev[7].record(stream)
-
-    # ---- warm-up, then the timed region: exactly `steps` steps between two synchronisations ----
-    run = step
-    if args.graph:
-        # The entry points only enqueue kernels, so a step records into a HIP graph as it is.
-        for i in range(nsets):
-            step(i)
-        torch.cuda.synchronize()
-        graphs = []
-        for i in range(nsets):
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g, stream=stream):
-                step(i)
-            graphs.append(g)
-        run = lambda i: graphs[i % nsets].replay()
-    for i in range(args.warmup):
-        run(i)
-    torch.cuda.synchronize()
-    t_begin = time.perf_counter()
-    for i in range(args.steps):
-        run(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_begin
-    ms_per_step = elapsed * 1e3 / args.steps
-    tokens_per_s = T / (elapsed / args.steps)
-
-    # ---- per-kernel durations: the same steps again with HIP events on the launch stream ------
-    events = [[torch.cuda.Event(enable_timing=True) for _ in range(8)] for _ in range(args.steps)]
-    for i in range(args.steps):
-        step(i, events[i])
-    torch.cuda.synchronize()
-    names = ["hm_plan", "hm_expert_load", "hm_dispatch_pack", "hm_combine"]
-    per_call = {n: sorted(e[2 * j].elapsed_time(e[2 * j + 1]) for e in events) for j, n in enumerate(names)}
-    avg_ms = {n: sum(v) / len(v) for n, v in per_call.items()}
-    min_ms = {n: v[0] for n, v in per_call.items()}
-    med_ms = {n: v[len(v) // 2] for n, v in per_call.items()}
-
-    # the same two kernels back to back on ONE buffer set (inputs may sit in the 256 MB Infinity
-    # Cache): reported beside the cold figures, never used for `value` or the roofline fraction
-    wev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    for e in (wev if not args.no_warm_leg else []):
-        e[0].record(stream)
-        B.hm_dispatch_pack(xs[0], plan, packs[0], stream=stream)
-        e[1].record(stream)
-        B.hm_combine(packs[0], w_d, plan, outs[0], stream=stream)
-        e[2].record(stream)
-    torch.cuda.synchronize()
-    warm_ms = {"hm_dispatch_pack": None, "hm_combine": None}
-    if not args.no_warm_leg:
-        warm_ms = {"hm_dispatch_pack": sorted(e[0].elapsed_time(e[1]) for e in wev)[len(wev) // 2],
-                   "hm_combine": sorted(e[1].elapsed_time(e[2]) for e in wev)[len(wev) // 2]}
-
-    # correctness of what was timed: identity experts + weights summing to 1 -> output == input
-    assert torch.equal(outs[(args.steps - 1) % nsets], xs[(args.steps - 1) % nsets]), "round trip failed"
-    st, tr = B.hm_plan_status(plan, stream=stream)
-    assert st == 0 and tr == total_rows
-    loads = (plan.load_expert, plan.load_rank, plan.load_node) if fused else (le, lr, ln)
-    assert int(loads[0].sum().item()) == T * K and int(loads[2].sum().item()) >= T
-
-    row_bytes = 2 * H
-    alg_bytes = {"hm_dispatch_pack": (1 + c) * T * row_bytes, "hm_combine": (c + 1) * T * row_bytes}
-    kern = {}
-    for n in ("hm_dispatch_pack", "hm_combine"):
-        gbs = alg_bytes[n] / (avg_ms[n] * 1e-3) / 1e9
-        kern[n] = {"avg_ms": round(avg_ms[n], 5), "median_ms": round(med_ms[n], 5), "min_ms": round(min_ms[n], 5),
-                   "warm_single_set_median_ms": None if warm_ms[n] is None else round(warm_ms[n], 5), "alg_bytes": int(alg_bytes[n]),
-                   "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
-                   "traffic": measured_traffic(wl.name, level_name, n)}
-        if kern[n]["traffic"]:      # HBM bytes the counters saw per launch over this run's launch time
-            kern[n]["counter_GBps"] = round(kern[n]["traffic"] / (avg_ms[n] * 1e-3) / 1e9, 1)
+    head = time_send(wl, level, args.steps, args.warmup, args.sets, label=label, placement_key=placement_key,
+                     fused=not args.separate_load, explicit_weights=args.explicit_weights, warm_y=args.warm_y,
+                     graph=args.graph, warm_leg=not args.no_warm_leg, transposes=args.with_transpose, with_f32=args.with_f32)
+    T, K, H, E = head["T"], head["K"], head["H"], head["E"]
+    level_name, c, kern, stream = head["level"], head["c"], head["kern"], head["stream"]
     dominant = max(kern, key=lambda n: kern[n]["avg_ms"])
-    pair_ms = avg_ms["hm_dispatch_pack"] + avg_ms["hm_combine"]
-    pair_gbs = (alg_bytes["hm_dispatch_pack"] + alg_bytes["hm_combine"]) / (pair_ms * 1e-3) / 1e9
-    log("per-call (HIP events, avg/median/min ms): " + ", ".join("%s %.4f/%.4f/%.4f" % (n, avg_ms[n], med_ms[n], min_ms[n]) for n in names))
-    if not args.no_warm_leg:
-        log("warm, one buffer set (median ms): dispatch %.4f, combine %.4f" % (warm_ms["hm_dispatch_pack"], warm_ms["hm_combine"]))
-    log("dispatch+combine: %.4f ms -> %.1f GB/s algorithmic = %.1f%% of %.0f GB/s; %.2f M tokens/s (pair only)"
-        % (pair_ms, pair_gbs, 100 * pair_gbs / HBM_PEAK_GBS, HBM_PEAK_GBS, T / (pair_ms * 1e-3) / 1e6))
-
-    if args.with_transpose:
-        gout = torch.randn((T, H), dtype=torch.float32, device="cuda") * 1e-2
-        gy = torch.empty((total_rows, H), dtype=torch.float32, device="cuda")
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-        with torch.cuda.stream(stream):
-            for i in range(args.warmup):
-                B.hm_combine_transpose(gout, plan, gy, stream=stream)
-            for a, b in evs:
-                a.record(stream)
-                B.hm_combine_transpose(gout, plan, gy, stream=stream)
-                b.record(stream)
-        torch.cuda.synchronize()
-        tms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
-        tb = (1 + c) * T * 4 * H
-        log("hm_combine_transpose: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
-            % (tms, tb / (tms * 1e-3) / 1e9, 100 * tb / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
-        del gy
-        gout16 = gout.to(torch.bfloat16)
-        gy16 = torch.empty((total_rows, H), dtype=torch.bfloat16, device="cuda")
-        with torch.cuda.stream(stream):
-            for i in range(args.warmup):
-                B.hm_combine_transpose_bf16(gout16, plan, gy16, stream=stream)
-            for a, b in evs:
-                a.record(stream)
-                B.hm_combine_transpose_bf16(gout16, plan, gy16, stream=stream)
-                b.record(stream)
-        torch.cuda.synchronize()
-        tms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
-        log("hm_combine_transpose_bf16: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
-            % (tms, tb / 2 / (tms * 1e-3) / 1e9, 100 * tb / 2 / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
-        del gout16, gy16
-
-    if args.with_f32:
-        y32 = torch.randn((total_rows, H), dtype=torch.float32, device="cuda")
-        o32 = torch.empty((T, H), dtype=torch.float32, device="cuda")
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-        with torch.cuda.stream(stream):
-            for i in range(args.warmup):
-                B.hm_combine_f32(y32, w_d, plan, o32, stream=stream)
-            for a, b in evs:
-                a.record(stream)
-                B.hm_combine_f32(y32, w_d, plan, o32, stream=stream)
-                b.record(stream)
-        torch.cuda.synchronize()
-        tms = sum(a.elapsed_time(b) for a, b in evs) / len(evs)
-        tb = (1 + c) * T * 4 * H
-        log("hm_combine_f32: %.4f ms -> %.1f GB/s algorithmic (%.1f%% of peak)"
-            % (tms, tb / (tms * 1e-3) / 1e9, 100 * tb / (tms * 1e-3) / 1e9 / HBM_PEAK_GBS))
-        del y32, o32
 
     # ---- context for the roofline fraction: the runtime's own device-to-device copy of 1 GiB -------
     # (also the known-size launch the rocprofv3 counter runs are scaled by: --calibrate-copy)
@@ -305,87 +433,95 @@ def main() -> int:
                     "achieved_GBps": round(cgbs, 1), "frac": round(cgbs / HBM_PEAK_GBS, 4)}
         log("reference: plain 1 GiB device copy %.4f ms -> %.1f GB/s = %.1f%% of peak" % (cms, cgbs, 100 * cgbs / HBM_PEAK_GBS))
         del src, dst
-
-    # ---- context: flat streams with the same read : write mix and no indirection ------------------
     stream_ref = None
-    if copy_ref is not None:
-        stream_ref = {}
-        cr = max(1, min(16, int(round(c))))
-        mixes = [(1, 1), (1, cr), (cr, 1)] if cr > 1 else [(1, 1)]    # a plain copy, dispatch's mix, combine's mix
-        total_vec = int(alg_bytes["hm_dispatch_pack"]) // 16            # the bytes one row kernel moves
-        for nr, nw in mixes:
-            n = total_vec // (nr + nw)
-            srcs = [torch.empty((nr, n, 4), dtype=torch.int32, device="cuda").fill_(7) for _ in range(nsets)]
-            dsts = [torch.empty((nw, n, 4), dtype=torch.int32, device="cuda") for _ in range(nsets)]
-            pev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(40)]
-            for i in range(8):
-                B.hm_stream_probe(srcs[i % nsets], nr, dsts[i % nsets], nw, stream=stream)
-            for i, (a, b) in enumerate(pev):
-                a.record(stream)
-                B.hm_stream_probe(srcs[i % nsets], nr, dsts[i % nsets], nw, stream=stream)
-                b.record(stream)
-            torch.cuda.synchronize()
-            pms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
-            gbs = (nr + nw) * n * 16 / (pms * 1e-3) / 1e9
-            stream_ref["%dr+%dw" % (nr, nw)] = {"median_ms": round(pms, 5), "achieved_GBps": round(gbs, 1),
-                                                 "frac": round(gbs / HBM_PEAK_GBS, 4)}
-            del srcs, dsts
-        log("reference: flat streams of %d MB, no indirection (hm_stream_probe): " % (total_vec * 16 // 1000000)
-            + ", ".join("%s %.1f%%" % (k, 100 * v["frac"]) for k, v in stream_ref.items()))
+    if not args.no_warm_leg:
+        stream_ref = flat_stream_references(c, head["alg_bytes"]["hm_dispatch_pack"], head["nsets"], stream)
 
     # ---- the oracle on this machine's host cores (reported baseline, not the target) ---------------
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
         oracle.build()
+        r, x = head["routing"], head["x_host"]
         best = None
         reps = 0
         t_all = time.perf_counter()
         while reps < 12 and (time.perf_counter() - t_all) < 12:      # about 10 s of CPU work
             t1 = time.perf_counter()
-            op = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
-            oracle.expert_load(r.topk_ids, r.expert_to_rank, wl.nodes, wl.ranks_per_node)
+            op = oracle.plan(r.topk_ids, r.topk_weights, head["e2r"], head["nodes"], head["rpn"], level)
+            oracle.expert_load(r.topk_ids, head["e2r"], head["nodes"], head["rpn"])
             opk = oracle.dispatch_pack(x, op.row_token)
-            oo = oracle.combine(opk, r.topk_weights, op.slot_row)
+            oracle.combine(opk, r.topk_weights, op.slot_row)
             dt = time.perf_counter() - t1
             best = dt if best is None else min(best, dt)
             reps += 1
-        assert op.total_rows == total_rows
+        assert op.total_rows == head["total_rows"]
         cpu = {"value": round(T / best, 1), "unit": "tokens/s", "cores": 1, "kind": "oracle",
                "sample": "the whole %s batch (T=%d, level %s), same call sequence, best of %d passes, %.2f s per pass"
-                         % (wl.name, T, level_name, reps, best)}
+                         % (label, T, level_name, reps, best)}
         log("cpu oracle: %.2f s per pass -> %.0f tokens/s on 1 core (%d cores visible)" % (best, T / best, os.cpu_count()))
+
+    # ---- every other configuration of the benchmark set, the same step, fewer repetitions -------
+    table = None
+    if not args.no_table:
+        table = []
+        for name, lname in TABLE:
+            twl, tkey = get_workload(name)
+            if name == label and lname == level_name:
+                continue
+            big = twl.T >= 32768
+            res = time_send(twl, LEVELS[lname], max(5, args.table_steps // (3 if big else 1)), min(args.warmup, 5), args.sets,
+                            label=name, placement_key=tkey, host_x=False, transposes=big)
+            row = {"workload": name, "level": lname, "T": res["T"], "H": res["H"], "E": res["E"], "K": res["K"],
+                   "ranks": "%dx%d" % (res["nodes"], res["rpn"]), "rows_per_token": round(res["c"], 4),
+                   "tokens_per_s": round(res["tokens_per_s"], 1), "ms_per_step": round(res["ms_per_step"], 5),
+                   "plan_us": round(res["plan_ms"] * 1e3, 2),
+                   "dispatch": {k: res["kern"]["hm_dispatch_pack"][k] for k in ("avg_ms", "achieved_GBps", "frac", "traffic")},
+                   "combine": {k: res["kern"]["hm_combine"][k] for k in ("avg_ms", "achieved_GBps", "frac", "traffic")},
+                   "pair_GBps": round(res["pair_gbs"], 1), "pair_frac": round(res["pair_gbs"] / HBM_PEAK_GBS, 4)}
+            row.update(res["extra"])
+            table.append(row)
+        log("%-13s %-5s %6s %5s %7s %9s %9s %8s %8s %7s" % ("workload", "level", "T", "H", "rows/t", "Mtok/s", "plan us", "disp %", "comb %", "pair %"))
+        for row in table:
+            log("%-13s %-5s %6d %5d %7.3f %9.2f %9.2f %8.1f %8.1f %7.1f"
+                % (row["workload"], row["level"], row["T"], row["H"], row["rows_per_token"], row["tokens_per_s"] / 1e6,
+                   row["plan_us"], 100 * row["dispatch"]["frac"], 100 * row["combine"]["frac"], 100 * row["pair_frac"]))
 
     result = {
         "metric": "dedup dispatch+combine tokens/s (plan + expert_load + dispatch_pack + combine per step)",
-        "expert_load": "filled by hm_plan (fused)" if fused else "separate hm_expert_load call",
+        "expert_load": "separate hm_expert_load call" if args.separate_load else "filled by hm_plan (fused)",
+        "combine_weights": "caller's router weights, merged in the kernel" if args.explicit_weights else "merged by hm_plan (row_weight)",
         "launch": "HIP graph replay, one graph per buffer set" if args.graph else "eager launches on one stream",
-        "value": round(tokens_per_s, 1),
+        "value": round(head["tokens_per_s"], 1),
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": round(head["ms_per_step"], 5),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "%s: T=%d H=%d E=%d top-%d, %d nodes x %d ranks, dedup level %s, identity experts"
-                               % (wl.name, T, H, E, K, wl.nodes, wl.ranks_per_node, level_name),
-                   "rows_per_token": round(c, 4), "buffer_sets": nsets,
-                   "combine_input": "same-step buffer (warm)" if args.warm_y else "identical buffer written %d steps earlier (cold)" % y_shift},
+                               % (label, T, H, E, K, head["nodes"], head["rpn"], level_name),
+                   "rows_per_token": round(c, 4), "buffer_sets": head["nsets"],
+                   "combine_input": "same-step buffer (warm)" if args.warm_y else "identical buffer written %d steps earlier (cold)" % head["y_shift"]},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": kern[dominant]["achieved_GBps"],
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kern[dominant]["frac"],
-                     "traffic": measured_traffic(wl.name, level_name, dominant)},
+                     "traffic": kern[dominant]["traffic"],
+                     "traffic_source": "rocprofv3 FETCH_SIZE + WRITE_SIZE summary under profiles/, taken on these kernel sources"
+                                       if kern[dominant]["traffic"] else None},
         "cpu_baseline": cpu,
         "kernels": kern,
-        "pair": {"ms": round(pair_ms, 5), "achieved_GBps": round(pair_gbs, 1), "frac": round(pair_gbs / HBM_PEAK_GBS, 4),
-                 "tokens_per_s": round(T / (pair_ms * 1e-3), 1)},
-        "plan_ms": round(avg_ms["hm_plan"], 5),
+        "pair": {"ms": round(head["pair_ms"], 5), "achieved_GBps": round(head["pair_gbs"], 1),
+                 "frac": round(head["pair_gbs"] / HBM_PEAK_GBS, 4), "tokens_per_s": round(T / (head["pair_ms"] * 1e-3), 1)},
+        "plan_ms": round(head["plan_ms"], 5),
         "device_copy_reference": copy_ref,
         "flat_stream_reference": stream_ref,
-        "expert_load_ms": None if fused else round(avg_ms["hm_expert_load"], 5),
+        "expert_load_ms": None if head["expert_load_ms"] is None else round(head["expert_load_ms"], 5),
+        "other_calls": head["extra"] or None,
+        "configs": table,
     }
     print(json.dumps(result), flush=True)
     return 0
@@ -472,10 +608,10 @@ def run_recv(args) -> int:
     calls = [
         ("A.hm_plan_mapped", lambda s: B.hm_plan_mapped(idsA, wA, dmA, R, True, plan=planA, stream=stream), 0),
         ("A.hm_dispatch_pack", lambda s: B.hm_dispatch_pack(inA[s], planA, outA[s], stream=stream), (rowsA_in + rowsA_out) * 2 * H),
-        ("A.hm_combine_mix", lambda s: B.hm_combine_mix(outA[(s + nsets // 2) % nsets], wA, planA, backA[s], stream=stream), (rowsA_in + rowsA_out) * 2 * H),
+        ("A.hm_combine_mix", lambda s: B.hm_combine_mix(outA[(s + nsets // 2) % nsets], None, planA, backA[s], stream=stream), (rowsA_in + rowsA_out) * 2 * H),
         ("B.hm_plan_mapped", lambda s: B.hm_plan_mapped(idsB, wB, dmB, n_local, False, plan=planB, stream=stream), 0),
         ("B.hm_dispatch_pack", lambda s: B.hm_dispatch_pack(inB[s], planB, outB[s], stream=stream), (rowsB_in + rowsB_out) * 2 * H),
-        ("B.hm_combine_mix", lambda s: B.hm_combine_mix(outB[(s + nsets // 2) % nsets], wB, planB, backB[s], stream=stream), (rowsB_in + rowsB_out) * 2 * H),
+        ("B.hm_combine_mix", lambda s: B.hm_combine_mix(outB[(s + nsets // 2) % nsets], None, planB, backB[s], stream=stream), (rowsB_in + rowsB_out) * 2 * H),
     ]
 
     def step(i, ev=None):
@@ -659,7 +795,7 @@ def run_table4(args) -> int:
             def pair(i):
                 s_ = i % nsets
                 B.hm_dispatch_pack(xs[s_], plan, packs[s_], stream=stream)
-                B.hm_combine(packs[(s_ + 2) % nsets], w_d, plan, outs[s_], stream=stream)
+                B.hm_combine(packs[(s_ + 2) % nsets], None, plan, outs[s_], stream=stream)
 
             for i in range(args.warmup):
                 pair(i)

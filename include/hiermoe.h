@@ -85,6 +85,15 @@ typedef struct {
  *                             hm_plan also produces the counts of hm_expert_load, in the same
  *                             launches (the planner of Section IV needs them every iteration).
  *                             hm_plan_mapped ignores them.
+ *
+ * Two more host fields steer launch shapes only, never results.  `max_rows_per_token` is written
+ * by hm_plan (K at level none, else min(K, num_dest)) and zeroed by hm_plan_mapped (a hop table
+ * may leave most slots without a copy, so there is no useful bound).  `expected_rows` is the
+ * number of packed rows the caller expects the plan to hold, 0 = unknown: hm_plan_status stores
+ * total_rows there, a caller that does not synchronise may store the previous iteration's count;
+ * hm_plan leaves it alone.  The row kernels take rows per token from expected_rows / T if it is
+ * set, else from max_rows_per_token, else assume few -- never from the sizes of the caller's row
+ * buffers, which may be worst-case allocations.  Zero-initialise the struct before filling it in.
  */
 typedef struct {
   int32_t num_dest;
@@ -101,6 +110,8 @@ typedef struct {
   int32_t *load_expert;
   int32_t *load_rank;
   int32_t *load_node;
+  int32_t max_rows_per_token;
+  int64_t expected_rows;
 } hm_plan_out;
 
 /* Bytes of device scratch hm_plan needs for these sizes (0 on invalid arguments). */
@@ -124,10 +135,10 @@ hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int3
 
 /*
  * hm_plan_status -- waits for `hip_stream`, then returns the plan's device status word and
- * stores total_rows (= dest_offset[num_dest]) into *total_rows (host, may be NULL).
+ * stores total_rows (= dest_offset[num_dest]) into *total_rows (host, may be NULL) and into
+ * plan->expected_rows.
  */
-hm_status hm_plan_status(const hm_plan_out *plan /* host struct */, int64_t *total_rows /* host */,
-                         void *hip_stream);
+hm_status hm_plan_status(hm_plan_out *plan /* host struct */, int64_t *total_rows /* host */, void *hip_stream);
 
 /*
  * hm_plan_static -- hm_plan for callers that cannot allocate or pass a workspace: code recorded
@@ -163,9 +174,26 @@ hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, int32_t H, 
  * Slots that share a row are merged first (their weights are added in fp32, ascending k) so each
  * distinct row is read once.  y [y_rows,H] bf16, out [T,H] bf16.  Dropped slots and rows outside
  * [0,y_rows) contribute nothing (the latter flagged HM_ERR_CAPACITY).  Uses plan->slot_row, status.
+ * topk_weights may be NULL: the weights are then the ones hm_plan already merged, plan->row_weight
+ * (the same additions in the same order, so the same bits when the plan was built from these
+ * router weights -- the normal case), the first slot of a row is the one plan->slot_keep marks,
+ * and rows at or beyond plan->row_capacity count as outside y.  This is the faster form (no
+ * merge of the K slots in every wave); pass the weights only if they differ from the plan's.
+ * The same holds for hm_combine_f32 and hm_combine_mix.
  */
 hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
                      int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream);
+
+/*
+ * hm_combine_launch_shape -- host only, launches nothing: the shape hm_combine / hm_combine_f32 /
+ * hm_combine_mix would launch with for this plan on rows of H % 8 == 0 (H % 4 for fp32) elements:
+ * 16-byte vectors per lane, rows whose loads are in flight per wave, resident waves per CU the
+ * launch allows (32 = no cap).  weights_from_plan != 0 asks about the topk_weights == NULL form.
+ * For tests and tuning: it shows what plan->expected_rows / max_rows_per_token select.
+ */
+hm_status hm_combine_launch_shape(int32_t T, int32_t K, int32_t H, const hm_plan_out *plan, int32_t weights_from_plan,
+                                  int32_t *vectors_per_lane /* host */, int32_t *rows_in_flight /* host */,
+                                  int32_t *waves_per_cu /* host */);
 
 /*
  * hm_combine_f32 -- hm_combine for rows kept in binary32 (the element width is free in the paper:
@@ -372,18 +400,6 @@ hm_status hm_swap_select(int32_t d, const int32_t *U /* host */, int32_t G, int3
  * order makes the next hm_plan / hm_swap_counts on the same stream see the new placement.
  */
 hm_status hm_swap_apply(int32_t *expert_to_rank, int32_t E, const int32_t *best_pair, void *hip_stream);
-
-/*
- * hm_stream_probe -- a measurement aid, not part of the paper's method: a flat stream with
- * read_streams contiguous inputs and write_streams contiguous outputs of vectors_per_stream
- * 16-byte vectors each (src holds the inputs back to back, dst the outputs; both device, 16-byte
- * aligned; 1..16 streams each way), no indirection: every output vector is the XOR of the input
- * vectors at its index.  Launch shape, vector width and cache hints are those of the row kernels,
- * so its rate is what the memory system gives for the mix of hm_dispatch_pack (1 read, c writes)
- * or hm_combine (c reads, 1 write).
- */
-hm_status hm_stream_probe(const void *src, int32_t read_streams, void *dst, int32_t write_streams,
-                          int64_t vectors_per_stream, void *hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char *hm_status_string(hm_status s);

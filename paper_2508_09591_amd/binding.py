@@ -27,8 +27,8 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
            "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply",
-           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16", "hm_stream_probe",
-           "hm_plan_static", "hm_plan_static_max_bytes")
+           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16",
+           "hm_plan_static", "hm_plan_static_max_bytes", "hm_combine_launch_shape")
 
 
 class hm_topology(ctypes.Structure):
@@ -42,7 +42,8 @@ class hm_plan_out(ctypes.Structure):
                 ("slot_keep", ctypes.c_void_p), ("row_weight", ctypes.c_void_p),
                 ("rank_mask", ctypes.c_void_p), ("node_mask", ctypes.c_void_p),
                 ("status", ctypes.c_void_p), ("load_expert", ctypes.c_void_p),
-                ("load_rank", ctypes.c_void_p), ("load_node", ctypes.c_void_p)]
+                ("load_rank", ctypes.c_void_p), ("load_node", ctypes.c_void_p),
+                ("max_rows_per_token", ctypes.c_int32), ("expected_rows", ctypes.c_int64)]
 
 
 class HierMoEError(RuntimeError):
@@ -79,12 +80,13 @@ def lib():
         L.hm_dispatch_pack.argtypes = [vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, i64, vp]
         L.hm_combine.restype = ctypes.c_int
         L.hm_combine.argtypes = [vp, i64, vp, i32, i32, i32, ctypes.POINTER(hm_plan_out), vp, vp]
+        L.hm_combine_launch_shape.restype = ctypes.c_int
+        L.hm_combine_launch_shape.argtypes = [i32, i32, i32, ctypes.POINTER(hm_plan_out), i32, ctypes.POINTER(i32),
+                                              ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.hm_swap_multi_workspace_bytes.restype = ctypes.c_size_t
         L.hm_swap_multi_workspace_bytes.argtypes = [i32, i32, i32, vp]
         L.hm_swap_counts_multi.restype = ctypes.c_int
         L.hm_swap_counts_multi.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
-        L.hm_stream_probe.restype = ctypes.c_int
-        L.hm_stream_probe.argtypes = [vp, i32, vp, i32, i64, vp]
         L.hm_swap_apply.restype = ctypes.c_int
         L.hm_swap_apply.argtypes = [vp, i32, vp, vp]
         L.hm_combine_f32.restype = ctypes.c_int
@@ -218,12 +220,26 @@ def alloc_plan(T: int, K: int, E: int, nodes: int, ranks_per_node: int, level: i
     return Plan(T=T, K=K, level=level, num_dest=Dn, row_capacity=int(row_capacity), c=c, **bufs)
 
 
+def _adopt_table(plan: Plan, T: int, K: int, weights: torch.Tensor):
+    """A plan's buffers may be reused for another routing table if they are large enough; the
+    plan then describes that table (the row calls check their tensors against plan.T / plan.K)."""
+    if weights.numel() != T * K:
+        raise ValueError("weights hold %d values for %d x %d slots" % (weights.numel(), T, K))
+    if T * K > plan.slot_row.numel() or T * K > plan.slot_keep.numel():
+        raise ValueError("plan buffers hold %d slots, the table has %d x %d" % (plan.slot_row.numel(), T, K))
+    for m in (plan.rank_mask, plan.node_mask):
+        if m is not None and T > m.numel():
+            raise ValueError("plan mask buffers hold %d tokens, the table has %d" % (m.numel(), T))
+    plan.T, plan.K = T, K
+
+
 def hm_plan(topk_ids: torch.Tensor, topk_weights: torch.Tensor, expert_to_rank: torch.Tensor,
             nodes: int, ranks_per_node: int, level: int, plan: Optional[Plan] = None, stream=None) -> Plan:
     T, K = topk_ids.shape
     E = expert_to_rank.shape[0]
     if plan is None:
         plan = alloc_plan(T, K, E, nodes, ranks_per_node, level, device=topk_ids.device)
+    _adopt_table(plan, T, K, topk_weights)
     rc = lib().hm_plan(_dev(topk_ids, torch.int32, "topk_ids"), _dev(topk_weights, torch.float32, "topk_weights"),
                        _dev(expert_to_rank, torch.int32, "expert_to_rank"), T, K, E,
                        hm_topology(nodes, ranks_per_node), level, plan.ref(),
@@ -239,6 +255,7 @@ def hm_plan_static(topk_ids: torch.Tensor, topk_weights: torch.Tensor, expert_to
     (alloc_plan); the call itself allocates nothing."""
     T, K = topk_ids.shape
     E = expert_to_rank.shape[0]
+    _adopt_table(plan, T, K, topk_weights)
     rc = lib().hm_plan_static(_dev(topk_ids, torch.int32, "topk_ids"), _dev(topk_weights, torch.float32, "topk_weights"),
                               _dev(expert_to_rank, torch.int32, "expert_to_rank"), T, K, E,
                               hm_topology(nodes, ranks_per_node), level, plan.ref(), _stream(stream))
@@ -254,32 +271,55 @@ def hm_plan_status(plan: Plan, stream=None):
     return int(rc), int(total.value)
 
 
+def _rows_call_shape(plan: Plan, tokens: int, weights: Optional[torch.Tensor], what: str):
+    """The C calls take T and K beside the plan and trust them: a tensor with more tokens than the
+    plan was built for would make the kernels read the slot tables past their end."""
+    if tokens != plan.T:
+        raise ValueError("%s has %d rows but the plan was built for %d tokens" % (what, tokens, plan.T))
+    if weights is not None and weights.numel() != plan.T * plan.K:
+        raise ValueError("weights hold %d values, the plan has %d x %d slots" % (weights.numel(), plan.T, plan.K))
+
+
 def hm_dispatch_pack(x: torch.Tensor, plan: Plan, packed: torch.Tensor, stream=None) -> torch.Tensor:
     T, H = x.shape
+    _rows_call_shape(plan, T, None, "x")
     rc = lib().hm_dispatch_pack(_dev(x, torch.bfloat16, "x"), T, plan.K, H, plan.ref(),
                                 _dev(packed, torch.bfloat16, "packed"), packed.shape[0], _stream(stream))
     _check("hm_dispatch_pack", rc)
     return packed
 
 
-def hm_combine(y: torch.Tensor, topk_weights: torch.Tensor, plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
+def hm_combine(y: torch.Tensor, topk_weights: Optional[torch.Tensor], plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """topk_weights None: the weights the plan merged (plan.row_weight) are used, the faster form."""
     T, H = out.shape
+    _rows_call_shape(plan, T, topk_weights, "out")
     rc = lib().hm_combine(_dev(y, torch.bfloat16, "y"), y.shape[0], _dev(topk_weights, torch.float32, "topk_weights"),
                           T, plan.K, H, plan.ref(), _dev(out, torch.bfloat16, "out"), _stream(stream))
     _check("hm_combine", rc)
     return out
 
 
-def hm_combine_f32(y: torch.Tensor, topk_weights: torch.Tensor, plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
+def hm_combine_f32(y: torch.Tensor, topk_weights: Optional[torch.Tensor], plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
     T, H = out.shape
+    _rows_call_shape(plan, T, topk_weights, "out")
     rc = lib().hm_combine_f32(_dev(y, torch.float32, "y"), y.shape[0], _dev(topk_weights, torch.float32, "topk_weights"),
                               T, plan.K, H, plan.ref(), _dev(out, torch.float32, "out"), _stream(stream))
     _check("hm_combine_f32", rc)
     return out
 
 
+def hm_combine_launch_shape(plan: Plan, H: int, weights_from_plan: bool = True):
+    """(16-byte vectors per lane, rows in flight per wave, waves per CU) the combine calls would use."""
+    v, r, w = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib().hm_combine_launch_shape(plan.T, plan.K, H, plan.ref(), 1 if weights_from_plan else 0,
+                                       ctypes.byref(v), ctypes.byref(r), ctypes.byref(w))
+    _check("hm_combine_launch_shape", rc)
+    return int(v.value), int(r.value), int(w.value)
+
+
 def hm_combine_transpose(gout: torch.Tensor, plan: Plan, gy: torch.Tensor, stream=None) -> torch.Tensor:
     T, H = gout.shape
+    _rows_call_shape(plan, T, None, "gout")
     rc = lib().hm_combine_transpose(_dev(gout, torch.float32, "gout"), T, plan.K, H, plan.ref(),
                                     _dev(gy, torch.float32, "gy"), gy.shape[0], _stream(stream))
     _check("hm_combine_transpose", rc)
@@ -288,6 +328,7 @@ def hm_combine_transpose(gout: torch.Tensor, plan: Plan, gy: torch.Tensor, strea
 
 def hm_combine_transpose_bf16(gout: torch.Tensor, plan: Plan, gy: torch.Tensor, stream=None) -> torch.Tensor:
     T, H = gout.shape
+    _rows_call_shape(plan, T, None, "gout")
     rc = lib().hm_combine_transpose_bf16(_dev(gout, torch.bfloat16, "gout"), T, plan.K, H, plan.ref(),
                                          _dev(gy, torch.bfloat16, "gy"), gy.shape[0], _stream(stream))
     _check("hm_combine_transpose_bf16", rc)
@@ -325,6 +366,7 @@ def hm_plan_mapped(row_ids: torch.Tensor, row_weights: torch.Tensor, dest_map: t
     if plan is None:
         plan = alloc_plan(rows, K, E, 1, 1, HM_DEDUP_GPU if dedup else HM_DEDUP_NONE, device=dest_map.device,
                           num_dest=num_dest)
+    _adopt_table(plan, rows, K, row_weights)
     rc = lib().hm_plan_mapped(_dev(row_ids, torch.int32, "row_ids"), _dev(row_weights, torch.float32, "row_weights"),
                               _dev(dest_map, torch.int32, "dest_map"), rows, K, E, num_dest, 1 if dedup else 0,
                               plan.ref(), plan.workspace.data_ptr(), plan.workspace.numel() * 4, _stream(stream))
@@ -333,8 +375,9 @@ def hm_plan_mapped(row_ids: torch.Tensor, row_weights: torch.Tensor, dest_map: t
     return plan
 
 
-def hm_combine_mix(y: torch.Tensor, row_weights: torch.Tensor, plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
+def hm_combine_mix(y: torch.Tensor, row_weights: Optional[torch.Tensor], plan: Plan, out: torch.Tensor, stream=None) -> torch.Tensor:
     T, H = out.shape
+    _rows_call_shape(plan, T, row_weights, "out")
     rc = lib().hm_combine_mix(_dev(y, torch.bfloat16, "y"), y.shape[0], _dev(row_weights, torch.float32, "row_weights"),
                               T, plan.K, H, plan.ref(), _dev(out, torch.bfloat16, "out"), _stream(stream))
     _check("hm_combine_mix", rc)
@@ -424,19 +467,6 @@ def hm_swap_select(U, G: int, M: float, v: float, z_inter, z_intra: torch.Tensor
                               workspace.data_ptr(), workspace.numel() * 8, _stream(stream))
     _check("hm_swap_select", rc)
     return Q, best_pair, best_time
-
-
-def hm_stream_probe(src: torch.Tensor, read_streams: int, dst: torch.Tensor, write_streams: int, stream=None):
-    """src: [read_streams, n] and dst: [write_streams, n] of 16-byte vectors (any dtype, contiguous)."""
-    nbytes = src.numel() * src.element_size()
-    n = nbytes // (16 * read_streams)
-    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
-        raise TypeError("src and dst must be contiguous GPU tensors")
-    if nbytes != n * 16 * read_streams or dst.numel() * dst.element_size() != n * 16 * write_streams:
-        raise ValueError("src / dst sizes do not match the stream counts")
-    rc = lib().hm_stream_probe(src.data_ptr(), read_streams, dst.data_ptr(), write_streams, n, _stream(stream))
-    _check("hm_stream_probe", rc)
-    return dst
 
 
 def hm_swap_apply(expert_to_rank: torch.Tensor, best_pair: torch.Tensor, stream=None) -> torch.Tensor:

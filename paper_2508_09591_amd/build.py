@@ -10,6 +10,8 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhiermoe.so")
+PROBE_SRC = os.path.join(PKG, "bench_probe", "stream_probe.hip")   # bench.py's flat-stream reference, not product
+PROBE_LIB = os.path.join(PKG, "libhmprobe.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
@@ -31,13 +33,20 @@ def sources():
 
 
 def build_library(verbose: bool = False) -> str:
-    """Compile every csrc/*.hip into one shared object; always recompiles."""
+    """Compile every csrc/*.hip into libhiermoe.so, and the benchmark's flat-stream probe into a
+    library of its own; always recompiles."""
     tmp = LIB + ".tmp.%d" % os.getpid()
     cmd = [hipcc_path(), *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp, *sources()]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    tmp = PROBE_LIB + ".tmp.%d" % os.getpid()
+    cmd = [hipcc_path(), *HIPCC_FLAGS, "-o", tmp, PROBE_SRC]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE_LIB)
     return LIB
 
 

@@ -445,6 +445,7 @@ static hm_status plan_on_counts(const int32_t *topk_ids, const float *topk_weigh
   p.load_rank = out->load_rank;
   p.load_node = out->load_node;
   out->num_dest = p.Dn;
+  out->max_rows_per_token = level == HM_DEDUP_NONE ? K : (K < p.Dn ? K : p.Dn);
   return hm::launch_plan(p, (hipStream_t)hip_stream);
 }
 
@@ -565,6 +566,7 @@ extern "C" hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_wei
   p.status = out->status;
   p.load_expert = p.load_rank = p.load_node = nullptr;   // the fused loads need the rank placement
   out->num_dest = num_dest;
+  out->max_rows_per_token = 0;   // a hop table may leave most slots without a copy: no useful bound
 
   return hm::launch_plan(p, (hipStream_t)hip_stream);
 }
@@ -598,7 +600,7 @@ extern "C" hm_status hm_level_dest_map(const int32_t *expert_to_rank, int32_t E,
   return hm_launch_status();
 }
 
-extern "C" hm_status hm_plan_status(const hm_plan_out *plan, int64_t *total_rows, void *hip_stream) {
+extern "C" hm_status hm_plan_status(hm_plan_out *plan, int64_t *total_rows, void *hip_stream) {
   if (!plan || !plan->status || !plan->dest_offset) return HM_ERR_NULL;
   if (plan->num_dest < 1 || plan->num_dest > 64) return HM_ERR_SHAPE;
   hipStream_t stream = (hipStream_t)hip_stream;
@@ -610,6 +612,7 @@ extern "C" hm_status hm_plan_status(const hm_plan_out *plan, int64_t *total_rows
     return HM_ERR_HIP;
   if (hipStreamSynchronize(stream) != hipSuccess) return HM_ERR_HIP;
   if (total_rows) *total_rows = host[1];
+  plan->expected_rows = host[1];   // what the row kernels size their launches by
   return (hm_status)host[0];
 }
 

@@ -7,31 +7,40 @@
 // visit and readlane broadcasts each row index into a scalar register, so every global access
 // is a base + lane*16 B coalesced stream of 16-byte vectors.
 //
-// Dispatch and transpose use segments of 64 consecutive 16-byte vectors (1 KiB, one vector per
-// lane).  Work items this small matter on MI355X: a kernel here lasts well under 100 us, so with
-// multi-KiB items the last round of waves leaves most of the chip idle; 1 KiB items measured
-// 15-20 % faster than 7 KiB ones on the 14 KiB rows of the DeepSeek-V3 shape.  Combine, which is
-// read-heavy, did best with 4 KiB segments (4 vectors per lane) and the loads of up to four rows
-// issued before the first use; from about 32 Ki tokens of that shape on, the ramp-up and the
-// tail no longer matter and 7 KiB segments are faster (2.5 % at 32 Ki tokens, 5.5 % at 64 Ki;
-// 1.8 % slower at 8 Ki), so the launcher picks the width from the number of segments -- and the
-// rows in flight from the rows per token the caller's buffer implies: with about one row per token
-// (the local-expert stage of a receiver) four rows in flight are never used, and two do better.  Every row-sized stream is read and written with non-temporal
-// accesses: rows are touched once per kernel, and output lines left dirty in the caches were
-// measured to slow the next kernel down by about 10 %.
+// Segments are 64 consecutive 16-byte vectors (1 KiB, one vector per lane).  Work items this
+// small matter on MI355X: a kernel here lasts well under 100 us on the DeepSeek-V3 shape, so with
+// multi-KiB items the last round of waves leaves most of the chip idle.  Every row-sized stream
+// is read and written with non-temporal accesses: rows are touched once per kernel, and output
+// lines left dirty in the caches were measured to slow the next kernel down by about 10 %.
+//
+// Waves per CU are capped on purpose.  With every wave slot filled, a kernel that writes (or
+// reads) seven or eight 1 KiB pieces per wave has several hundred KiB per CU queued at the
+// memory system, and the rate drops (a flat 1-read + 7-write stream: 64 % of peak with 32 waves
+// per CU, 78 % with 8); with too few waves the index lookups are no longer hidden.  The cap is
+// set with an unused dynamic LDS allocation: dispatch and the fp32 transpose run 24 waves per CU
+// (-5 % on the 64 Ki-token layer at node level, -9 % at rank level, neutral elsewhere; the bf16
+// transpose does more arithmetic per byte and is faster uncapped); combine keeps about 128 KiB
+// of row loads in flight per CU (32 waves up to four rows per token, 16 at eight).
+//
+// Combine has two forms.  With the caller's weights (topk_weights != NULL) every wave merges the
+// K slots of its token itself (2K readlanes) and handles 4 KiB of the row, four rows in flight.
+// With the plan's merged weights (topk_weights == NULL) the first slot of each row is the one
+// slot_keep marks and its weight is one gathered load from row_weight, so the prologue is short
+// enough for 1 KiB segments with all of a token's rows (up to eight) in flight: 3-9 % faster.
 #include "hm_device.h"
+
+#include <atomic>
 
 namespace hm {
 
-constexpr int kElemThreads = 256;   // element-wise fallback kernels
-constexpr int kCopyThreads = 128;   // dispatch / transpose: 2 waves per workgroup
+constexpr int kElemThreads = 256;     // element-wise fallback kernels
+constexpr int kCopyThreads = 128;     // dispatch / transpose: two waves per workgroup ...
+constexpr int kCopyWavesPerCu = 24;   // ... and this many waves resident per CU (dispatch, fp32 transpose)
 constexpr int kCombineThreads = 256;
-constexpr int kCombineVecs = 4;     // combine: 16-byte vectors per lane (4 KiB segments) ...
-constexpr int kCombineVecsWide = 7; // ... or 7 KiB segments once the launch has this many of them:
-constexpr int64_t kCombineWideMinUnits = 65536;
-constexpr int kCombineRows = 4;     // combine: rows whose loads are in flight together ...
-constexpr int kCombineRowsFew = 2;  // ... or two, when the tokens have about one row each,
-constexpr int kCombineRowsMany = 8; // ... or eight, when they have six or more
+constexpr int kCombineVecs = 4;       // combine with the caller's weights: 16-byte vectors per lane (4 KiB segments),
+constexpr int kCombineRows = 4;       //   rows whose loads are in flight together
+constexpr int kCombineRowsPlan = 8;   // combine with the plan's weights: 1 KiB segments, up to eight rows in flight
+constexpr int kCombineBytesInFlight = 128 * 1024;   // per CU, what the cap on resident waves aims at
 
 struct RowParams {
   int32_t T, K;
@@ -298,32 +307,103 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
   }
 }
 
+// The same sum with the weights the plan merged: lane k < K holds slot k; the slot slot_keep marks
+// is the first of its row, and row_weight[row] is the fp32 sum, in ascending k, of the weights of
+// the slots that share the row -- the number merge_slots computes.  One 1 KiB segment per wave,
+// the loads of up to R rows issued before the first fma.
+template <bool MIX, int R, typename ROW>
+__global__ __launch_bounds__(kCombineThreads) void combine_plan_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
+                                                                            int64_t y_rows,
+                                                                            const float *__restrict__ row_weight,
+                                                                            u32x4 *__restrict__ out) {
+  int t, seg;
+  if (!unit_of_wave<kCombineThreads>(p, t, seg)) return;
+  const int lane = lane_id();
+  int my_row = -1;
+  float agg = 0.0f;
+  if (lane < p.K) {
+    const int64_t s = (int64_t)t * p.K + lane;
+    const int row = p.slot_row[s];
+    if (p.slot_keep[s] && row >= 0) {
+      if (row < y_rows) my_row = row;
+      else if (seg == 0) flag(p.status, HM_ERR_CAPACITY);
+    }
+  }
+  uint64_t todo = __ballot(my_row >= 0);
+  if (my_row >= 0) agg = row_weight[my_row];   // in flight together with the first rows
+  float inv_wsum = 0.0f;
+  if (MIX) {
+    float wsum = 0.0f;
+    for (uint64_t m = todo; m; m &= m - 1) wsum = wsum + read_lane(agg, __builtin_ctzll(m));
+    inv_wsum = wsum != 0.0f ? 1.0f / wsum : 0.0f;
+  }
+  const int v = seg * kWave + lane;
+  const bool in_row = v < p.nvec;
+  constexpr int E = ROW::kPerVec;
+  float acc[E];
+#pragma unroll
+  for (int e = 0; e < E; ++e) acc[e] = 0.0f;
+  while (todo) {
+    u32x4 r[R];
+    float a[R];
+    bool have[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+      have[j] = todo != 0;
+      a[j] = 0.0f;
+      r[j] = (u32x4){0u, 0u, 0u, 0u};
+      if (have[j]) {
+        const int k = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int row = read_lane(my_row, k);
+        a[j] = read_lane(agg, k);
+        if (in_row) r[j] = load_stream(y + (int64_t)row * p.nvec + v);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < R; ++j)
+      if (have[j]) ROW::fma_into(acc, a[j], r[j]);
+  }
+  if (in_row) {
+    if (MIX) {
+#pragma unroll
+      for (int e = 0; e < E; ++e) acc[e] = acc[e] * inv_wsum;
+    }
+    store_stream(out + (int64_t)t * p.nvec + v, ROW::pack(acc));
+  }
+}
+
 // Any H / alignment: one thread per (token, element); same merge order and the same fma chain
 // as the vector kernel, so both give identical bits.
 template <bool MIX, typename ROW>
 __global__ __launch_bounds__(kElemThreads) void combine_elems_kernel(RowParams p, int32_t H,
                                                                     const typename ROW::elem *__restrict__ y,
                                                                     int64_t y_rows, const float *__restrict__ topk_weights,
+                                                                    const float *__restrict__ row_weight,
                                                                     typename ROW::elem *__restrict__ out) {
   const int64_t i = (int64_t)blockIdx.x * kElemThreads + threadIdx.x;
   if (i >= (int64_t)p.T * H) return;
   const int t = (int)(i / H), j = (int)(i - (int64_t)t * H);
   const int32_t *rows = p.slot_row + (int64_t)t * p.K;
-  const float *w = topk_weights + (int64_t)t * p.K;
   float acc = 0.0f, wsum = 0.0f;
   for (int k = 0; k < p.K; ++k) {
     const int row = rows[k];
     if (row < 0) continue;
+    bool first = true;
+    for (int k1 = 0; k1 < k; ++k1) first = first && rows[k1] != row;
+    if (!first) continue;
     if (row >= y_rows) {
       if (j == 0) flag(p.status, HM_ERR_CAPACITY);
       continue;
     }
-    bool first = true;
-    for (int k1 = 0; k1 < k; ++k1) first = first && rows[k1] != row;
-    if (!first) continue;
     float agg = 0.0f;
-    for (int k1 = 0; k1 < p.K; ++k1)
-      if (rows[k1] == row) agg = agg + w[k1];
+    if (row_weight) {   // the plan's merged weight: the same additions in the same order
+      agg = row_weight[row];
+    } else {
+      const float *w = topk_weights + (int64_t)t * p.K;
+      for (int k1 = 0; k1 < p.K; ++k1)
+        if (rows[k1] == row) agg = agg + w[k1];
+    }
     acc = __builtin_fmaf(agg, ROW::widen(y[(int64_t)row * H + j]), acc);
     wsum = wsum + agg;
   }
@@ -412,6 +492,65 @@ static inline bool grid_for_elems(RowParams &p, int64_t n, dim3 &grid) {
   return true;
 }
 
+// Bytes of (unused) dynamic LDS per workgroup that leave room for `waves_per_cu` waves of
+// `block`-thread workgroups on a CU; 0 = no cap.  The CU's LDS size is read from the device once.
+static inline int lds_per_cu() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  int v = cached[dev].load(std::memory_order_relaxed);
+  if (v == 0) {
+    int bytes = 0;
+    if (hipDeviceGetAttribute(&bytes, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, dev) != hipSuccess) bytes = 0;
+    v = bytes >= 65536 ? bytes : -1;
+    cached[dev].store(v, std::memory_order_relaxed);
+  }
+  return v > 0 ? v : 0;
+}
+static inline unsigned lds_cap_bytes(int waves_per_cu, int block) {
+  const int per_cu = lds_per_cu();
+  const int blocks = waves_per_cu / (block / kWave);
+  if (per_cu == 0 || blocks < 1 || waves_per_cu >= 32) return 0;
+  const int bytes = (per_cu / blocks) & ~511;
+  return bytes > 65536 ? 65536u : (unsigned)bytes;
+}
+
+// Rows a token is expected to own: from the caller's (or hm_plan_status's) row count if there is
+// one, else from the bound hm_plan left in the struct, else unknown (0).
+static inline double rows_per_token(const hm_plan_out *plan, int32_t T) {
+  if (plan->expected_rows > 0 && T > 0) return (double)plan->expected_rows / (double)T;
+  if (plan->max_rows_per_token > 0) return (double)plan->max_rows_per_token;
+  return 0.0;
+}
+
+// Launch shape of the combine kernels: 16-byte vectors per lane, rows in flight per wave, and the
+// cap on resident waves per CU (32 = none).  Kept in one place so that the launcher and
+// hm_combine_launch_shape agree.
+struct CombineShape {
+  int vecs, rows, waves_per_cu;
+};
+static inline CombineShape combine_shape(const hm_plan_out *plan, int32_t T, bool weights_from_plan) {
+  CombineShape sh;
+  if (!weights_from_plan) {
+    sh.vecs = kCombineVecs;
+    sh.rows = kCombineRows;
+    sh.waves_per_cu = 32;
+    return sh;
+  }
+  sh.vecs = 1;
+  sh.rows = kCombineRowsPlan;
+  const double c = rows_per_token(plan, T);
+  int waves = 32;
+  if (c > 4.0) {   // c KiB of loads per wave: keep about kCombineBytesInFlight per CU
+    waves = (int)((double)kCombineBytesInFlight / (c * 1024.0));
+    waves &= ~3;   // whole workgroups of four waves
+    if (waves < 16) waves = 16;
+    if (waves > 32) waves = 32;
+  }
+  sh.waves_per_cu = waves;
+  return sh;
+}
+
 }  // namespace hm
 
 static hm_status check_rows_args(int32_t T, int32_t K, int32_t H, const hm_plan_out *plan, bool need_keep) {
@@ -441,8 +580,8 @@ extern "C" hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, 
   dim3 grid;
   if (H % 8 == 0 && aligned16(x_bf16) && aligned16(packed_bf16)) {
     if (!grid_for_units(p, H / 8, 1, kCopyThreads, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL(dispatch_rows_kernel, grid, dim3(kCopyThreads), 0, stream, p, (const u32x4 *)x_bf16,
-                       (u32x4 *)packed_bf16, packed_rows);
+    hipLaunchKernelGGL(dispatch_rows_kernel, grid, dim3(kCopyThreads), lds_cap_bytes(kCopyWavesPerCu, kCopyThreads),
+                       stream, p, (const u32x4 *)x_bf16, (u32x4 *)packed_bf16, packed_rows);
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
     hipLaunchKernelGGL(dispatch_elems_kernel, grid, dim3(kElemThreads), 0, stream, p, H, (const uint16_t *)x_bf16,
@@ -456,11 +595,13 @@ static hm_status launch_combine(const void *y, int64_t y_rows, const float *topk
                                 int32_t H, const hm_plan_out *plan, void *out, void *hip_stream) {
   using namespace hm;
   typedef typename ROW::elem elem;
-  hm_status st = check_rows_args(T, K, H, plan, false);
+  const bool from_plan = topk_weights == nullptr;   // merged weights and first-slot marks of the plan
+  hm_status st = check_rows_args(T, K, H, plan, from_plan);
   if (st != HM_OK) return st;
-  if (y_rows < 0) return HM_ERR_SHAPE;
+  if (from_plan && !plan->row_weight) return HM_ERR_NULL;
+  if (y_rows < 0 || (from_plan && plan->row_capacity < 0)) return HM_ERR_SHAPE;
   if (T == 0) return HM_OK;
-  if (!topk_weights || !out || (!y && y_rows > 0)) return HM_ERR_NULL;
+  if (!out || (!y && y_rows > 0)) return HM_ERR_NULL;
   hipStream_t stream = (hipStream_t)hip_stream;
   RowParams p;
   p.T = T;
@@ -471,34 +612,39 @@ static hm_status launch_combine(const void *y, int64_t y_rows, const float *topk
   dim3 grid;
   if (H % ROW::kPerVec == 0 && aligned16(y) && aligned16(out)) {
     const int nvec = H / ROW::kPerVec;
-    const int64_t wide_units = (int64_t)T * ((nvec + kWave * kCombineVecsWide - 1) / (kWave * kCombineVecsWide));
-    if (y_rows < 2 * (int64_t)T) {
-      // about one row per token (the local-expert stage of a receiver): four rows in flight are
-      // never used, two leave room for more waves (0.31 -> 0.28 ms on that stage)
-      if (!grid_for_units(p, nvec, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
-      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, kCombineRowsFew, ROW>), grid, dim3(kCombineThreads), 0,
-                         stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
-    } else if (y_rows >= 6 * (int64_t)T && nvec >= 512) {
-      // six or more rows per token (no or rank-level dedup) on long rows: all of a token's rows in
-      // flight at once (1.45 -> 1.30 ms on the 64 Ki-token layer, 3-4 % at 8 Ki tokens)
-      if (!grid_for_units(p, nvec, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
-      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, kCombineRowsMany, ROW>), grid, dim3(kCombineThreads), 0,
-                         stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
-    } else if (wide_units >= kCombineWideMinUnits) {
-      if (!grid_for_units(p, nvec, kCombineVecsWide, kCombineThreads, grid)) return HM_ERR_SHAPE;
-      hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecsWide, kCombineRows, ROW>), grid, dim3(kCombineThreads), 0,
-                         stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
+    const CombineShape sh = combine_shape(plan, T, from_plan);
+    if (!grid_for_units(p, nvec, sh.vecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
+    if (from_plan) {
+      // rows the plan's weight array does not cover are treated like rows beyond y
+      const int64_t rows = y_rows < plan->row_capacity ? y_rows : plan->row_capacity;
+      hipLaunchKernelGGL((combine_plan_rows_kernel<MIX, kCombineRowsPlan, ROW>), grid, dim3(kCombineThreads),
+                         lds_cap_bytes(sh.waves_per_cu, kCombineThreads), stream, p, (const u32x4 *)y, rows,
+                         plan->row_weight, (u32x4 *)out);
     } else {
-      if (!grid_for_units(p, nvec, kCombineVecs, kCombineThreads, grid)) return HM_ERR_SHAPE;
       hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, kCombineRows, ROW>), grid, dim3(kCombineThreads), 0,
                          stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);
     }
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;
+    // the element-wise kernel finds the first slot of each row itself and takes the row's merged
+    // weight from the plan when the caller passed none
     hipLaunchKernelGGL((combine_elems_kernel<MIX, ROW>), grid, dim3(kElemThreads), 0, stream, p, H, (const elem *)y,
-                       y_rows, topk_weights, (elem *)out);
+                       from_plan && plan->row_capacity < y_rows ? plan->row_capacity : y_rows, topk_weights,
+                       from_plan ? plan->row_weight : nullptr, (elem *)out);
   }
   return hm_launch_status();
+}
+
+extern "C" hm_status hm_combine_launch_shape(int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
+                                             int32_t weights_from_plan, int32_t *vectors_per_lane,
+                                             int32_t *rows_in_flight, int32_t *waves_per_cu) {
+  hm_status st = check_rows_args(T, K, H, plan, false);
+  if (st != HM_OK) return st;
+  const hm::CombineShape sh = hm::combine_shape(plan, T, weights_from_plan != 0);
+  if (vectors_per_lane) *vectors_per_lane = sh.vecs;
+  if (rows_in_flight) *rows_in_flight = sh.rows;
+  if (waves_per_cu) *waves_per_cu = sh.waves_per_cu;
+  return HM_OK;
 }
 
 extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
@@ -537,7 +683,8 @@ static hm_status launch_transpose(const void *gout, int32_t T, int32_t K, int32_
   dim3 grid;
   if (H % ROW::kPerVec == 0 && aligned16(gout) && aligned16(gy)) {
     if (!grid_for_units(p, H / ROW::kPerVec, 1, kCopyThreads, grid)) return HM_ERR_SHAPE;
-    hipLaunchKernelGGL((transpose_rows_kernel<ROW>), grid, dim3(kCopyThreads), 0, stream, p, (const u32x4 *)gout,
+    const unsigned lds = ROW::kPerVec == 4 ? lds_cap_bytes(kCopyWavesPerCu, kCopyThreads) : 0u;   // fp32 rows only
+    hipLaunchKernelGGL((transpose_rows_kernel<ROW>), grid, dim3(kCopyThreads), lds, stream, p, (const u32x4 *)gout,
                        plan->row_weight, plan->row_capacity, (u32x4 *)gy, gy_rows);
   } else {
     if (!grid_for_elems(p, (int64_t)T * H, grid)) return HM_ERR_SHAPE;

@@ -61,3 +61,16 @@ def assert_plan_equal(gpu: GpuPlan, ora, ctx=""):
         assert np.array_equal(h[f], getattr(ora, f)), (ctx, f)
     # weights: compare encodings, not values
     assert np.array_equal(h["row_weight"].view(np.uint32), ora.row_weight.view(np.uint32)), (ctx, "row_weight")
+
+
+def combine_forms(fn, y, weights, plan, out, stream=None):
+    """Run a combine entry point (hm_combine, hm_combine_f32, hm_combine_mix) in both of its
+    forms -- with the caller's weights, and with the weights the plan merged (weights = NULL) --
+    and require the same bits from both; `out` holds the result."""
+    fn(y, weights, plan, out)
+    other = torch.full_like(out, float("nan"))
+    fn(y, None, plan, other)
+    if plan.row_capacity >= y.shape[0]:      # rows past the plan's weight array count as outside y
+        a, b = out.contiguous().view(torch.uint8).cpu().numpy(), other.contiguous().view(torch.uint8).cpu().numpy()
+        assert np.array_equal(a, b), "the two forms of %s disagree" % fn.__name__
+    return out

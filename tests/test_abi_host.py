@@ -117,10 +117,17 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_dispatch_pack(fake, 4, 2, 0, ref, fake, 8, None) == B.HM_ERR_SHAPE
     assert L.hm_dispatch_pack(fake, 4, 2, 64, ref, fake, -1, None) == B.HM_ERR_SHAPE
     assert L.hm_dispatch_pack(fake, 0, 2, 64, ref, fake, 8, None) == B.HM_OK          # nothing to do
-    assert L.hm_combine(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
+    # weights = NULL selects the plan's merged weights: the plan must then carry row_weight and slot_keep
+    no_rw = _plan_struct(B)
+    no_rw.row_weight = None
+    no_keep = _plan_struct(B)
+    no_keep.slot_keep = None
+    assert L.hm_combine(fake, 8, None, 4, 2, 64, ctypes.byref(no_rw), fake, None) == B.HM_ERR_NULL
+    assert L.hm_combine(fake, 8, None, 4, 2, 64, ctypes.byref(no_keep), fake, None) == B.HM_ERR_NULL
+    assert L.hm_combine(fake, 8, fake, 4, 2, 64, ctypes.byref(no_keep), None, None) == B.HM_ERR_NULL   # out missing
     assert L.hm_combine(fake, 8, fake, 4, 0, 64, ref, fake, None) == B.HM_ERR_SHAPE
     assert L.hm_combine(fake, 8, fake, 4, 2, 64, ref, None, None) == B.HM_ERR_NULL
-    assert L.hm_combine_f32(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
+    assert L.hm_combine_f32(fake, 8, None, 4, 2, 64, ctypes.byref(no_rw), fake, None) == B.HM_ERR_NULL
     assert L.hm_combine_f32(fake, -2, fake, 4, 2, 64, ref, fake, None) == B.HM_ERR_SHAPE
     assert L.hm_combine_f32(fake, 8, fake, 0, 2, 64, ref, fake, None) == B.HM_OK          # T = 0: nothing to do
     assert L.hm_combine_transpose(None, 4, 2, 64, ref, fake, 8, None) == B.HM_ERR_NULL
@@ -149,7 +156,7 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert mapped(nd=0) == B.HM_ERR_TOPOLOGY
     assert mapped(nd=65) == B.HM_ERR_TOPOLOGY
     assert mapped(ws_bytes=4) == B.HM_ERR_WORKSPACE
-    assert L.hm_combine_mix(fake, 8, None, 4, 2, 64, ref, fake, None) == B.HM_ERR_NULL
+    assert L.hm_combine_mix(fake, 8, None, 4, 2, 64, ctypes.byref(no_rw), fake, None) == B.HM_ERR_NULL
     assert L.hm_combine_mix(fake, -1, fake, 4, 2, 64, ref, fake, None) == B.HM_ERR_SHAPE
 
     assert L.hm_level_dest_map(fake, 8, 8, 0, 2, 3, fake, fake, None) == B.HM_ERR_TOPOLOGY      # 2 does not divide 3
@@ -193,15 +200,60 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 4, 2, None, zz, None, fake, big, None) == B.HM_ERR_NULL
     zn2 = (ctypes.c_void_p * 2)(fake, None)
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 4, 2, ng2, zn2, None, fake, big, None) == B.HM_ERR_NULL
-    assert L.hm_stream_probe(None, 1, fake, 1, 64, None) == B.HM_ERR_NULL
-    assert L.hm_stream_probe(fake, 0, fake, 1, 64, None) == B.HM_ERR_SHAPE
-    assert L.hm_stream_probe(fake, 1, fake, 17, 64, None) == B.HM_ERR_SHAPE
-    assert L.hm_stream_probe(fake, 1, ctypes.c_void_p(0x1008), 1, 64, None) == B.HM_ERR_SHAPE      # misaligned
-    assert L.hm_stream_probe(fake, 1, fake, 1, 0, None) == B.HM_OK
     assert L.hm_swap_apply(None, 8, fake, None) == B.HM_ERR_NULL
     assert L.hm_swap_apply(fake, 8, None, None) == B.HM_ERR_NULL
     assert L.hm_swap_apply(fake, 0, fake, None) == B.HM_ERR_SHAPE
     assert L.hm_swap_select(1, i32x(1), 4, 8, 1.0, 1.0, None, None, None, 1.0, None, None, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
+
+
+def test_combine_launch_shape_follows_the_plan_not_the_buffers(B):
+    """The row kernels size their launches from what the plan struct says about rows per token
+    (expected_rows, else the bound hm_plan left), never from the caller's buffer sizes -- which is
+    why the query takes no buffer size at all.  Host logic only: nothing is launched."""
+    L = B.lib()
+    T, K, H = 8192, 8, 7168
+
+    def shape(bound, expected, from_plan=1, tokens=T):
+        c = _plan_struct(B)
+        c.max_rows_per_token = bound
+        c.expected_rows = expected
+        v, r, w = ctypes.c_int32(-1), ctypes.c_int32(-1), ctypes.c_int32(-1)
+        rc = L.hm_combine_launch_shape(tokens, K, H, ctypes.byref(c), from_plan, ctypes.byref(v), ctypes.byref(r), ctypes.byref(w))
+        assert rc == B.HM_OK
+        return v.value, r.value, w.value
+
+    assert shape(4, 0) == (1, 8, 32)                    # node level on 4 nodes: at most 4 rows per token
+    assert shape(8, 0) == (1, 8, 16)                    # rank level / no dedup, K = 8: eight 1 KiB loads per wave
+    assert shape(0, 0) == (1, 8, 32)                    # a mapped plan that was never synchronised: unknown, assume few
+    assert shape(8, int(1.16 * T)) == (1, 8, 32)        # the count wins over the bound (local-expert stage of a receiver)
+    assert shape(0, int(6.0 * T)) == (1, 8, 20)         # 128 KiB / 6 KiB = 21 waves -> whole workgroups of four
+    assert shape(4, int(7.49 * T)) == (1, 8, 16)
+    assert shape(8, 64 * T) == (1, 8, 16)               # never below 16 waves per CU
+    assert shape(8, int(7.49 * T), from_plan=0) == (4, 4, 32)   # caller's weights: the merging kernel, no cap
+    assert shape(8, 0, tokens=0) == (1, 8, 16)
+    assert L.hm_combine_launch_shape(T, K, H, None, 1, None, None, None) == B.HM_ERR_NULL
+    assert L.hm_combine_launch_shape(T, 0, H, ctypes.byref(_plan_struct(B)), 1, None, None, None) == B.HM_ERR_SHAPE
+
+
+def test_binding_checks_tensors_against_the_plan(B):
+    """The C calls take T and K beside the plan; the binding refuses tensors that do not match
+    the table the plan was built for before anything reaches the library."""
+    import torch
+    from types import SimpleNamespace
+    plan = SimpleNamespace(T=16, K=2)
+    B._rows_call_shape(plan, 16, torch.zeros(32), "x")
+    with pytest.raises(ValueError):
+        B._rows_call_shape(plan, 17, None, "x")
+    with pytest.raises(ValueError):
+        B._rows_call_shape(plan, 16, torch.zeros(33), "x")
+    small = SimpleNamespace(T=4, K=2, slot_row=torch.zeros(8), slot_keep=torch.zeros(8), rank_mask=torch.zeros(4),
+                            node_mask=None)
+    B._adopt_table(small, 3, 2, torch.zeros(6))
+    assert (small.T, small.K) == (3, 2)
+    with pytest.raises(ValueError):
+        B._adopt_table(small, 5, 2, torch.zeros(10))      # more slots than the buffers hold
+    with pytest.raises(ValueError):
+        B._adopt_table(small, 4, 2, torch.zeros(7))       # weights do not match the table
 
 
 def test_binding_refuses_cpu_tensors(B):

@@ -56,7 +56,7 @@ def _run_layer(hw, oracle, wl, T, H, level, e2r=None, check_transpose=False, exp
     y = packed_ref if model == "identity" else _scaled_y(oracle, wl, r, ora, packed_ref)
     y_d = hw.to_dev_bf16(y) if model != "identity" else packed_d[:ora.total_rows]
     out_d = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
-    B.hm_combine(y_d, g.w_d, g.plan, out_d)
+    hw.combine_forms(B.hm_combine, y_d, g.w_d, g.plan, out_d)
     out = hw.bf16_to_host(out_d)
     out_ref = oracle.combine(y, r.topk_weights, ora.slot_row)
     dist = bf16_ulp_distance(out, out_ref)
@@ -166,7 +166,7 @@ def test_full_size_stress_sampled(hw, oracle):
         packed_d.view(torch.int16).fill_(0x7FC1)
         B.hm_dispatch_pack(x_d, g.plan, packed_d)
         out_d = torch.empty((wl.T, wl.H), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine(packed_d, g.w_d, g.plan, out_d)
+        hw.combine_forms(B.hm_combine, packed_d, g.w_d, g.plan, out_d)
         gy_d = torch.empty((n, wl.H), dtype=torch.float32, device="cuda")
         B.hm_combine_transpose(gout_d, g.plan, gy_d)
         # whole-buffer property: identity experts and weights summing to 1 -> the layer is the identity
@@ -231,7 +231,7 @@ def test_edge_shapes(hw, oracle, T, K, E, nodes, rpn, H):
         assert np.array_equal(hw.bf16_to_host(packed_d[:n]), oracle.dispatch_pack(x, ora.row_token)), ctx
         y = W.f32_to_bf16_bits(rng.random((max(n, 1), H)).astype(np.float32) + np.float32(0.5))[:n]  # same-sign terms
         out_d = torch.zeros((max(T, 1), H), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine(hw.to_dev_bf16(y) if n else packed_d[:0], g.w_d, g.plan, out_d[:T])
+        hw.combine_forms(B.hm_combine, hw.to_dev_bf16(y) if n else packed_d[:0], g.w_d, g.plan, out_d[:T])
         ref = oracle.combine(y, w, ora.slot_row) if T else np.zeros((0, H), np.uint16)
         assert T == 0 or bf16_ulp_distance(hw.bf16_to_host(out_d[:T]), ref).max() <= 1, ctx
         gy_d = torch.zeros((max(n, 1), H), dtype=torch.float32, device="cuda")
@@ -271,8 +271,8 @@ def test_vector_and_elementwise_kernels_agree_on_misaligned_views(hw, oracle):
     oa = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
     ob_store = torch.zeros(T * H + 1, dtype=torch.bfloat16, device="cuda")
     ob = ob_store[1:].view(T, H)
-    B.hm_combine(a, g.w_d, g.plan, oa)
-    B.hm_combine(b, g.w_d, g.plan, ob)
+    hw.combine_forms(B.hm_combine, a, g.w_d, g.plan, oa)
+    hw.combine_forms(B.hm_combine, b, g.w_d, g.plan, ob)
     assert torch.equal(oa.view(torch.int16), ob.contiguous().view(torch.int16))
     assert bf16_ulp_distance(hw.bf16_to_host(oa), x).max() == 0
 
@@ -300,7 +300,7 @@ def test_bad_ids_and_small_buffers_are_flagged_not_faulted(hw, oracle):
         B.hm_dispatch_pack(hw.to_dev_bf16(x), g.plan, packed_d)
         assert np.array_equal(hw.bf16_to_host(packed_d), oracle.dispatch_pack(x, ora.row_token))
         out_d = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine(packed_d, g.w_d, g.plan, out_d)
+        hw.combine_forms(B.hm_combine, packed_d, g.w_d, g.plan, out_d)
         ref = oracle.combine(hw.bf16_to_host(packed_d), w, ora.slot_row)
         assert bf16_ulp_distance(hw.bf16_to_host(out_d), ref).max() <= 1
         le, lr, ln, st = oracle.expert_load(ids, e2r, nodes, rpn)
@@ -354,7 +354,7 @@ def test_dropped_slots_on_the_gpu(hw, oracle):
         packed = hw.bf16_to_host(packed_d)
         assert np.array_equal(packed, oracle.dispatch_pack(x, ora.row_token))
         out_d = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine(packed_d, g.w_d, g.plan, out_d)
+        hw.combine_forms(B.hm_combine, packed_d, g.w_d, g.plan, out_d)
         out = hw.bf16_to_host(out_d)
         assert bf16_ulp_distance(out, oracle.combine(packed, w, ora.slot_row)).max() <= 1
         assert not out[11].any()
@@ -492,7 +492,7 @@ def test_random_shapes_against_the_oracle(hw, oracle):
         packed = hw.bf16_to_host(packed_d[:n])
         assert np.array_equal(packed, oracle.dispatch_pack(x, ora.row_token)), ctx
         out_d = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine(packed_d[:n], g.w_d, g.plan, out_d)
+        hw.combine_forms(B.hm_combine, packed_d[:n], g.w_d, g.plan, out_d)
         assert bf16_ulp_distance(hw.bf16_to_host(out_d), oracle.combine(packed, w, ora.slot_row)).max() <= 1, ctx
         gout = rng.standard_normal((T, H)).astype(np.float32)
         gy_d = torch.zeros((max(n, 1), H), dtype=torch.float32, device="cuda")
@@ -543,7 +543,7 @@ def test_combine_on_binary32_rows(hw, oracle, name, T, H):
         g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
         y = rng.standard_normal((ora.total_rows, H)).astype(np.float32)
         out_d = torch.full((T, H), float("nan"), dtype=torch.float32, device="cuda")
-        B.hm_combine_f32(hw.dev(y), g.w_d, g.plan, out_d)
+        hw.combine_forms(B.hm_combine_f32, hw.dev(y), g.w_d, g.plan, out_d)
         got = out_d.cpu().numpy()
         ref = oracle.combine_f32(y, r.topk_weights, ora.slot_row)
         mag = np.einsum("tk,tkh->th", np.abs(r.topk_weights).astype(np.float64), np.abs(y).astype(np.float64)[ora.slot_row])
@@ -554,7 +554,7 @@ def test_combine_on_binary32_rows(hw, oracle, name, T, H):
         assert st == 0
     # a row index beyond the caller's buffer is skipped and flagged, as in hm_combine
     out_d.fill_(float("nan"))
-    B.hm_combine_f32(hw.dev(y)[:ora.total_rows - 3], g.w_d, g.plan, out_d)
+    hw.combine_forms(B.hm_combine_f32, hw.dev(y)[:ora.total_rows - 3], g.w_d, g.plan, out_d)
     st, _ = B.hm_plan_status(g.plan)
     assert st == B.HM_ERR_CAPACITY and not torch.isnan(out_d).any()
 
@@ -613,7 +613,7 @@ def test_combine_with_cancelling_terms(hw, oracle):
         g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
         y = W.f32_to_bf16_bits(rng.standard_normal((ora.total_rows, H)).astype(np.float32))
         out_d = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine(hw.to_dev_bf16(y), g.w_d, g.plan, out_d)
+        hw.combine_forms(B.hm_combine, hw.to_dev_bf16(y), g.w_d, g.plan, out_d)
         got = hw.bf16_to_host(out_d)
         ref = oracle.combine(y, r.topk_weights, ora.slot_row)
         dist = bf16_ulp_distance(got, ref)
@@ -631,14 +631,17 @@ def test_combine_with_cancelling_terms(hw, oracle):
 
 
 def test_stream_probe_moves_what_it_says(hw):
-    """The measurement aid: every output stream is the XOR of the input streams, ragged tail included."""
+    """The benchmark's measurement aid (a library of its own, not part of the product): every
+    output stream is the XOR of the input streams, ragged tail included, for every launch shape."""
     import torch
-    from paper_2508_09591_amd import binding as B
+    import bench
     rng = np.random.default_rng(3)
-    for nr, nw, n in ((1, 1, 64), (1, 3, 1000), (3, 1, 4097), (7, 2, 130), (16, 16, 65)):
+    shapes = [(64, 32), (128, 20), (256, 8), (64, 5), (256, 32)]
+    for i, (nr, nw, n) in enumerate(((1, 1, 64), (1, 3, 1000), (3, 1, 4097), (7, 2, 130), (16, 16, 65))):
         src = rng.integers(-2 ** 31, 2 ** 31 - 1, (nr, n, 4), dtype=np.int64).astype(np.int32)
         dst_d = torch.full((nw, n, 4), 77, dtype=torch.int32, device="cuda")
-        B.hm_stream_probe(hw.dev(src), nr, dst_d, nw)
+        block, waves = shapes[i]
+        bench.stream_probe(hw.dev(src), nr, dst_d, nw, block, waves)
         want = np.bitwise_xor.reduce(src, axis=0)
         got = dst_d.cpu().numpy()
         for j in range(nw):
@@ -672,7 +675,7 @@ def test_step_under_hip_graph_capture(hw, oracle):
     def step():
         B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level, plan=plan)
         B.hm_dispatch_pack(x_d, plan, packed_d)
-        B.hm_combine(packed_d, w_d, plan, out_d)
+        B.hm_combine(packed_d, None, plan, out_d)           # the plan's merged weights: the form a step uses
         B.hm_combine_transpose(gout_d, plan, gy_d)
 
     side = torch.cuda.Stream()

@@ -129,7 +129,7 @@ def test_combine_mix_parity(hw, oracle, rows, K, H):
         y = W.f32_to_bf16_bits((rng.random((max(total, 1), H)) + 0.5).astype(np.float32))[:total]
         out_d = torch.full((rows, H), float("nan"), dtype=torch.bfloat16, device="cuda")
         y_d = hw.to_dev_bf16(y) if total else torch.zeros((0, H), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine_mix(y_d, w_d, plan, out_d)
+        hw.combine_forms(B.hm_combine_mix, y_d, w_d, plan, out_d)
         ref = oracle.combine_mix(y, w, ora.slot_row)
         got = hw.bf16_to_host(out_d)
         dist = bf16_ulp_distance(got, ref)
@@ -138,7 +138,7 @@ def test_combine_mix_parity(hw, oracle, rows, K, H):
         empty = (ora.slot_row < 0).all(axis=1)
         assert empty.any() and not got[empty].any()      # rows without a valid slot give zeros
         # the unnormalised merge on the same plan still matches hm_combine's oracle
-        B.hm_combine(y_d, w_d, plan, out_d)
+        hw.combine_forms(B.hm_combine, y_d, w_d, plan, out_d)
         assert bf16_ulp_distance(hw.bf16_to_host(out_d), oracle.combine(y, w, ora.slot_row)).max() <= 1
 
 
@@ -220,17 +220,17 @@ def test_hierarchical_layer_stage_by_stage(hw, oracle, name, T, H, src_local):
                 s3 = slice(o3.dest_offset[j], o3.dest_offset[j + 1])
                 yexp[s3] = W.f32_to_bf16_bits(c[e] * W.bf16_bits_to_f32(xin[s3]))
             out3_d = torch.zeros((b2 - a2, H), dtype=torch.bfloat16, device="cuda")
-            B.hm_combine_mix(hw.to_dev_bf16(yexp), w3_d, plan3, out3_d)
+            hw.combine_forms(B.hm_combine_mix, hw.to_dev_bf16(yexp), w3_d, plan3, out3_d)
             assert bf16_ulp_distance(hw.bf16_to_host(out3_d), oracle.combine_mix(yexp, h_w2, o3.slot_row)).max() <= 1
             y2_d[a2:b2] = out3_d
         # ---- merge on the receiving rank before the rows go back to the source ----
         out2_d = torch.zeros((b1 - a1, H), dtype=torch.bfloat16, device="cuda")
-        B.hm_combine_mix(y2_d, hw.dev(h_w1), plan2, out2_d)
+        hw.combine_forms(B.hm_combine_mix, y2_d, hw.dev(h_w1), plan2, out2_d)
         assert bf16_ulp_distance(hw.bf16_to_host(out2_d), oracle.combine_mix(hw.bf16_to_host(y2_d), h_w1, o2.slot_row)).max() <= 1
         y1_d[a1:b1] = out2_d
     # ---- final combine at the source ----
     out_d = torch.zeros((T, H), dtype=torch.bfloat16, device="cuda")
-    B.hm_combine(y1_d, g1.w_d, g1.plan, out_d)
+    hw.combine_forms(B.hm_combine, y1_d, g1.w_d, g1.plan, out_d)
     out = hw.bf16_to_host(out_d)
     assert bf16_ulp_distance(out, oracle.combine(hw.bf16_to_host(y1_d), w, o1.slot_row)).max() <= 1
     expect = (w.astype(np.float64) * c[ids].astype(np.float64)).sum(1)[:, None] * W.bf16_bits_to_f64(x)
@@ -322,17 +322,17 @@ def test_d_dimensional_exchange_hop_by_hop(hw, oracle, name, chain, T, H):
                     s3 = slice(o3.dest_offset[jj], o3.dest_offset[jj + 1])
                     yexp[s3] = W.f32_to_bf16_bits(c[e] * W.bf16_bits_to_f32(xin[s3]))
                 res_d = torch.zeros((b - a, H), dtype=torch.bfloat16, device="cuda")
-                B.hm_combine_mix(hw.to_dev_bf16(yexp), w3_d, plan3, res_d)
+                hw.combine_forms(B.hm_combine_mix, hw.to_dev_bf16(yexp), w3_d, plan3, res_d)
                 assert bf16_ulp_distance(hw.bf16_to_host(res_d), oracle.combine_mix(yexp, h2w, o3.slot_row)).max() <= 1
                 y_d[a:b] = res_d
             else:
                 y_d[a:b] = hop(level + 1, peer, sub_tokens, sub_rows, sub_ids, sub_w)
         out_d = torch.zeros((n, H), dtype=torch.bfloat16, device="cuda")
         if level == 0:
-            B.hm_combine(y_d, w_d, plan, out_d)
+            hw.combine_forms(B.hm_combine, y_d, w_d, plan, out_d)
             ref = oracle.combine(hw.bf16_to_host(y_d), h_w, ora.slot_row)
         else:
-            B.hm_combine_mix(y_d, w_d, plan, out_d)
+            hw.combine_forms(B.hm_combine_mix, y_d, w_d, plan, out_d)
             ref = oracle.combine_mix(hw.bf16_to_host(y_d), h_w, ora.slot_row)
         assert bf16_ulp_distance(hw.bf16_to_host(out_d), ref).max() <= 1
         return out_d
