@@ -5,19 +5,32 @@
 //     dest_offset[d] + (kept slots of d in earlier workgroups) + (in earlier waves of this
 //     workgroup) + (in lower lanes of this wave),
 // and the last term is a popcount over a wavefront ballot.  No atomics decide positions, so the
-// plan is deterministic and stable.  Two launches:
-//   plan_count_kernel  per-workgroup, per-destination counts of kept slots -> workspace
-//   plan_write_kernel  every workgroup re-reads the (small) count matrix to get its own base
-//                      rows and the destination totals, then writes the index maps.
-// Re-reading the matrix costs workgroups^2 * destinations loads in total, so beyond
-// kPlanScanMinEntries entries a third launch in between (plan_scan_kernel, one workgroup per
-// destination) turns the matrix into exclusive prefixes plus a row of totals and the write
-// kernel reads just its own row: linear in the number of slots at any size.
-// Both first stage the rank and destination of their 1024 slots, plus a halo of K-1 slots on
-// either side (the rest of the first and last token), in LDS: each expert id is looked up once
-// and all "same destination as an earlier / later slot of my token" questions become LDS reads.
+// plan is deterministic and stable.  A workgroup first stages the rank and destination of its
+// 1024 slots, plus a halo of K-1 slots on either side (the rest of the first and last token), in
+// LDS: each expert id is looked up once and all "same destination as an earlier / later slot of
+// my token" questions become LDS reads.
+//
+// Every workgroup needs the counts of all the others (the destination totals give dest_offset),
+// so the plan has a grid-wide dependency in the middle.  Two ways through it:
+//   * plans of at most 256 workgroups (262,144 slots) run as ONE launch, plan_fused_kernel: the
+//     workgroups publish their counts, meet at a grid barrier and go on to write the maps from
+//     what they staged.  At these sizes the work is a few microseconds and a second launch (its
+//     gap, and staging everything again) cost more than the kernels themselves.  All workgroups
+//     are resident together (the launcher checks the device's capacity), the barrier spins on
+//     per-workgroup flags holding a value unique to the launch, so the caller's workspace needs
+//     no initialisation, and every wait is bounded: a wave that gives up flags HM_ERR_HIP and
+//     exits.
+//   * larger plans take separate launches: plan_count_kernel (per-workgroup counts ->
+//     workspace), plan_scan_kernel once the matrix has kPlanScanMinEntries entries (one
+//     workgroup per destination turns it into exclusive prefixes plus a row of totals; below
+//     that every workgroup of the write kernel re-reads the small matrix itself), and
+//     plan_write_kernel.  Linear in the number of slots at any size.
 #include "hm_device.h"
 
+#include <unistd.h>
+
+#include <atomic>
+#include <chrono>
 #include <mutex>
 
 namespace hm {
@@ -28,6 +41,9 @@ constexpr int kPlanHalo = 63;                              // K - 1 <= 63
 constexpr int kPlanStaged = kPlanThreads + 2 * kPlanHalo;
 constexpr int kPlanHist = 8192;                            // experts histogrammed in LDS for the fused loads
 constexpr int64_t kPlanScanMinEntries = 16384;             // count-matrix entries from which the scan launch pays
+constexpr int kPlanFusedMaxBlocks = 256;                   // largest plan (in workgroups) the one-launch kernel takes
+constexpr int kPlanSpinLimit = 1 << 18;                    // polls of the grid barrier before a wave gives up
+constexpr int kPlanStagedExperts = 4096;                   // one-launch kernel: largest expert table staged in LDS
 
 struct PlanParams {
   const int32_t *ids;
@@ -178,7 +194,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   __shared__ int32_t block_base[kWave];             // first row of this workgroup per destination
   __shared__ uint64_t ballots[kPlanWaves][kWave];   // [wave][destination] -> lanes that keep a slot
   __shared__ int32_t wave_base[kPlanWaves][kWave];  // kept slots in earlier waves of the workgroup
-  __shared__ int32_t hist[kPlanHist];               // fused expert load: slots per expert
+  extern __shared__ int32_t hist[];                 // fused expert load: slots per expert (E entries, only if asked for)
   __shared__ int32_t blk_rank[kWave], blk_node[kWave];
   __shared__ float s_weight[kPlanStaged];           // router weights of the staged slots
   const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
@@ -320,6 +336,337 @@ __global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) 
   if ((int)threadIdx.x < nodes && blk_node[threadIdx.x]) atomicAdd(&p.load_node[threadIdx.x], blk_node[threadIdx.x]);
 }
 
+// ---- one-launch plan ---------------------------------------------------------------------------
+// Words that another workgroup of the same launch reads or writes are accessed with device-scope
+// atomic loads and stores (the workgroups sit on different dies with caches of their own).
+__device__ __forceinline__ void st_device(int32_t *a, int32_t v) {
+  __hip_atomic_store(a, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t ld_device(const uint64_t *a) {
+  return __hip_atomic_load(a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_device(uint64_t *a, uint64_t v) {
+  __hip_atomic_store(a, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// The calling wave's earlier device-scope stores have been acknowledged when this returns.
+__device__ __forceinline__ void wait_for_own_stores() { __asm__ volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+constexpr int kTagShift = 11;   // a workgroup keeps at most 1024 slots per destination: the count takes 11 bits
+
+// Rank (or hop-table destination) of an expert id from the table staged in LDS; the codes of
+// stage_and_classify: -1 invalid, -2 no copy at this hop / slot dropped by the router.
+__device__ __forceinline__ int lookup_staged(const PlanParams &p, const int8_t *s_map, int id) {
+  if (id == -1) return -2;
+  if ((unsigned)id >= (unsigned)p.E) return -1;
+  return s_map[id];
+}
+// The same from global memory, for tables too large to stage.
+__device__ __forceinline__ int lookup_global(const PlanParams &p, int id) {
+  if (p.dest_map) {
+    if (id == -1) return -2;
+    if ((unsigned)id >= (unsigned)p.E) return -1;
+    const int v = p.dest_map[id];
+    return (v >= 0 && v < p.Dn) ? v : (v == -1 ? -2 : -1);
+  }
+  return rank_of(p.expert_to_rank, p.E, p.G, id);
+}
+
+// The grid-wide step without a separate barrier: a workgroup publishes its per-destination
+// counts as 64-bit words (launch tag << 11 | count), one atomic store each, and every workgroup
+// reads the whole matrix, waiting on each word until it carries the tag of this launch -- the
+// count and its "ready" flag arrive in one word, so no fence orders them.  The tag is 53 bits
+// of a value unique to the launch, so what an uninitialised workspace holds cannot pass for it.
+// passed[b] is set once workgroup b has read the matrix; workgroup 0 finally waits for all of
+// passed and zeroes matrix and flags, so a replay of a captured launch (same tag) starts clean.
+// Every wait is bounded by kPlanSpinLimit polls; a wave that gives up makes the workgroup skip
+// its writes, flags HM_ERR_HIP and exits.
+//
+// The kernel is a chain of dependent memory round trips, so it is ordered to keep that chain
+// short: the expert -> rank table is staged in LDS while the ids are in flight (no dependent
+// lookup, and the division by ranks_per_node is done once per expert, not per slot), the halo
+// slots are fetched in the same round as the workgroup's own, and everything that does not need
+// the other workgroups' counts -- slot_keep, the masks, the LDS partials of the load counts --
+// is done while the counts are on their way.
+__global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, uint64_t *matrix, uint64_t *passed,
+                                                                  uint64_t tag, int staged_table) {
+  __shared__ int8_t s_rank[kPlanStaged];
+  __shared__ int8_t s_node[kPlanStaged];
+  __shared__ int8_t s_dest[kPlanStaged];
+  __shared__ float s_weight[kPlanStaged];
+  __shared__ uint64_t ballots[kPlanWaves][kWave];
+  __shared__ int32_t wave_base[kPlanWaves][kWave];
+  __shared__ int32_t part_tot[kPlanWaves][kWave];
+  __shared__ int32_t part_pre[kPlanWaves][kWave];
+  __shared__ int32_t block_base[kWave];
+  __shared__ int32_t blk_rank[kWave], blk_node[kWave];
+  __shared__ int32_t gave_up;
+  extern __shared__ int32_t dyn_lds[];   // if staged_table: [hist: E int32 if the load arrays are asked for][rank: E int8][node: E int8]
+  const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
+  const int bid = (int)blockIdx.x;
+  const bool loads = p.load_expert != nullptr;
+  int32_t *hist = dyn_lds;
+  int8_t *s_map = (int8_t *)(dyn_lds + (loads ? p.E : 0));
+  int8_t *s_nmap = s_map + p.E;
+  const int halo = p.K - 1;
+  const int first = bid * kPlanThreads;   // slot indices fit 31 bits
+
+  // ---- phase 1a: everything that comes from memory, issued in one round
+  const int s = first + (int)threadIdx.x;                     // own slot, LDS entry halo + threadIdx.x
+  const bool has2 = (int)threadIdx.x < 2 * halo;              // a halo slot as well:
+  const int i2 = (int)threadIdx.x < halo ? (int)threadIdx.x : kPlanThreads + (int)threadIdx.x;   // its LDS entry
+  const int64_t s2 = (int64_t)first - halo + i2;
+  const bool live = s < p.nslots, live2 = has2 && s2 >= 0 && s2 < p.nslots;
+  int id = -1, id2 = -1;
+  float w = 0.0f, w2 = 0.0f;
+  if (live) {
+    id = p.ids[s];
+    w = p.weights[s];
+  }
+  if (live2) {
+    id2 = p.ids[s2];
+    w2 = p.weights[s2];
+  }
+  if (staged_table) {
+    for (int e = threadIdx.x; e < p.E; e += kPlanThreads) {
+      int v, n = -1;
+      if (p.dest_map) {
+        const int m = p.dest_map[e];
+        v = (m >= 0 && m < p.Dn) ? m : (m == -1 ? -2 : -1);
+      } else {
+        const int g = p.expert_to_rank[e];
+        v = ((unsigned)g >= (unsigned)p.G) ? -1 : g;
+        if (v >= 0) n = v / p.R;
+      }
+      s_map[e] = (int8_t)v;
+      s_nmap[e] = (int8_t)n;
+    }
+    if (loads)
+      for (int e = threadIdx.x; e < p.E; e += kPlanThreads) hist[e] = 0;
+  }
+  if (threadIdx.x < kWave) blk_rank[threadIdx.x] = blk_node[threadIdx.x] = 0;
+  if (threadIdx.x == 0) gave_up = 0;
+  if (bid == 0) {   // what the atomics of the other workgroups add to: out before this workgroup's counts are
+    if (threadIdx.x == 0) st_device(p.status, 0);
+    if (loads) {
+      for (int i = threadIdx.x; i < p.E; i += kPlanThreads) st_device(p.load_expert + i, 0);
+      if ((int)threadIdx.x < p.G) st_device(p.load_rank + threadIdx.x, 0);
+      if ((int)threadIdx.x < p.G / p.R) st_device(p.load_node + threadIdx.x, 0);
+    }
+    wait_for_own_stores();
+  }
+  __syncthreads();
+
+  // ---- phase 1b: ranks, nodes and destinations of the staged slots into LDS
+  {
+    int r = -1, n = -1;
+    if (live) {
+      if (staged_table) {
+        r = lookup_staged(p, s_map, id);
+        if (r >= 0) n = s_nmap[id];
+      } else {
+        r = lookup_global(p, id);
+        if (r >= 0 && !p.dest_map) n = r / p.R;
+      }
+    }
+    const int own = halo + (int)threadIdx.x;
+    s_rank[own] = (int8_t)r;
+    s_node[own] = (int8_t)n;
+    s_dest[own] = (int8_t)(r < 0 ? -1 : (p.level == HM_DEDUP_NODE && !p.dest_map ? n : r));
+    s_weight[own] = w;
+    if (has2) {
+      int r2 = -1, n2 = -1;
+      if (live2) {
+        if (staged_table) {
+          r2 = lookup_staged(p, s_map, id2);
+          if (r2 >= 0) n2 = s_nmap[id2];
+        } else {
+          r2 = lookup_global(p, id2);
+          if (r2 >= 0 && !p.dest_map) n2 = r2 / p.R;
+        }
+      }
+      s_rank[i2] = (int8_t)r2;
+      s_node[i2] = (int8_t)n2;
+      s_dest[i2] = (int8_t)(r2 < 0 ? -1 : (p.level == HM_DEDUP_NODE && !p.dest_map ? n2 : r2));
+      s_weight[i2] = w2;
+    }
+  }
+  __syncthreads();
+  Slot me;
+  me.live = live;
+  me.t = me.k = me.tok0 = 0;
+  me.rank = me.dest = -1;
+  me.keep = false;
+  if (live) {
+    me.t = (int)((unsigned)s / (unsigned)p.K);
+    me.k = s - me.t * p.K;
+    const int own = halo + (int)threadIdx.x;
+    me.tok0 = own - me.k;
+    me.rank = s_rank[own];
+    me.dest = s_dest[own];
+    me.keep = me.dest >= 0;
+    if (me.keep && p.level != HM_DEDUP_NONE)
+      for (int k1 = 0; k1 < me.k; ++k1)
+        if (s_dest[me.tok0 + k1] == me.dest) me.keep = false;
+  }
+  const int kept_dest = me.keep ? me.dest : -1;
+  for (int d = 0; d < p.Dn; ++d) {
+    const uint64_t b = __ballot(kept_dest == d);
+    if (lane == d) ballots[wv][d] = b;
+  }
+  __syncthreads();
+  if (lane < p.Dn) {
+    int a = 0;
+    for (int w1 = 0; w1 < wv; ++w1) a += __popcll(ballots[w1][lane]);
+    wave_base[wv][lane] = a;
+    if (wv == kPlanWaves - 1)   // the last wave's base plus its own count is the workgroup's count
+      st_device(matrix + (int64_t)bid * p.Dn + lane, (tag << kTagShift) | (uint64_t)(a + __popcll(ballots[wv][lane])));
+  }
+
+  // ---- while the counts travel: what needs no other workgroup
+  uint64_t rm = 0;
+  uint32_t nm = 0;
+  if (me.live) {
+    if (me.dest < 0) {
+      p.slot_row[s] = -1;
+      p.slot_keep[s] = 0;
+    } else {
+      p.slot_keep[s] = me.keep ? 1 : 0;
+    }
+    if (me.k == 0 && (p.rank_mask || p.node_mask || loads)) {   // per-token masks, owned by the token's slot 0
+      for (int k2 = 0; k2 < p.K; ++k2) {
+        const int r2 = s_rank[me.tok0 + k2];
+        if (r2 >= 0) {
+          rm |= 1ull << r2;
+          if (!p.dest_map) nm |= 1u << s_node[me.tok0 + k2];
+        }
+      }
+      if (p.rank_mask) p.rank_mask[me.t] = rm;
+      if (p.node_mask) p.node_mask[me.t] = nm;
+    }
+  }
+  if (loads) {   // LDS partials of the counts of hm_expert_load (a ballot per group; lane g keeps group g)
+    if (me.live && me.rank >= 0 && staged_table) atomicAdd(&hist[id], 1);
+    int my_rank_cnt = 0, my_node_cnt = 0;
+    const int nodes = p.G / p.R;
+    for (int g = 0; g < p.G; ++g) {
+      const uint64_t b = __ballot((rm >> g) & 1ull);
+      if (lane == g) my_rank_cnt = __popcll(b);
+    }
+    for (int n = 0; n < nodes; ++n) {
+      const uint64_t b = __ballot((nm >> n) & 1u);
+      if (lane == n) my_node_cnt = __popcll(b);
+    }
+    if (my_rank_cnt) atomicAdd(&blk_rank[lane], my_rank_cnt);
+    if (my_node_cnt) atomicAdd(&blk_node[lane], my_node_cnt);
+  }
+
+  // ---- the count matrix: wave wv reads rows wv, wv+16, ..., lane = destination, and reads them
+  // again, as a whole wave, until every word carries this launch's tag
+  {
+    int tot = 0, pre = 0;
+    bool ready = false;
+    for (int spin = 0; spin < kPlanSpinLimit; ++spin) {
+      tot = pre = 0;
+      bool mine = true;
+      if (lane < p.Dn) {
+        for (int b = wv; b < p.nblocks; b += kPlanWaves) {
+          const uint64_t v = ld_device(matrix + (int64_t)b * p.Dn + lane);
+          mine = mine && (v >> kTagShift) == tag;
+          const int c = (int)(v & ((1u << kTagShift) - 1u));
+          tot += c;
+          if (b < bid) pre += c;
+        }
+      }
+      ready = __ballot(!mine) == 0ull;
+      if (ready) break;
+      __builtin_amdgcn_s_sleep(2);
+    }
+    part_tot[wv][lane] = tot;
+    part_pre[wv][lane] = pre;
+    if (!ready && lane == 0) gave_up = 1;
+  }
+  __syncthreads();
+  const bool go = gave_up == 0;   // uniform over the workgroup
+  if (go) {
+    if (threadIdx.x == 0) st_device(passed + bid, tag);
+    if (loads) {   // global atomics first: they complete in the shadow of the map stores
+      const int nodes = p.G / p.R;
+      if (staged_table) {
+        for (int e = threadIdx.x; e < p.E; e += kPlanThreads)
+          if (hist[e]) atomicAdd(&p.load_expert[e], hist[e]);
+      } else if (me.live && me.rank >= 0) {
+        atomicAdd(&p.load_expert[id], 1);
+      }
+      if ((int)threadIdx.x < p.G && blk_rank[threadIdx.x]) atomicAdd(&p.load_rank[threadIdx.x], blk_rank[threadIdx.x]);
+      if ((int)threadIdx.x < nodes && blk_node[threadIdx.x]) atomicAdd(&p.load_node[threadIdx.x], blk_node[threadIdx.x]);
+    }
+    if (me.live && me.rank == -1) flag(p.status, HM_ERR_BAD_ID);
+    if (wv == 0) {
+      int tot = 0, pre = 0;
+      if (lane < p.Dn)
+        for (int w1 = 0; w1 < kPlanWaves; ++w1) {
+          tot += part_tot[w1][lane];
+          pre += part_pre[w1][lane];
+        }
+      int incl = tot;  // inclusive scan over destinations (lanes >= Dn hold 0)
+      for (int off = 1; off < kWave; off <<= 1) {
+        const int v = __shfl_up(incl, off, kWave);
+        if (lane >= off) incl += v;
+      }
+      const int offset = incl - tot;
+      block_base[lane] = offset + pre;
+      if (bid == 0 && lane < p.Dn) {
+        p.dest_count[lane] = tot;
+        p.dest_offset[lane] = offset;
+        if (lane == p.Dn - 1) p.dest_offset[p.Dn] = incl;
+      }
+    }
+  } else if (threadIdx.x == 0) {
+    flag(p.status, HM_ERR_HIP);
+  }
+  __syncthreads();
+
+  // ---- rows: the slot that owns a row numbers it and serves the later slots that share it
+  if (go && me.live && me.keep) {
+    const uint64_t b = ballots[wv][me.dest];
+    const int pos = __popcll(b & ((1ull << lane) - 1ull));
+    const int row = block_base[me.dest] + wave_base[wv][me.dest] + pos;
+    p.slot_row[s] = row;
+    float wsum = s_weight[me.tok0 + me.k];
+    if (p.level != HM_DEDUP_NONE) {
+      for (int k2 = me.k + 1; k2 < p.K; ++k2) {
+        if (s_dest[me.tok0 + k2] == me.dest) {
+          p.slot_row[s + (k2 - me.k)] = row;
+          wsum = wsum + s_weight[me.tok0 + k2];  // ascending k, fp32
+        }
+      }
+    }
+    if (row < p.row_capacity) {
+      p.row_token[row] = me.t;
+      p.row_weight[row] = wsum;
+    } else {
+      flag(p.status, HM_ERR_CAPACITY);
+    }
+  }
+
+  // ---- workgroup 0 leaves matrix and flags clean (also when a wait gave up: the status word says so)
+  if (bid == 0) {
+    if (wv == 0 && go) {
+      bool ok = true;
+      for (int spin = 0; spin < kPlanSpinLimit; ++spin) {
+        ok = true;
+        for (int b = lane; b < p.nblocks; b += kWave) ok = ok && ld_device(passed + b) == tag;
+        if (__ballot(!ok) == 0ull) break;
+        __builtin_amdgcn_s_sleep(2);
+      }
+      if (__ballot(!ok) != 0ull && lane == 0) flag(p.status, HM_ERR_HIP);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < p.nblocks * p.Dn; i += kPlanThreads) st_device(matrix + i, 0ull);
+    for (int b = threadIdx.x; b < p.nblocks; b += kPlanThreads) st_device(passed + b, 0ull);
+  }
+}
+
 // Table of one hop for a (parent, child) pair of group cuts: purely elementwise.
 __global__ __launch_bounds__(kPlanThreads) void level_dest_map_kernel(const int32_t *__restrict__ expert_to_rank, int E,
                                                                        int G, int my_rank, int ranks_per_parent,
@@ -385,12 +732,69 @@ static inline int32_t plan_blocks(int64_t nslots) {
   return (int32_t)(b < 1 ? 1 : b);
 }
 
+// Workspace: the count matrix [workgroups + 1][Dn] int32 of the multi-launch kernels, then
+// (8-byte aligned) what the one-launch kernel uses instead: a matrix of [workgroups][Dn] tagged
+// 64-bit words and one 64-bit flag per workgroup.
+static inline size_t plan_counts_bytes(int64_t nslots, int Dn) {
+  const size_t b = ((size_t)plan_blocks(nslots) + 1) * (size_t)Dn * sizeof(int32_t);
+  return (b + 7) & ~(size_t)7;
+}
 static inline size_t plan_workspace(int64_t nslots, int Dn) {
-  return ((size_t)plan_blocks(nslots) + 1) * (size_t)Dn * sizeof(int32_t);
+  const int32_t nb = plan_blocks(nslots);
+  const size_t fused = nb <= kPlanFusedMaxBlocks ? ((size_t)nb * (size_t)Dn + (size_t)nb) * sizeof(uint64_t) : 0;
+  return plan_counts_bytes(nslots, Dn) + fused;
 }
 
-// count -> (scan) -> write on `stream`; p.nblocks, p.Dn and p.counts are set.
+// Workgroups of plan_fused_kernel that can be resident together on the current device (0 if that
+// cannot be established: the multi-launch path is always available).
+static inline int fused_capacity() {
+  static std::atomic<int> cached[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  int v = cached[dev].load(std::memory_order_relaxed);
+  if (v == 0) {
+    int cus = 0, per_cu = 0;
+    v = -1;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, plan_fused_kernel, kPlanThreads,
+                                                     kPlanStagedExperts * 6) == hipSuccess &&
+        cus > 0 && per_cu > 0)
+      v = cus * per_cu;
+    cached[dev].store(v, std::memory_order_relaxed);
+  }
+  return v > 0 ? v : 0;
+}
+
+// 53 bits no earlier launch of this process has used and stale memory is unlikely to hold; never 0.
+static inline uint64_t next_tag() {
+  static std::atomic<uint64_t> counter{0};
+  static std::once_flag seeded;
+  std::call_once(seeded, [] {
+    uint64_t z = (uint64_t)std::chrono::steady_clock::now().time_since_epoch().count() ^ ((uint64_t)getpid() << 40);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    counter.store(z ^ (z >> 31), std::memory_order_relaxed);
+  });
+  const uint64_t mask = (1ull << 53) - 1ull;
+  uint64_t e = (counter.fetch_add(1, std::memory_order_relaxed) + 1) & mask;
+  if (e == 0) e = (counter.fetch_add(1, std::memory_order_relaxed) + 1) & mask;
+  return e;
+}
+
+// One launch when the plan is small enough, else count -> (scan) -> write, on `stream`;
+// p.nblocks, p.Dn and p.counts are set.
 static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
+  const bool loads = p.load_expert != nullptr;
+  const unsigned hist_bytes = loads && p.E <= kPlanHist ? (unsigned)p.E * sizeof(int32_t) : 0u;
+  if (p.nblocks <= kPlanFusedMaxBlocks && p.nblocks <= fused_capacity()) {
+    p.scanned = 0;
+    const int staged = p.E <= kPlanStagedExperts ? 1 : 0;   // tables (and histogram) in LDS
+    const unsigned lds = staged ? ((loads ? (unsigned)p.E * sizeof(int32_t) : 0u) + ((2u * (unsigned)p.E + 15u) & ~15u)) : 0u;
+    uint64_t *matrix = (uint64_t *)((char *)p.counts + plan_counts_bytes(p.nslots, p.Dn));
+    hipLaunchKernelGGL(plan_fused_kernel, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, matrix,
+                       matrix + (size_t)p.nblocks * p.Dn, next_tag(), staged);
+    return hm_launch_status();
+  }
   p.scanned = (int64_t)p.nblocks * p.Dn >= kPlanScanMinEntries ? 1 : 0;
   hipLaunchKernelGGL(plan_count_kernel, dim3(p.nblocks), dim3(kPlanThreads), 0, stream, p);
   if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
@@ -398,7 +802,7 @@ static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
     hipLaunchKernelGGL(plan_scan_kernel, dim3(p.Dn), dim3(kPlanThreads), 0, stream, p);
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   }
-  hipLaunchKernelGGL(plan_write_kernel, dim3(p.nblocks), dim3(kPlanThreads), 0, stream, p);
+  hipLaunchKernelGGL(plan_write_kernel, dim3(p.nblocks), dim3(kPlanThreads), hist_bytes, stream, p);
   return hm_launch_status();
 }
 

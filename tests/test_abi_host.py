@@ -38,10 +38,21 @@ def test_status_strings(B):
     assert B.status_string(-99) == "unknown status"
 
 
+def _workspace(workgroups, dests):
+    """Count matrix [workgroups + 1][dests] int32, padded to 8 bytes, then, for plans the one-launch
+    kernel takes (at most 256 workgroups of 1024 slots), its matrix of 8-byte words and one
+    8-byte flag per workgroup."""
+    counts = ((workgroups + 1) * dests * 4 + 7) // 8 * 8
+    return counts + (8 * (workgroups * dests + workgroups) if workgroups <= 256 else 0)
+
+
 def test_workspace_query(B):
-    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_NODE) == (64 + 1) * 4 * 4
-    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_GPU) == (64 + 1) * 32 * 4
-    assert B.hm_plan_workspace_bytes(0, 8, 256, 4, 8, B.HM_DEDUP_GPU) == (1 + 1) * 32 * 4
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_NODE) == _workspace(64, 4)
+    assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, B.HM_DEDUP_GPU) == _workspace(64, 32)
+    assert B.hm_plan_workspace_bytes(0, 8, 256, 4, 8, B.HM_DEDUP_GPU) == _workspace(1, 32)
+    assert B.hm_plan_workspace_bytes(8191, 3, 256, 1, 3, B.HM_DEDUP_GPU) == _workspace(24, 3)   # odd entry count: padded
+    assert B.hm_plan_workspace_bytes(32768, 8, 256, 8, 8, B.HM_DEDUP_GPU) == _workspace(256, 64)
+    assert B.hm_plan_workspace_bytes(32769, 8, 256, 8, 8, B.HM_DEDUP_GPU) == _workspace(257, 64)  # several launches: no flags
     assert B.hm_plan_workspace_bytes(8192, 8, 256, 9, 8, B.HM_DEDUP_GPU) == 0      # 72 ranks
     assert B.hm_plan_workspace_bytes(8192, 65, 256, 4, 8, B.HM_DEDUP_GPU) == 0     # K too large
     assert B.hm_plan_workspace_bytes(8192, 8, 256, 4, 8, 3) == 0                   # bad level
@@ -144,7 +155,7 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_recv_dest_map(fake, 0, topo, 0, 0, fake, fake, None) == B.HM_ERR_SHAPE
     assert L.hm_recv_dest_map(fake, 8, topo, 4, 0, fake, fake, None) == B.HM_ERR_TOPOLOGY     # rank 4 of 4
     assert L.hm_recv_dest_map(fake, 8, topo, 0, 2, fake, fake, None) == B.HM_ERR_LEVEL
-    assert L.hm_plan_mapped_workspace_bytes(8192, 8, 8) == (64 + 1) * 8 * 4
+    assert L.hm_plan_mapped_workspace_bytes(8192, 8, 8) == _workspace(64, 8)
     assert L.hm_plan_mapped_workspace_bytes(8192, 8, 65) == 0
 
     def mapped(ids=fake, w=fake, dm=fake, rows=4, K=2, E=8, nd=4, out=ref, ws=fake, ws_bytes=1 << 20):
