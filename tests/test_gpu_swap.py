@@ -207,3 +207,54 @@ def test_planner_loop_stays_on_the_device(hw, oracle):
     for pr in ((3, 3), (-1, 2), (0, E)):
         B.hm_swap_apply(e2r_d, hw.dev(np.array(pr, np.int32)))
     assert torch.equal(e2r_d, before)
+
+
+def test_swap_select_hand_cases_on_the_device(hw):
+    """Eq.(8)-(11) on the device against numbers worked out by hand and against numpy -- a pin on
+    the device formulas that does not pass through the oracle."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    E, G = 3, 2
+    Z = np.zeros((E, E, G), np.int32)
+    Z[:] = [4, 4]
+    Z[0, 1] = Z[1, 0] = [5, 2]
+    Z[0, 2] = Z[2, 0] = [3, 3]
+    Zd = hw.dev(Z)
+
+    def select(U, M, v, z_inter, z_intra, si, s_intra, ai, bi, aa, ba, gamma):
+        n = z_intra.shape[0]
+        Q = torch.full((n, n), float("nan"), dtype=torch.float64, device="cuda")
+        bp = torch.full((2,), -1, dtype=torch.int32, device="cuda")
+        bt = torch.zeros(1, dtype=torch.float64, device="cuda")
+        B.hm_swap_select(U, G if n == 3 else wl.G, M, v, z_inter, z_intra, si, s_intra, ai, bi, aa, ba, gamma, Q, bp, bt)
+        return Q.cpu().numpy(), tuple(int(x) for x in bp.cpu().numpy()), float(bt.item())
+
+    # one dimension, plain maximum: Q = alpha + G * max(Z[r,c,:]) * M v * beta
+    Q, best, bt = select([1], 2.0, 1.0, [None], Zd, [0], 1.0, [0], [0], 10.0, 0.5, 0.0)
+    assert Q[0, 1] == 10 + 2 * 5 * 2 * 0.5 and Q[0, 2] == 10 + 2 * 3 * 2 * 0.5 and Q[1, 1] == 10 + 2 * 4 * 2 * 0.5
+    assert best == (0, 2) and bt == 16.0                           # first minimiser in row-major order
+    # smooth maximum of Eq.(11): n equal entries m -> m * n^(1/gamma); dominated entries vanish as gamma grows
+    Q10, _, _ = select([1], 1.0, 1.0, [None], Zd, [0], 1.0, [0], [0], 0.0, 1.0, 10.0)
+    assert abs(Q10[1, 1] - G * 4 * 2 ** 0.1) < 1e-12
+    assert abs(Q10[0, 1] - G * 5 * (1 + 0.4 ** 10) ** 0.1) < 1e-12
+    Qbig, _, _ = select([1], 1.0, 1.0, [None], Zd, [0], 1.0, [0], [0], 0.0, 1.0, 400.0)
+    assert abs(Qbig[0, 1] - G * 5) < 1e-9
+    # two dimensions on a real routing table, gamma = 10 (the paper's default), against numpy
+    wl = W.WORKLOADS["skew"]
+    r = W.make_routing(wl, T=256)
+    e2r = r.extras["expert_to_rank_swapped"]
+    Zn_d, Zg_d = _gpu_z(hw, r.topk_ids, e2r, wl.G, wl.nodes)[0], _gpu_z(hw, r.topk_ids, e2r, wl.G, wl.G)[0]
+    Zn, Zg = Zn_d.cpu().numpy(), Zg_d.cpu().numpy()
+    U, M, v, gamma = [1, wl.nodes], 2048.0, 2.0, 10.0
+    ai, bi, aa, ba = [0, 0.497], [0, 5.29e-7], 0.571, 1.27e-7
+    Q, best, bt = select(U, M, v, [None, Zn_d], Zg_d, [0, 1.0], float(wl.nodes), ai, bi, aa, ba, gamma)
+
+    def smax(x):
+        m = x.max(axis=-1).astype(np.float64)
+        s = ((x / np.maximum(m, 1)[..., None]) ** gamma).sum(-1) ** (1 / gamma)
+        return np.where(m > 0, m * s, 0.0)
+
+    ref = (wl.nodes * smax(Zn) * M * v * bi[1] + ai[1]) + ((wl.G // wl.nodes) * wl.nodes * smax(Zg) * M * v * ba + aa)
+    assert np.allclose(Q, ref, rtol=1e-12, atol=0)
+    assert best == tuple(int(i) for i in np.unravel_index(np.argmin(Q), Q.shape)) and bt == Q[best]
+    assert bt <= Q[0, 0]
