@@ -736,6 +736,9 @@ def run_planner(args) -> int:
     log("d* = %d, t_d = %s; best swap %s -> %.4f vs %.4f without a swap"
         % (int(best_d.item()), np.round(times.cpu().numpy()[:D], 4).tolist(), tuple(bp.cpu().numpy().tolist()),
            float(bt.item()), float(Q[0, 0].item())))
+    monitored = None
+    if args.monitored:
+        monitored = monitored_dimension_choice(wl, e2r, ai, bi, aa, ba, stream)
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -759,9 +762,70 @@ def run_planner(args) -> int:
               "roofline": {"bound": "alu", "kernel": "hm_swap_counts", "achieved": round(updates / (swap_ms * 1e-3) / 1e12, 5),
                            "peak": 157.3 / 2, "unit": "Tupdate/s (int32 add, vs the 78.6 Tadd/s vector rate)",
                            "frac": round(updates / (swap_ms * 1e-3) / 1e12 / (157.3 / 2), 6), "traffic": None},
-              "cpu_baseline": cpu, "kernels": kern}
+              "cpu_baseline": cpu, "kernels": kern, "monitored_counts": monitored}
     print(json.dumps(result), flush=True)
     return 0
+
+
+def monitored_dimension_choice(wl, e2r, ai, bi, aa, ba, stream):
+    """Alg.1 for the two-dimensional exchange with the counts it monitors instead of the fan-in
+    proxy: the inter-node hop of the N same-local-index source ranks is run on the device (each
+    with its own seeded routing), the receiver's intra-node plan gives the per-GPU counts of the
+    tokens it holds after that hop, p^(2,G), and hm_alltoall_times takes those dest_count vectors
+    straight from device memory.  Returns both sets of times and d*."""
+    import dataclasses
+    import numpy as np
+    import torch
+    from paper_2508_09591_amd import binding as B
+    from paper_2508_09591_amd import workloads as W
+
+    N, R, G, K, E = wl.nodes, wl.ranks_per_node, wl.G, wl.K, wl.E
+    node, local = 1 % N, 0
+    me = node * R + local
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    e2r_d = dev(e2r)
+    parts_i, parts_w, own = [], [], None
+    with torch.cuda.stream(stream):
+        for n in range(N):
+            rt = W.make_routing(dataclasses.replace(wl, seed=1000 + n * R + local))
+            ids_d, w_d = dev(rt.topk_ids), dev(rt.topk_weights)
+            if n == node:
+                own = (ids_d, w_d)
+            p1 = B.hm_plan(ids_d, w_d, e2r_d, N, R, B.HM_DEDUP_NODE, stream=stream)
+            st, tot = B.hm_plan_status(p1, stream=stream)
+            assert st == 0
+            off = p1.dest_offset[:N + 1].cpu().numpy()
+            a, b = int(off[node]), int(off[node + 1])
+            for t, parts, dt in ((ids_d, parts_i, torch.int32), (w_d, parts_w, torch.float32)):
+                rows = torch.empty((tot, 2 * K), dtype=torch.bfloat16, device="cuda")
+                B.hm_dispatch_pack(t.view(torch.bfloat16).view(-1, 2 * K), p1, rows, stream=stream)
+                parts.append(rows[a:b].contiguous().view(dt).view(-1, K))
+        rid, rw = torch.cat(parts_i).contiguous(), torch.cat(parts_w).contiguous()
+        dmA = torch.empty(E, dtype=torch.int32, device="cuda")
+        ndA = torch.empty(1, dtype=torch.int32, device="cuda")
+        B.hm_recv_dest_map(e2r_d, N, R, me, B.HM_RECV_INTRA_NODE, dmA, ndA, stream=stream)
+        planA = B.hm_plan_mapped(rid, rw, dmA, R, True, stream=stream)
+        plan_gpu = B.hm_plan(own[0], own[1], e2r_d, N, R, B.HM_DEDUP_GPU, stream=stream)
+        plan_node = B.hm_plan(own[0], own[1], e2r_d, N, R, B.HM_DEDUP_NODE, stream=stream)
+        p_inter = torch.zeros((2, 64), dtype=torch.int32, device="cuda")
+        p_intra = torch.zeros((2, 64), dtype=torch.int32, device="cuda")
+        p_inter[1, :N] = plan_node.dest_count[:N]
+        p_intra[0, :G] = plan_gpu.dest_count[:G]
+        p_intra[1, :R] = planA.dest_count[:R]            # the monitored counts
+        p_proxy = p_intra.clone()
+        p_proxy[1, :G] = plan_gpu.dest_count[:G] * N     # the proxy: own per-GPU counts times the fan-in
+        times = torch.zeros(4, dtype=torch.float64, device="cuda")
+        best = torch.zeros(1, dtype=torch.int32, device="cuda")
+        out = {}
+        for name, pa in (("monitored", p_intra), ("fan_in_proxy", p_proxy)):
+            B.hm_alltoall_times([1, N], G, wl.H, 2.0, p_inter, pa, ai[:2], bi[:2], aa[:2], ba[:2], times, best, stream=stream)
+            torch.cuda.synchronize()
+            out[name] = {"t_d": [round(float(x), 6) for x in times.cpu().numpy()[:2]], "d_star": int(best.item()),
+                         "max_p2G": int(pa[1].max().item())}
+    out["what"] = ("two-dimensional exchange U=[1,%d] seen from rank %d: received rows %d -> %d after the intra-node re-dedup"
+                   % (N, me, rid.shape[0], int(planA.dest_count[:R].sum().item())))
+    log("Alg.1 with monitored counts: %s; fan-in proxy: %s" % (out["monitored"], out["fan_in_proxy"]))
+    return out
 
 
 def run_table4(args) -> int:

@@ -102,9 +102,9 @@ def test_full_size_layers(hw, oracle, name):
         _run_layer(hw, oracle, wl, wl.T, wl.H, level, check_transpose=(name == "dsv3"))
 
 
-def test_combine_with_wide_segments(hw, oracle):
-    """Launches with at least 65536 seven-KiB segments take the wide combine kernel: a ragged row
-    length (two segments, the second mostly empty) with scaled experts, element by element."""
+def test_combine_on_a_ragged_row_length(hw, oracle):
+    """33001 tokens of 517 vectors per row (nine 1 KiB segments, the last one almost empty; two 4 KiB
+    segments for the kernel that merges the caller's weights) with scaled experts, element by element."""
     import dataclasses
     wl = dataclasses.replace(W.WORKLOADS["skew"], name="wide", K=4, E=32, nodes=2, ranks_per_node=4, seed=77)
     for level in (GPU, NODE):
@@ -187,8 +187,99 @@ def test_full_size_stress_sampled(hw, oracle):
             ref = oracle.combine(y_sub, r.topk_weights[t0:t0 + 300], inv.reshape(sr.shape).astype(np.int32))
             got = hw.bf16_to_host(out_d[t0:t0 + 300])
             assert bf16_ulp_distance(got, ref).max() <= 1, (ctx, t0)
-        del packed_d, out_d, gy_d
+        # scaled experts ("output = c[e] * input", a shared row carrying the weight-normalised mixture):
+        # Y is built on the device from the verified packed rows by the harness (one fp32 multiply,
+        # rounded to bf16 -- the numpy form below gives the same bits), combine is checked on token windows
+        cexp = W.make_expert_scales(wl)
+        num = np.zeros(n)
+        np.add.at(num, ora.slot_row.reshape(-1), (r.topk_weights * cexp[r.topk_ids]).astype(np.float64).reshape(-1))
+        scale = (num / ora.row_weight.astype(np.float64)).astype(np.float32)
+        y_d = (packed_d.float() * hw.dev(scale)[:, None]).to(torch.bfloat16)
+        hw.combine_forms(B.hm_combine, y_d, g.w_d, g.plan, out_d)
+        for t0 in [0, wl.T - 300] + [int(v) for v in rng.integers(0, wl.T - 300, 2)]:
+            sr = ora.slot_row[t0:t0 + 300]
+            uniq, inv = np.unique(sr, return_inverse=True)
+            y_sub = W.f32_to_bf16_bits(scale[uniq][:, None] * W.bf16_bits_to_f32(oracle.dispatch_pack(x, ora.row_token[uniq])))
+            assert np.array_equal(hw.bf16_to_host(y_d[torch.from_numpy(uniq).cuda()]), y_sub), (ctx, t0)
+            ref = oracle.combine(y_sub, r.topk_weights[t0:t0 + 300], inv.reshape(sr.shape).astype(np.int32))
+            got = hw.bf16_to_host(out_d[t0:t0 + 300])
+            assert bf16_ulp_distance(got, ref).max() <= 1, (ctx, "scaled", t0)
+        del packed_d, out_d, gy_d, y_d
         torch.cuda.empty_cache()
+
+
+def test_full_size_dsv3_at_the_other_levels(hw, oracle):
+    """The DeepSeek-V3-shaped layer at full size at rank level and without dedup (about seven and
+    exactly eight rows per token: combine runs with the cap on resident waves), scaled experts,
+    element by element."""
+    wl = W.WORKLOADS["dsv3"]
+    for level in (GPU, NONE):
+        _run_layer(hw, oracle, wl, wl.T, wl.H, level, expert_model="scaled")
+
+
+def test_full_size_dsv3_scaled_experts_at_node_level(hw, oracle):
+    wl = W.WORKLOADS["dsv3"]
+    _run_layer(hw, oracle, wl, wl.T, wl.H, NODE, expert_model="scaled")
+
+
+def test_worst_case_buffers_without_a_sync(hw, oracle):
+    """The mode the header recommends to callers that do not want to synchronise: row buffers
+    allocated for the worst case (row_capacity rows) and no hm_plan_status before the row calls.
+    The launch shape then comes from the bound hm_plan left in the struct -- never from the buffer
+    sizes -- and the results are the oracle's whatever shape a hint selects."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    wl = W.WORKLOADS["dsv3"]
+    T, H = 1500, 7168
+    r = W.make_routing(wl, T=T)
+    x = W.make_activations(wl, T=T, H=H)
+    x_d = hw.to_dev_bf16(x)
+    ids_d, w_d, e2r_d = hw.dev(r.topk_ids), hw.dev(r.topk_weights), hw.dev(r.expert_to_rank)
+    for level, bound, shape in ((GPU, 8, (1, 8, 16)), (NODE, 4, (1, 8, 32)), (NONE, 8, (1, 8, 16))):
+        ctx = "no-sync level=%s" % LEVEL[level]
+        print("case:", ctx, flush=True)
+        ora = oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level)
+        plan = B.hm_plan(ids_d, w_d, e2r_d, wl.nodes, wl.ranks_per_node, level)       # no hm_plan_status
+        assert plan.c.expected_rows == 0 and plan.c.max_rows_per_token == bound
+        assert B.hm_combine_launch_shape(plan, H) == shape, ctx
+        assert B.hm_combine_launch_shape(plan, H, weights_from_plan=False) == (4, 4, 32)
+        cap = plan.row_capacity                                                       # T * min(K, destinations)
+        packed_d = torch.full((cap, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+        B.hm_dispatch_pack(x_d, plan, packed_d)
+        n = ora.total_rows
+        assert cap > n or level == NONE
+        assert np.array_equal(hw.bf16_to_host(packed_d[:n]), oracle.dispatch_pack(x, ora.row_token)), ctx
+        assert bool(torch.isnan(packed_d[n:]).all())                                  # nothing beyond total_rows
+        ref = oracle.combine(hw.bf16_to_host(packed_d[:n]), r.topk_weights, ora.slot_row)
+        outs = []
+        for hint in (0, n, T, 64 * T):           # unknown, the true count, "one row per token", "very many"
+            plan.c.expected_rows = hint
+            out_d = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+            hw.combine_forms(B.hm_combine, packed_d, w_d, plan, out_d)
+            outs.append(hw.bf16_to_host(out_d))
+            assert bf16_ulp_distance(outs[-1], ref).max() <= 1, (ctx, hint)
+            assert np.array_equal(outs[-1], outs[0]), (ctx, hint)                     # the shape never changes the bits
+        plan.c.expected_rows = T
+        assert B.hm_combine_launch_shape(plan, H) == (1, 8, 32)
+        plan.c.expected_rows = 64 * T
+        assert B.hm_combine_launch_shape(plan, H) == (1, 8, 16)
+        st, total = B.hm_plan_status(plan)
+        assert st == 0 and total == n and plan.c.expected_rows == n                   # the status call leaves the count as the hint
+    # a hop-table plan (about one row per token, no useful bound): unknown means "few", whatever the buffer
+    on3 = r.expert_to_rank == 3
+    dm = hw.dev(np.where(on3, np.cumsum(on3) - 1, -1).astype(np.int32))      # experts of rank 3 -> 0, 1, 2, ...; others: no copy
+    nd = int(on3.sum())
+    mp = B.hm_plan_mapped(ids_d, w_d, dm, nd, False)
+    assert mp.c.max_rows_per_token == 0 and mp.c.expected_rows == 0
+    assert B.hm_combine_launch_shape(mp, H) == (1, 8, 32)
+    o = oracle.plan_mapped(r.topk_ids, r.topk_weights, dm.cpu().numpy(), nd, False)
+    big_d = torch.full((mp.row_capacity, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    B.hm_dispatch_pack(x_d, mp, big_d)
+    assert np.array_equal(hw.bf16_to_host(big_d[:o.total_rows]), oracle.dispatch_pack(x, o.row_token))
+    out_d = torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda")
+    hw.combine_forms(B.hm_combine_mix, big_d, w_d, mp, out_d)
+    refm = oracle.combine_mix(hw.bf16_to_host(big_d[:o.total_rows]), r.topk_weights, o.slot_row)
+    assert bf16_ulp_distance(hw.bf16_to_host(out_d), refm).max() <= 1
 
 
 def test_table4_grid(hw, oracle):
