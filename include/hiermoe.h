@@ -220,8 +220,9 @@ hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t 
  * width of a row is free in the paper: the `v` of Section II-B):
  *     gy[row,:] = bf16( row_weight[row] * gout[t,:] ),  the exact product rounded once (the fp32
  * product's own rounding error, recovered with one fma, settles the cases where rounding twice
- * would differ).  gout [T,H] bf16, gy [gy_rows,H] bf16; fast path needs H % 8 == 0 and 16-byte
- * aligned buffers.  Errors as hm_combine_transpose.
+ * would differ; that error term underflows for |row_weight * gout| below about 2^-102, where an
+ * exact tie of the fp32 product may be broken to even instead).  gout [T,H] bf16, gy [gy_rows,H]
+ * bf16; fast path needs H % 8 == 0 and 16-byte aligned buffers.  Errors as hm_combine_transpose.
  */
 hm_status hm_combine_transpose_bf16(const void *gout_bf16, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
                                     void *gy_bf16, int64_t gy_rows, void *hip_stream);

@@ -71,4 +71,18 @@ static inline hm_status hm_check_tk(int32_t T, int32_t K) {
   if ((int64_t)T * K > 2147483647LL) return HM_ERR_SHAPE;
   return HM_OK;
 }
-static inline hm_status hm_launch_status() { return hipGetLastError() == hipSuccess ? HM_OK : HM_ERR_HIP; }
+// Launch errors.  HIP keeps the last error of a thread until somebody reads it, so an error the
+// host program left behind before calling into this library must not be reported as a failed
+// launch of ours (nor cleared: it is the host program's to find).  Every entry point notes what
+// was pending when it was entered; a launch counts as failed only if a new error appears.
+static thread_local hipError_t hm_pending_at_entry = hipSuccess;
+struct hm_entry_scope {
+  hm_entry_scope() { hm_pending_at_entry = hipPeekAtLastError(); }
+};
+#define HM_ENTRY_SCOPE const hm_entry_scope hm_entry_scope_here
+static inline hm_status hm_launch_status() {
+  const hipError_t now = hipPeekAtLastError();
+  if (now == hipSuccess || now == hm_pending_at_entry) return HM_OK;
+  (void)hipGetLastError();   // ours: reported through the return code, not left for the next caller
+  return HM_ERR_HIP;
+}

@@ -93,6 +93,7 @@ __global__ __launch_bounds__(kLoadThreads) void load_count_kernel(LoadParams p) 
 extern "C" hm_status hm_expert_load(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
                                     int32_t E, hm_topology topo, int32_t *load_expert, int32_t *load_rank,
                                     int32_t *load_node, int32_t *status, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   using namespace hm;
   if (!expert_to_rank || !load_expert || !load_rank || !load_node) return HM_ERR_NULL;
   hm_status st = hm_check_tk(T, K);

@@ -117,6 +117,7 @@ __global__ __launch_bounds__(kWave) void alltoall_times_kernel(TimeParams p) {
 extern "C" hm_status hm_group_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
                                      int32_t E, int32_t G, int32_t depth, const int32_t *groups, int32_t *counts,
                                      int32_t *status, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   using namespace hm;
   if (!expert_to_rank || !groups || !counts) return HM_ERR_NULL;
   hm_status st = hm_check_tk(T, K);
@@ -153,6 +154,7 @@ extern "C" hm_status hm_alltoall_times(int32_t D, const int32_t *U, int32_t G, d
                                        const int32_t *p_inter, const int32_t *p_intra, const double *alpha_inter,
                                        const double *beta_inter, const double *alpha_intra, const double *beta_intra,
                                        double *times, int32_t *best, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   using namespace hm;
   if (!U || !p_inter || !p_intra || !alpha_inter || !beta_inter || !alpha_intra || !beta_intra || !times || !best)
     return HM_ERR_NULL;

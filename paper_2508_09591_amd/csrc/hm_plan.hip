@@ -875,6 +875,7 @@ static hm_status check_plan_args(const int32_t *topk_ids, const float *topk_weig
 extern "C" hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
                              int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
                              hm_plan_out *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!workspace) return HM_ERR_NULL;
   hm_status st = check_plan_args(topk_ids, topk_weights, expert_to_rank, T, K, E, topo, level, out);
   if (st != HM_OK) return st;
@@ -913,6 +914,7 @@ extern "C" size_t hm_plan_static_max_bytes(void) { return hm::kPlanStaticBytes; 
 extern "C" hm_status hm_plan_static(const int32_t *topk_ids, const float *topk_weights, const int32_t *expert_to_rank,
                                     int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
                                     hm_plan_out *out, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   hm_status st = check_plan_args(topk_ids, topk_weights, expert_to_rank, T, K, E, topo, level, out);
   if (st != HM_OK) return st;
   if (hm_plan_workspace_bytes(T, K, E, topo, level) > hm::kPlanStaticBytes) return HM_ERR_WORKSPACE;
@@ -932,6 +934,7 @@ extern "C" size_t hm_plan_mapped_workspace_bytes(int32_t rows, int32_t K, int32_
 extern "C" hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_weights, const int32_t *dest_map,
                                     int32_t rows, int32_t K, int32_t E, int32_t num_dest, int32_t dedup, hm_plan_out *out,
                                     void *workspace, size_t workspace_bytes, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!out || !dest_map || !workspace) return HM_ERR_NULL;
   if (!out->dest_count || !out->dest_offset || !out->row_token || !out->slot_row || !out->slot_keep ||
       !out->row_weight || !out->status)
@@ -977,6 +980,7 @@ extern "C" hm_status hm_plan_mapped(const int32_t *row_ids, const float *row_wei
 
 extern "C" hm_status hm_recv_dest_map(const int32_t *expert_to_rank, int32_t E, hm_topology topo, int32_t my_rank,
                                       hm_recv_stage stage, int32_t *dest_map, int32_t *num_dest, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!expert_to_rank || !dest_map || !num_dest) return HM_ERR_NULL;
   if (E < 1) return HM_ERR_SHAPE;
   hm_status st = hm_check_topology(topo);
@@ -992,6 +996,7 @@ extern "C" hm_status hm_recv_dest_map(const int32_t *expert_to_rank, int32_t E, 
 extern "C" hm_status hm_level_dest_map(const int32_t *expert_to_rank, int32_t E, int32_t G, int32_t my_rank,
                                        int32_t parent_groups, int32_t child_groups, int32_t *dest_map, int32_t *num_dest,
                                        void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!expert_to_rank || !dest_map || !num_dest) return HM_ERR_NULL;
   if (E < 1) return HM_ERR_SHAPE;
   if (G < 1 || G > 64 || my_rank < 0 || my_rank >= G) return HM_ERR_TOPOLOGY;
@@ -1005,6 +1010,7 @@ extern "C" hm_status hm_level_dest_map(const int32_t *expert_to_rank, int32_t E,
 }
 
 extern "C" hm_status hm_plan_status(hm_plan_out *plan, int64_t *total_rows, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!plan || !plan->status || !plan->dest_offset) return HM_ERR_NULL;
   if (plan->num_dest < 1 || plan->num_dest > 64) return HM_ERR_SHAPE;
   hipStream_t stream = (hipStream_t)hip_stream;

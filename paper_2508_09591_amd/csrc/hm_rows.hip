@@ -151,7 +151,9 @@ struct RowBf16 {
   static __device__ __forceinline__ elem narrow(float f) { return (elem)f32_to_bf16(f); }
   // bf16(a * g) with ONE rounding.  The fp32 product p is already rounded; a second rounding to
   // bf16 differs from the exact one only when p sits exactly on a bf16 tie, and there the sign of
-  // the product's rounding error e = fma(a, g, -p) (exact) says on which side the true value lies.
+  // the product's rounding error e = fma(a, g, -p) says on which side the true value lies.  e is
+  // exact as long as it does not underflow, i.e. for |a * g| >= 2^-102 or so; for smaller products
+  // (gradients of that size do not occur in practice) a tie may be broken to even instead.
   static __device__ __forceinline__ uint32_t scale1(float a, float g) {
     const float p = a * g;
     const float e = __builtin_fmaf(a, g, -p);
@@ -564,6 +566,7 @@ static hm_status check_rows_args(int32_t T, int32_t K, int32_t H, const hm_plan_
 
 extern "C" hm_status hm_dispatch_pack(const void *x_bf16, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
                                       void *packed_bf16, int64_t packed_rows, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   using namespace hm;
   hm_status st = check_rows_args(T, K, H, plan, true);
   if (st != HM_OK) return st;
@@ -638,6 +641,7 @@ static hm_status launch_combine(const void *y, int64_t y_rows, const float *topk
 extern "C" hm_status hm_combine_launch_shape(int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
                                              int32_t weights_from_plan, int32_t *vectors_per_lane,
                                              int32_t *rows_in_flight, int32_t *waves_per_cu) {
+  HM_ENTRY_SCOPE;
   hm_status st = check_rows_args(T, K, H, plan, false);
   if (st != HM_OK) return st;
   const hm::CombineShape sh = hm::combine_shape(plan, T, weights_from_plan != 0);
@@ -649,16 +653,19 @@ extern "C" hm_status hm_combine_launch_shape(int32_t T, int32_t K, int32_t H, co
 
 extern "C" hm_status hm_combine(const void *y_bf16, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
                                 int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   return launch_combine<false, hm::RowBf16>(y_bf16, y_rows, topk_weights, T, K, H, plan, out_bf16, hip_stream);
 }
 
 extern "C" hm_status hm_combine_f32(const float *y, int64_t y_rows, const float *topk_weights, int32_t T, int32_t K,
                                     int32_t H, const hm_plan_out *plan, float *out, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   return launch_combine<false, hm::RowF32>(y, y_rows, topk_weights, T, K, H, plan, out, hip_stream);
 }
 
 extern "C" hm_status hm_combine_mix(const void *y_bf16, int64_t y_rows, const float *row_weights, int32_t T, int32_t K,
                                     int32_t H, const hm_plan_out *plan, void *out_bf16, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   return launch_combine<true, hm::RowBf16>(y_bf16, y_rows, row_weights, T, K, H, plan, out_bf16, hip_stream);
 }
 
@@ -696,10 +703,12 @@ static hm_status launch_transpose(const void *gout, int32_t T, int32_t K, int32_
 
 extern "C" hm_status hm_combine_transpose(const float *gout, int32_t T, int32_t K, int32_t H, const hm_plan_out *plan,
                                           float *gy, int64_t gy_rows, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   return launch_transpose<hm::RowF32>(gout, T, K, H, plan, gy, gy_rows, hip_stream);
 }
 
 extern "C" hm_status hm_combine_transpose_bf16(const void *gout_bf16, int32_t T, int32_t K, int32_t H,
                                                const hm_plan_out *plan, void *gy_bf16, int64_t gy_rows, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   return launch_transpose<hm::RowBf16>(gout_bf16, T, K, H, plan, gy_bf16, gy_rows, hip_stream);
 }

@@ -447,6 +447,7 @@ static hm_status swap_counts_checks(const int32_t *topk_ids, const int32_t *expe
 extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
                                     int32_t E, int32_t G, int32_t ng, int32_t *Z, int32_t *status, void *workspace,
                                     size_t workspace_bytes, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!Z) return HM_ERR_NULL;
   hm_status st = swap_counts_checks(topk_ids, expert_to_rank, T, K, E, workspace);
   if (st != HM_OK) return st;
@@ -458,6 +459,7 @@ extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expe
 extern "C" hm_status hm_swap_counts_multi(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K,
                                           int32_t E, int32_t G, int32_t ncuts, const int32_t *ng, int32_t *const *Z,
                                           int32_t *status, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!Z || !ng) return HM_ERR_NULL;
   hm_status st = swap_counts_checks(topk_ids, expert_to_rank, T, K, E, workspace);
   if (st != HM_OK) return st;
@@ -479,6 +481,7 @@ extern "C" hm_status hm_swap_select(int32_t d, const int32_t *U, int32_t G, int3
                                     double scale_intra, const double *alpha_inter, const double *beta_inter,
                                     double alpha_intra, double beta_intra, double gamma, double *Q, int32_t *best_pair,
                                     double *best_time, void *workspace, size_t workspace_bytes, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   using namespace hm;
   if (!U || !z_intra || !Q || !best_pair || !best_time || !workspace) return HM_ERR_NULL;
   if (d < 1 || d > kMaxDim || G < 1 || G > 64 || U[0] != 1) return HM_ERR_TOPOLOGY;
@@ -522,6 +525,7 @@ extern "C" hm_status hm_swap_select(int32_t d, const int32_t *U, int32_t G, int3
 }
 
 extern "C" hm_status hm_swap_apply(int32_t *expert_to_rank, int32_t E, const int32_t *best_pair, void *hip_stream) {
+  HM_ENTRY_SCOPE;
   if (!expert_to_rank || !best_pair) return HM_ERR_NULL;
   if (E < 1) return HM_ERR_SHAPE;
   hipLaunchKernelGGL(hm::swap_apply_kernel, dim3(1), dim3(hm::kWave), 0, (hipStream_t)hip_stream, expert_to_rank, E,

@@ -686,6 +686,18 @@ def test_transpose_on_bf16_gradients(hw, oracle, name, T, H):
     twice = W.f32_to_bf16_bits((w * np.float32(1.0 + 2.0 ** -7)).astype(np.float32))      # rounded twice
     assert (ref[:, :1] != twice).any()                     # the family does contain such traps
     assert np.array_equal(hw.bf16_to_host(gy_d), ref)
+    # the same family with negative gradients, with several gradient values per row (products just
+    # below, on and above a tie), and scaled down to where the fp32 product is still normal but
+    # small (2^-100): the sign of the rounding error decides every one of them
+    vals = np.array([1.0 + 2.0 ** -7, -(1.0 + 2.0 ** -7), 1.0 + 3 * 2.0 ** -7, -(1.0 + 5 * 2.0 ** -7),
+                     (1.0 + 2.0 ** -7) * 2.0 ** -100, -(1.0 + 3 * 2.0 ** -7) * 2.0 ** -100, 1.5, -1.75], np.float32)
+    gg = W.f32_to_bf16_bits(np.tile(vals, (n_w, 1)))
+    assert np.array_equal(W.bf16_bits_to_f32(gg[0]), vals)                                # all exact in bf16
+    B.hm_combine_transpose_bf16(hw.to_dev_bf16(gg), g.plan, gy_d)
+    ref = oracle.combine_transpose_bf16(gg, ora.row_token, ora.row_weight)
+    twice = W.f32_to_bf16_bits((w * vals[None, :]).astype(np.float32))
+    assert (ref != twice)[:, [0, 1, 4]].any(axis=0).all()      # a trap in the negative and in the small column as well
+    assert np.array_equal(hw.bf16_to_host(gy_d), ref)
 
 
 def test_combine_with_cancelling_terms(hw, oracle):
