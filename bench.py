@@ -92,6 +92,26 @@ def stream_probe(src, read_streams, dst, write_streams, block_threads=64, waves_
     return dst
 
 
+_event_overhead = {}
+
+
+def event_pair_overhead_ms(stream):
+    """What a start / stop pair of HIP events reads with nothing between them (median of 200 pairs
+    on `stream`): the markers' own cost, which every per-call figure below would otherwise carry.
+    It is measured once per stream and reported beside the per-call times (not subtracted: with a
+    kernel between the markers part of it hides behind the kernel)."""
+    import torch
+    key = stream.cuda_stream
+    if key not in _event_overhead:
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(200)]
+        for a, b in pairs:
+            a.record(stream)
+            b.record(stream)
+        torch.cuda.synchronize()
+        _event_overhead[key] = sorted(a.elapsed_time(b) for a, b in pairs)[100]
+    return _event_overhead[key]
+
+
 def get_workload(name):
     """A workload of the benchmark set plus the placement to use: `skew-swapped` is the skew layer
     under its seeded random expert placement."""
@@ -203,8 +223,13 @@ def time_send(wl, level, steps, warmup, nsets, *, label=None, placement_key=None
         step(i, events[i])
     torch.cuda.synchronize()
     names = ["hm_plan", "hm_expert_load", "hm_dispatch_pack", "hm_combine"]
+    ov = event_pair_overhead_ms(stream)
     per_call = {n: sorted(e[2 * j].elapsed_time(e[2 * j + 1]) for e in events) for j, n in enumerate(names)}
     avg_ms = {n: sum(v) / len(v) for n, v in per_call.items()}
+    # An empty event pair already reads `ov`; with a kernel between the markers part of that cost hides
+    # behind the kernel, so the kernel's own duration lies between (reading - ov) and the reading.  The
+    # reading -- the conservative end -- is what every rate and roofline fraction below uses.
+    low_avg_ms = {n: max(avg_ms[n] - ov, 0.0) for n in names}
     min_ms = {n: v[0] for n, v in per_call.items()}
     med_ms = {n: v[len(v) // 2] for n, v in per_call.items()}
 
@@ -221,7 +246,7 @@ def time_send(wl, level, steps, warmup, nsets, *, label=None, placement_key=None
             e[2].record(stream)
         torch.cuda.synchronize()
         warm_ms = {"hm_dispatch_pack": sorted(e[0].elapsed_time(e[1]) for e in wev)[len(wev) // 2],
-                   "hm_combine": sorted(e[1].elapsed_time(e[2]) for e in wev)[len(wev) // 2]}
+                   "hm_combine": sorted(e[1].elapsed_time(e[2]) for e in wev)[len(wev) // 2]}     # one marker between the two calls: not corrected
 
     # correctness of what was timed: identity experts + weights summing to 1 -> output == input
     assert torch.equal(outs[(steps - 1) % nsets], xs[(steps - 1) % nsets]), "round trip failed"
@@ -236,6 +261,7 @@ def time_send(wl, level, steps, warmup, nsets, *, label=None, placement_key=None
     for n in ("hm_dispatch_pack", "hm_combine"):
         gbs = alg_bytes[n] / (avg_ms[n] * 1e-3) / 1e9
         kern[n] = {"avg_ms": round(avg_ms[n], 5), "median_ms": round(med_ms[n], 5), "min_ms": round(min_ms[n], 5),
+                   "avg_ms_less_empty_event_pair": round(low_avg_ms[n], 5),
                    "warm_single_set_median_ms": None if warm_ms[n] is None else round(warm_ms[n], 5), "alg_bytes": int(alg_bytes[n]),
                    "achieved_GBps": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4),
                    "traffic": measured_traffic(label, level_name, n)}
@@ -244,7 +270,8 @@ def time_send(wl, level, steps, warmup, nsets, *, label=None, placement_key=None
             kern[n]["traffic_over_algorithmic"] = round(kern[n]["traffic"] / alg_bytes[n], 4)
     pair_ms = avg_ms["hm_dispatch_pack"] + avg_ms["hm_combine"]
     pair_gbs = (alg_bytes["hm_dispatch_pack"] + alg_bytes["hm_combine"]) / (pair_ms * 1e-3) / 1e9
-    log("per-call (HIP events, avg/median/min ms): " + ", ".join("%s %.4f/%.4f/%.4f" % (n, avg_ms[n], med_ms[n], min_ms[n]) for n in names))
+    log("per-call (HIP events, avg/median/min ms; an empty event pair reads %.1f us): " % (ov * 1e3)
+        + ", ".join("%s %.4f/%.4f/%.4f" % (n, avg_ms[n], med_ms[n], min_ms[n]) for n in names))
     if warm_leg:
         log("warm, one buffer set (median ms): dispatch %.4f, combine %.4f" % (warm_ms["hm_dispatch_pack"], warm_ms["hm_combine"]))
     log("dispatch+combine: %.4f ms -> %.1f GB/s algorithmic = %.1f%% of %.0f GB/s; %.2f M tokens/s (pair only); step %.4f ms"
@@ -289,7 +316,7 @@ def time_send(wl, level, steps, warmup, nsets, *, label=None, placement_key=None
     res = {"label": label, "level": level_name, "T": T, "H": H, "K": K, "E": E, "nodes": wl.nodes, "rpn": wl.ranks_per_node,
            "total_rows": total_rows, "c": c, "nsets": nsets, "y_shift": y_shift, "ms_per_step": ms_per_step,
            "tokens_per_s": T / (elapsed / steps), "kern": kern, "pair_ms": pair_ms, "pair_gbs": pair_gbs,
-           "plan_ms": avg_ms["hm_plan"], "expert_load_ms": None if fused else avg_ms["hm_expert_load"],
+           "plan_ms": avg_ms["hm_plan"], "expert_load_ms": None if fused else avg_ms["hm_expert_load"], "event_overhead_ms": ov,
            "alg_bytes": alg_bytes, "extra": extra, "routing": r, "e2r": e2r, "x_host": x, "stream": stream}
     del xs, packs, outs
     torch.cuda.empty_cache()
@@ -320,7 +347,7 @@ def flat_stream_references(c, total_bytes, nsets, stream):
                 stream_probe(srcs[i % nsets], nr, dsts[i % nsets], nw, block, waves, stream=stream)
                 b.record(stream)
             torch.cuda.synchronize()
-            pms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]
+            pms = sorted(a.elapsed_time(b) for a, b in pev)[len(pev) // 2]                     # timed like the row kernels
             if best is None or pms < best[0]:
                 best = (pms, block, waves)
         pms, block, waves = best
@@ -517,6 +544,10 @@ def run_send(args) -> int:
         "pair": {"ms": round(head["pair_ms"], 5), "achieved_GBps": round(head["pair_gbs"], 1),
                  "frac": round(head["pair_gbs"] / HBM_PEAK_GBS, 4), "tokens_per_s": round(T / (head["pair_ms"] * 1e-3), 1)},
         "plan_ms": round(head["plan_ms"], 5),
+        "event_pair_overhead_ms": round(head["event_overhead_ms"], 5),
+        "per_call_timing": "start / stop HIP events around each call on the launch stream; an empty pair already reads "
+                           "event_pair_overhead_ms, so a kernel's own duration lies between avg_ms_less_empty_event_pair "
+                           "and avg_ms (the kernel traces under profiles/ fall in between); rates use avg_ms",
         "device_copy_reference": copy_ref,
         "flat_stream_reference": stream_ref,
         "expert_load_ms": None if head["expert_load_ms"] is None else round(head["expert_load_ms"], 5),
@@ -753,15 +784,28 @@ def run_planner(args) -> int:
                "sample": "the whole %s batch once (incremental Z update for %d cuts + selection), %.2f s" % (wl.name, len(cuts), dt)}
         log("cpu oracle: %.2f s" % dt)
     swap_ms = kern[names[2]]
-    # integer work of the factor pass: T*K*(K + ng) table updates per cut, plus E*E*ng outputs
-    updates = sum(T * K * (K + u) + E * E * u for u in cuts)
+    # What bounds the co-occurrence pass is its read-modify-write updates: per token and cut, one update of the
+    # expert-by-expert table for every (expert alone in its group, other selected expert) pair go to global
+    # memory (popular pairs serialise on one address); everything else accumulates in LDS first.  The rate is
+    # put against what the L2 atomic units could do at best: 8 dies x 16 channels x one update per clock.
+    ids_h = r.topk_ids
+    pair_updates = 0
+    for u in cuts:
+        grp = (e2r[ids_h] // (G // u)).astype(np.int64)                                  # [T, K] group of every selected expert
+        same = (grp[:, :, None] == grp[:, None, :]).sum(2)                              # selected experts sharing my group (top-K ids are distinct)
+        pair_updates += int(((same == 1).sum(1) * (K - 1)).sum())
+    peak_updates = 8 * 16 * 2.4e9
     result = {"metric": "planner (counts + d* + swap tensor Z + best pair) tokens/s", "value": round(T / (ms_per_step * 1e-3), 1),
               "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
               "config": {"workload": "%s: T=%d K=%d E=%d G=%d, hierarchy U=%s, gamma=10" % (wl.name, T, K, E, G, U)},
-              "roofline": {"bound": "alu", "kernel": "hm_swap_counts", "achieved": round(updates / (swap_ms * 1e-3) / 1e12, 5),
-                           "peak": 157.3 / 2, "unit": "Tupdate/s (int32 add, vs the 78.6 Tadd/s vector rate)",
-                           "frac": round(updates / (swap_ms * 1e-3) / 1e12 / (157.3 / 2), 6), "traffic": None},
+              "roofline": {"bound": "alu", "kernel": "hm_swap_counts", "achieved": round(pair_updates / (swap_ms * 1e-3) / 1e9, 3),
+                           "peak": round(peak_updates / 1e9, 1),
+                           "unit": "G global read-modify-write updates/s (peak: 8 dies x 16 L2 channels x 1 update per clock at 2.4 GHz)",
+                           "frac": round(pair_updates / (swap_ms * 1e-3) / peak_updates, 5), "traffic": None,
+                           "updates_per_launch": pair_updates,
+                           "note": "seven short launches over a few hundred KiB of input: launch latency and same-address "
+                                   "serialisation of the updates, not arithmetic or bandwidth, set the time"},
               "cpu_baseline": cpu, "kernels": kern, "monitored_counts": monitored}
     print(json.dumps(result), flush=True)
     return 0

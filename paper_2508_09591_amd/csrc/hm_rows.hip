@@ -27,6 +27,8 @@
 // With the plan's merged weights (topk_weights == NULL) the first slot of each row is the one
 // slot_keep marks and its weight is one gathered load from row_weight, so the prologue is short
 // enough for 1 KiB segments with all of a token's rows (up to eight) in flight: 3-9 % faster.
+// Tokens with about one row each (the local-expert stage of a receiver) keep 4 KiB segments, two
+// rows in flight: a 1 KiB segment would be mostly prologue there (0.36 vs 0.28 ms on that stage).
 #include "hm_device.h"
 
 #include <atomic>
@@ -39,7 +41,9 @@ constexpr int kCopyWavesPerCu = 24;   // ... and this many waves resident per CU
 constexpr int kCombineThreads = 256;
 constexpr int kCombineVecs = 4;       // combine with the caller's weights: 16-byte vectors per lane (4 KiB segments),
 constexpr int kCombineRows = 4;       //   rows whose loads are in flight together
-constexpr int kCombineRowsPlan = 8;   // combine with the plan's weights: 1 KiB segments, up to eight rows in flight
+constexpr int kCombineRowsFew = 2;    //   ... or two, when the tokens are known to have fewer than two rows
+constexpr int kCombineRowsPlan = 8;   // combine with the plan's weights, two rows per token or more: 1 KiB segments,
+                                      //   up to eight rows in flight
 constexpr int kCombineBytesInFlight = 128 * 1024;   // per CU, what the cap on resident waves aims at
 
 struct RowParams {
@@ -311,9 +315,9 @@ __global__ __launch_bounds__(kCombineThreads) void combine_rows_kernel(RowParams
 
 // The same sum with the weights the plan merged: lane k < K holds slot k; the slot slot_keep marks
 // is the first of its row, and row_weight[row] is the fp32 sum, in ascending k, of the weights of
-// the slots that share the row -- the number merge_slots computes.  One 1 KiB segment per wave,
-// the loads of up to R rows issued before the first fma.
-template <bool MIX, int R, typename ROW>
+// the slots that share the row -- the number merge_slots computes.  A wave owns U KiB of the row;
+// the loads of up to R rows are issued before the first fma.
+template <bool MIX, int U, int R, typename ROW>
 __global__ __launch_bounds__(kCombineThreads) void combine_plan_rows_kernel(RowParams p, const u32x4 *__restrict__ y,
                                                                             int64_t y_rows,
                                                                             const float *__restrict__ row_weight,
@@ -339,39 +343,52 @@ __global__ __launch_bounds__(kCombineThreads) void combine_plan_rows_kernel(RowP
     for (uint64_t m = todo; m; m &= m - 1) wsum = wsum + read_lane(agg, __builtin_ctzll(m));
     inv_wsum = wsum != 0.0f ? 1.0f / wsum : 0.0f;
   }
-  const int v = seg * kWave + lane;
-  const bool in_row = v < p.nvec;
+  const int v0 = seg * (kWave * U) + lane;   // this lane's vectors: v0, v0+64, ...
   constexpr int E = ROW::kPerVec;
-  float acc[E];
+  float acc[U][E];
 #pragma unroll
-  for (int e = 0; e < E; ++e) acc[e] = 0.0f;
+  for (int i = 0; i < U; ++i)
+#pragma unroll
+    for (int e = 0; e < E; ++e) acc[i][e] = 0.0f;
   while (todo) {
-    u32x4 r[R];
+    u32x4 r[R][U];
     float a[R];
     bool have[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
       have[j] = todo != 0;
       a[j] = 0.0f;
-      r[j] = (u32x4){0u, 0u, 0u, 0u};
+#pragma unroll
+      for (int i = 0; i < U; ++i) r[j][i] = (u32x4){0u, 0u, 0u, 0u};
       if (have[j]) {
         const int k = __builtin_ctzll(todo);
         todo &= todo - 1;
         const int row = read_lane(my_row, k);
         a[j] = read_lane(agg, k);
-        if (in_row) r[j] = load_stream(y + (int64_t)row * p.nvec + v);
+        const u32x4 *src = y + (int64_t)row * p.nvec;
+#pragma unroll
+        for (int i = 0; i < U; ++i)
+          if (v0 + i * kWave < p.nvec) r[j][i] = load_stream(src + v0 + i * kWave);
       }
     }
 #pragma unroll
-    for (int j = 0; j < R; ++j)
-      if (have[j]) ROW::fma_into(acc, a[j], r[j]);
-  }
-  if (in_row) {
-    if (MIX) {
+    for (int j = 0; j < R; ++j) {
+      if (have[j]) {
 #pragma unroll
-      for (int e = 0; e < E; ++e) acc[e] = acc[e] * inv_wsum;
+        for (int i = 0; i < U; ++i) ROW::fma_into(acc[i], a[j], r[j][i]);
+      }
     }
-    store_stream(out + (int64_t)t * p.nvec + v, ROW::pack(acc));
+  }
+  u32x4 *dst = out + (int64_t)t * p.nvec;
+#pragma unroll
+  for (int i = 0; i < U; ++i) {
+    if (v0 + i * kWave < p.nvec) {
+      if (MIX) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) acc[i][e] = acc[i][e] * inv_wsum;
+      }
+      store_stream(dst + v0 + i * kWave, ROW::pack(acc[i]));
+    }
   }
 }
 
@@ -539,9 +556,20 @@ static inline CombineShape combine_shape(const hm_plan_out *plan, int32_t T, boo
     sh.waves_per_cu = 32;
     return sh;
   }
+  const double c = rows_per_token(plan, T);
+  sh.waves_per_cu = 32;
+  if (c <= 0.0) {   // unknown (a hop-table plan that was never synchronised): such plans have few rows per token
+    sh.vecs = kCombineVecs;
+    sh.rows = kCombineRows;
+    return sh;
+  }
+  if (c < 2.0) {    // about one row per token: 1 KiB segments would be mostly prologue
+    sh.vecs = kCombineVecs;
+    sh.rows = kCombineRowsFew;
+    return sh;
+  }
   sh.vecs = 1;
   sh.rows = kCombineRowsPlan;
-  const double c = rows_per_token(plan, T);
   int waves = 32;
   if (c > 4.0) {   // c KiB of loads per wave: keep about kCombineBytesInFlight per CU
     waves = (int)((double)kCombineBytesInFlight / (c * 1024.0));
@@ -620,9 +648,16 @@ static hm_status launch_combine(const void *y, int64_t y_rows, const float *topk
     if (from_plan) {
       // rows the plan's weight array does not cover are treated like rows beyond y
       const int64_t rows = y_rows < plan->row_capacity ? y_rows : plan->row_capacity;
-      hipLaunchKernelGGL((combine_plan_rows_kernel<MIX, kCombineRowsPlan, ROW>), grid, dim3(kCombineThreads),
-                         lds_cap_bytes(sh.waves_per_cu, kCombineThreads), stream, p, (const u32x4 *)y, rows,
-                         plan->row_weight, (u32x4 *)out);
+      if (sh.vecs == 1)
+        hipLaunchKernelGGL((combine_plan_rows_kernel<MIX, 1, kCombineRowsPlan, ROW>), grid, dim3(kCombineThreads),
+                           lds_cap_bytes(sh.waves_per_cu, kCombineThreads), stream, p, (const u32x4 *)y, rows,
+                           plan->row_weight, (u32x4 *)out);
+      else if (sh.rows == kCombineRowsFew)
+        hipLaunchKernelGGL((combine_plan_rows_kernel<MIX, kCombineVecs, kCombineRowsFew, ROW>), grid, dim3(kCombineThreads), 0,
+                           stream, p, (const u32x4 *)y, rows, plan->row_weight, (u32x4 *)out);
+      else
+        hipLaunchKernelGGL((combine_plan_rows_kernel<MIX, kCombineVecs, kCombineRows, ROW>), grid, dim3(kCombineThreads), 0,
+                           stream, p, (const u32x4 *)y, rows, plan->row_weight, (u32x4 *)out);
     } else {
       hipLaunchKernelGGL((combine_rows_kernel<MIX, kCombineVecs, kCombineRows, ROW>), grid, dim3(kCombineThreads), 0,
                          stream, p, (const u32x4 *)y, y_rows, topk_weights, (u32x4 *)out);

@@ -235,8 +235,9 @@ def test_combine_launch_shape_follows_the_plan_not_the_buffers(B):
 
     assert shape(4, 0) == (1, 8, 32)                    # node level on 4 nodes: at most 4 rows per token
     assert shape(8, 0) == (1, 8, 16)                    # rank level / no dedup, K = 8: eight 1 KiB loads per wave
-    assert shape(0, 0) == (1, 8, 32)                    # a mapped plan that was never synchronised: unknown, assume few
-    assert shape(8, int(1.16 * T)) == (1, 8, 32)        # the count wins over the bound (local-expert stage of a receiver)
+    assert shape(0, 0) == (4, 4, 32)                    # a mapped plan that was never synchronised: unknown, assume few
+    assert shape(8, int(1.16 * T)) == (4, 2, 32)        # the count wins over the bound (local-expert stage of a receiver)
+    assert shape(0, int(2.2 * T)) == (1, 8, 32)         # the intra-node stage of a receiver
     assert shape(0, int(6.0 * T)) == (1, 8, 20)         # 128 KiB / 6 KiB = 21 waves -> whole workgroups of four
     assert shape(4, int(7.49 * T)) == (1, 8, 16)
     assert shape(8, 64 * T) == (1, 8, 16)               # never below 16 waves per CU

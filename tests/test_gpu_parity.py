@@ -260,7 +260,7 @@ def test_worst_case_buffers_without_a_sync(hw, oracle):
             assert bf16_ulp_distance(outs[-1], ref).max() <= 1, (ctx, hint)
             assert np.array_equal(outs[-1], outs[0]), (ctx, hint)                     # the shape never changes the bits
         plan.c.expected_rows = T
-        assert B.hm_combine_launch_shape(plan, H) == (1, 8, 32)
+        assert B.hm_combine_launch_shape(plan, H) == (4, 2, 32)
         plan.c.expected_rows = 64 * T
         assert B.hm_combine_launch_shape(plan, H) == (1, 8, 16)
         st, total = B.hm_plan_status(plan)
@@ -271,7 +271,7 @@ def test_worst_case_buffers_without_a_sync(hw, oracle):
     nd = int(on3.sum())
     mp = B.hm_plan_mapped(ids_d, w_d, dm, nd, False)
     assert mp.c.max_rows_per_token == 0 and mp.c.expected_rows == 0
-    assert B.hm_combine_launch_shape(mp, H) == (1, 8, 32)
+    assert B.hm_combine_launch_shape(mp, H) == (4, 4, 32)
     o = oracle.plan_mapped(r.topk_ids, r.topk_weights, dm.cpu().numpy(), nd, False)
     big_d = torch.full((mp.row_capacity, H), float("nan"), dtype=torch.bfloat16, device="cuda")
     B.hm_dispatch_pack(x_d, mp, big_d)
