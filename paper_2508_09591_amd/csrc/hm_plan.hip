@@ -497,7 +497,11 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, 
   me.rank = me.dest = -1;
   me.keep = false;
   if (live) {
-    me.t = (int)((unsigned)s / (unsigned)p.K);
+    // s / K without a per-lane division: the workgroup's first slot is divided once (uniform),
+    // the rest is a numerator below 1024 + K, for which a 22-bit reciprocal is exact (K <= 64)
+    const unsigned t0 = (unsigned)first / (unsigned)p.K, r0 = (unsigned)first - t0 * (unsigned)p.K;
+    const unsigned recip = ((1u << 22) + (unsigned)p.K - 1u) / (unsigned)p.K;
+    me.t = (int)(t0 + (((r0 + threadIdx.x) * recip) >> 22));
     me.k = s - me.t * p.K;
     const int own = halo + (int)threadIdx.x;
     me.tok0 = own - me.k;
@@ -536,29 +540,23 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, 
       for (int k2 = 0; k2 < p.K; ++k2) {
         const int r2 = s_rank[me.tok0 + k2];
         if (r2 >= 0) {
+          // the first slot that sets a bit also counts the token for that rank / node: the
+          // duplicate-free loads of hm_expert_load, as LDS partials (the wave-wide ballots per
+          // group this replaces were a third of the kernel's vector instructions)
+          if (loads && !((rm >> r2) & 1ull)) atomicAdd(&blk_rank[r2], 1);
           rm |= 1ull << r2;
-          if (!p.dest_map) nm |= 1u << s_node[me.tok0 + k2];
+          if (!p.dest_map) {
+            const int n2 = s_node[me.tok0 + k2];
+            if (loads && !((nm >> n2) & 1u)) atomicAdd(&blk_node[n2], 1);
+            nm |= 1u << n2;
+          }
         }
       }
       if (p.rank_mask) p.rank_mask[me.t] = rm;
       if (p.node_mask) p.node_mask[me.t] = nm;
     }
   }
-  if (loads) {   // LDS partials of the counts of hm_expert_load (a ballot per group; lane g keeps group g)
-    if (me.live && me.rank >= 0 && staged_table) atomicAdd(&hist[id], 1);
-    int my_rank_cnt = 0, my_node_cnt = 0;
-    const int nodes = p.G / p.R;
-    for (int g = 0; g < p.G; ++g) {
-      const uint64_t b = __ballot((rm >> g) & 1ull);
-      if (lane == g) my_rank_cnt = __popcll(b);
-    }
-    for (int n = 0; n < nodes; ++n) {
-      const uint64_t b = __ballot((nm >> n) & 1u);
-      if (lane == n) my_node_cnt = __popcll(b);
-    }
-    if (my_rank_cnt) atomicAdd(&blk_rank[lane], my_rank_cnt);
-    if (my_node_cnt) atomicAdd(&blk_node[lane], my_node_cnt);
-  }
+  if (loads && me.live && me.rank >= 0 && staged_table) atomicAdd(&hist[id], 1);   // slots per expert, LDS partial
 
   // ---- the count matrix: wave wv reads rows wv, wv+16, ..., lane = destination, and reads them
   // again, as a whole wave, until every word carries this launch's tag
