@@ -715,12 +715,12 @@ def run_planner(args) -> int:
     best_d = torch.zeros(1, dtype=torch.int32, device="cuda")
     cuts = sorted(set(U[1:] + [G]))
     Z = {u: torch.empty((E, E, u), dtype=torch.int32, device="cuda") for u in cuts}
-    ws = {u: torch.empty(int(B.lib().hm_swap_workspace_bytes(E, u)) // 4 + 4, dtype=torch.int32, device="cuda") for u in cuts}
+    ws = {u: torch.empty(int(B.lib().hm_swap_workspace_bytes(T, K, E, u)) // 4 + 4, dtype=torch.int32, device="cuda") for u in cuts}
     ws_multi = None
     if not args.separate_cuts:
         import ctypes
         nga = (ctypes.c_int32 * len(cuts))(*cuts)
-        ws_multi = torch.empty(int(B.lib().hm_swap_multi_workspace_bytes(E, G, len(cuts), nga)) // 4 + 4,
+        ws_multi = torch.empty(int(B.lib().hm_swap_multi_workspace_bytes(T, K, E, G, len(cuts), nga)) // 4 + 4,
                                dtype=torch.int32, device="cuda")
     Q = torch.empty((E, E), dtype=torch.float64, device="cuda")
     bp = torch.zeros(2, dtype=torch.int32, device="cuda")

@@ -350,9 +350,10 @@ hm_status hm_alltoall_times(int32_t D, const int32_t *U /* host */, int32_t G, d
  * selected expert of its group and r is not selected}  for c's group (and symmetrically).
  * A pair in which either expert's placement entry is outside [0,G) keeps the unswapped counts;
  * invalid slots are ignored; both set *status (optional device int32[1]) to HM_ERR_BAD_ID.
- * workspace: hm_swap_workspace_bytes(E, ng) bytes of device scratch.
+ * workspace: hm_swap_workspace_bytes(T, K, E, ng) bytes of device scratch (0 for arguments out of
+ * range).
  */
-size_t hm_swap_workspace_bytes(int32_t E, int32_t ng);
+size_t hm_swap_workspace_bytes(int32_t T, int32_t K, int32_t E, int32_t ng);
 hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
                          int32_t G, int32_t ng, int32_t *Z, int32_t *status, void *workspace, size_t workspace_bytes,
                          void *hip_stream);
@@ -363,9 +364,10 @@ hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expert_to_rank,
  * array of ncuts group counts, each dividing G) and Z (host array of ncuts device pointers,
  * Z[c] = int32 [E*E*ng[c]]).  Results, status and error rules are those of ncuts separate
  * hm_swap_counts calls; the work that does not depend on the cut is done once.
- * workspace: hm_swap_multi_workspace_bytes(E, G, ncuts, ng) bytes of device scratch.
+ * workspace: hm_swap_multi_workspace_bytes(T, K, E, G, ncuts, ng) bytes of device scratch.
  */
-size_t hm_swap_multi_workspace_bytes(int32_t E, int32_t G, int32_t ncuts, const int32_t *ng /* host */);
+size_t hm_swap_multi_workspace_bytes(int32_t T, int32_t K, int32_t E, int32_t G, int32_t ncuts,
+                                     const int32_t *ng /* host */);
 hm_status hm_swap_counts_multi(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
                                int32_t G, int32_t ncuts, const int32_t *ng /* host */,
                                int32_t *const *Z /* host array of device pointers */, int32_t *status, void *workspace,

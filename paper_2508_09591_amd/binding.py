@@ -84,7 +84,7 @@ def lib():
         L.hm_combine_launch_shape.argtypes = [i32, i32, i32, ctypes.POINTER(hm_plan_out), i32, ctypes.POINTER(i32),
                                               ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.hm_swap_multi_workspace_bytes.restype = ctypes.c_size_t
-        L.hm_swap_multi_workspace_bytes.argtypes = [i32, i32, i32, vp]
+        L.hm_swap_multi_workspace_bytes.argtypes = [i32, i32, i32, i32, i32, vp]
         L.hm_swap_counts_multi.restype = ctypes.c_int
         L.hm_swap_counts_multi.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.hm_swap_apply.restype = ctypes.c_int
@@ -113,7 +113,7 @@ def lib():
         L.hm_alltoall_times.argtypes = [i32, ctypes.POINTER(i32), i32, ctypes.c_double, ctypes.c_double, vp, vp,
                                         dp, dp, dp, dp, vp, vp, vp]
         L.hm_swap_workspace_bytes.restype = ctypes.c_size_t
-        L.hm_swap_workspace_bytes.argtypes = [i32, i32]
+        L.hm_swap_workspace_bytes.argtypes = [i32, i32, i32, i32]
         L.hm_swap_counts.restype = ctypes.c_int
         L.hm_swap_counts.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp]
         L.hm_swap_select_workspace_bytes.restype = ctypes.c_size_t
@@ -416,7 +416,7 @@ def hm_swap_counts(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, G: int,
     """Z: int32 [E,E,ng] on the GPU."""
     T, K = topk_ids.shape
     E = expert_to_rank.shape[0]
-    need = int(lib().hm_swap_workspace_bytes(E, ng))
+    need = int(lib().hm_swap_workspace_bytes(T, K, E, ng))
     if workspace is None:
         workspace = torch.empty(need // 4 + 4, dtype=torch.int32, device=Z.device)
     rc = lib().hm_swap_counts(_dev(topk_ids, torch.int32, "topk_ids"), _dev(expert_to_rank, torch.int32, "expert_to_rank"),
@@ -436,7 +436,7 @@ def hm_swap_counts_multi(topk_ids: torch.Tensor, expert_to_rank: torch.Tensor, G
         raise ValueError("one Z tensor per cut")
     nga = (ctypes.c_int32 * n)(*[int(u) for u in ng])
     zp = (ctypes.c_void_p * n)(*[_dev(z, torch.int32, "Z") for z in Z])
-    need = int(lib().hm_swap_multi_workspace_bytes(E, G, n, nga))
+    need = int(lib().hm_swap_multi_workspace_bytes(T, K, E, G, n, nga))
     if workspace is None:
         workspace = torch.empty(need // 4 + 4, dtype=torch.int32, device=Z[0].device)
     rc = lib().hm_swap_counts_multi(_dev(topk_ids, torch.int32, "topk_ids"), _dev(expert_to_rank, torch.int32, "expert_to_rank"),

@@ -173,6 +173,326 @@ __global__ __launch_bounds__(kFactorThreads) void swap_factors_kernel(SwapParams
       if (lds[i]) atomicAdd(&p.L0[i], lds[i]);
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same tables as contractions over the tokens (E <= 256).
+//
+// With S[t][a] = 1 when token t selects expert a, A[t][a] = 1 when a is moreover the only selected
+// expert of its group, and M[t][g] = 1 when t selects something in group g (all 0/1 bytes):
+//   C  = A^T S   (its diagonal is L)        CG = S^T M   (L0[a] = CG[a][group of a])
+// so the read-modify-write updates of popular expert pairs, which serialise on one address, become
+// int8 matrix products with int32 accumulators held in registers.  A first kernel, one lane per
+// routing slot over the whole chip, works out what only the token's other slots can tell (is this
+// the first occurrence of the expert, is it alone in its group under each cut) and leaves one byte
+// per slot.  In the second a workgroup takes one cut and a contiguous chunk of the tokens, builds
+// the three indicator tiles for 128 tokens at a time in LDS (expert-major, so that a lane's MFMA
+// operand is 16 contiguous bytes), and stores its partial tables with plain stores; a third kernel
+// sums the chunks.  No table is touched by an atomic.
+// ---------------------------------------------------------------------------------------------
+constexpr int kCoocThreads = 1024;
+constexpr int kCoocWaves = kCoocThreads / kWave;
+constexpr int kCoocTokens = 128;     // tokens per tile: four k-steps of the 32x32x32 int8 MFMA
+constexpr int kCoocStride = 144;     // bytes per tile row: 128 tokens + 16, which spreads 32 rows over all banks
+constexpr int kCoocGroups = 64;      // rows of the group tile
+constexpr int kCoocChunksMax = 16;   // partial tables per cut
+constexpr int kCoocMaxE = 256;
+constexpr int kCoocStaged = 8;       // passes whose slots are fetched together (16 KiB of LDS)
+constexpr int kCoocTokensPerChunkMin = 512;   // below this a chunk is not worth a workgroup of its own
+
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x16 __attribute__((ext_vector_type(16)));
+
+struct CoocParams {
+  const int32_t *ids;
+  const int32_t *expert_to_rank;
+  int32_t T, K, E, G;
+  int32_t sub_log2;            // lanes per token: 2^sub_log2 >= K
+  int32_t ncuts;
+  int32_t chunks;              // gridDim.x of the matrix kernel
+  int32_t tokens_per_chunk;    // a multiple of kCoocTokens
+  int32_t ng[kMaxCuts], per[kMaxCuts];
+  uint8_t *slot_bits;          // [T * K]: bit 0 first valid occurrence, bit 1 + c alone in its group under cut c
+  int32_t *part[kMaxCuts];     // [chunks][E*E + E*ng + 64]: C, CG and base of one chunk
+  int32_t *status;
+};
+
+__host__ __device__ static inline int64_t cooc_part_ints(int64_t E, int64_t ng) { return E * E + E * ng + 64; }
+
+// One lane per routing slot; the K slots of a token sit in 2^sub_log2 consecutive lanes and learn
+// about each other through shuffles, eight in flight at a time.
+__global__ __launch_bounds__(kSwapThreads) void swap_slots_kernel(CoocParams p) {
+  const int sub = 1 << p.sub_log2;
+  const int lane = lane_id();
+  const int k = lane & (sub - 1);
+  const int sub0 = lane & ~(sub - 1);
+  const int64_t t = ((int64_t)blockIdx.x * kSwapThreads + threadIdx.x) >> p.sub_log2;
+  const bool live = t < p.T && k < p.K;
+  int a = -1, r = -1;   // my expert and its rank; -1 when the slot is empty, dropped or invalid
+  if (live) {
+    const int id = p.ids[t * p.K + k];
+    const int rk = rank_of(p.expert_to_rank, p.E, p.G, id);
+    if (rk == -1) flag(p.status, HM_ERR_BAD_ID);
+    if (rk >= 0) {
+      a = id;
+      r = rk;
+    }
+  }
+  bool first = a >= 0;   // the selected experts form a set: the first occurrence stands for it
+  for (int k0 = 0; k0 < p.K; k0 += 8) {
+    int a1[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) a1[j] = __shfl(a, sub0 + ((k0 + j) & (sub - 1)), kWave);
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (k0 + j < k && a1[j] == a) first = false;
+  }
+  // The group of my rank under each cut, one byte per cut; equal bytes of two such words are counted
+  // four cuts at a time (a zero byte of the exclusive or, found without a carry between bytes).
+  __shared__ uint32_t groups_of_rank[kWave];
+  if (threadIdx.x < kWave) {
+    uint32_t packed = 0;
+#pragma unroll
+    for (int c = 0; c < kMaxCuts; ++c) packed |= (uint32_t)(threadIdx.x / p.per[c]) << (8 * c);
+    groups_of_rank[threadIdx.x] = packed;
+  }
+  __syncthreads();
+  const uint32_t pg = r >= 0 ? groups_of_rank[r] : 0u;
+  const uint32_t mine = first ? pg : 0xFFFFFFFFu;   // no group has the number 255
+  uint32_t in_group = 0;   // distinct selected experts in my expert's group, one byte per cut (at most 64)
+  for (int k0 = 0; k0 < p.K; k0 += 8) {
+    uint32_t g1[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) g1[j] = (uint32_t)__shfl((int)mine, sub0 + ((k0 + j) & (sub - 1)), kWave);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t x = g1[j] ^ pg;
+      const uint32_t nonzero = (((x & 0x7F7F7F7Fu) + 0x7F7F7F7Fu) | x) & 0x80808080u;
+      if (k0 + j < p.K) in_group += (nonzero ^ 0x80808080u) >> 7;
+    }
+  }
+  if (live) {
+    int bits = 0;
+    if (first) {
+      bits = 1;
+#pragma unroll
+      for (int c = 0; c < kMaxCuts; ++c)
+        if (c < p.ncuts && ((in_group >> (8 * c)) & 0xFFu) == 1u) bits |= 2 << c;
+    }
+    p.slot_bits[t * p.K + k] = (uint8_t)bits;
+  }
+}
+
+// D += A B for one 32x32 tile over 32 tokens; a lane's operand: 16 token bytes of row (lane % 32).
+__device__ __forceinline__ i32x16 mfma_i8(i32x4 a, i32x4 b, i32x16 acc) {
+  return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc, 0, 0, 0);
+}
+
+// Workgroup (chunk, cut, panel).  Every wave holds one 32x32 tile of C, so a workgroup covers 16 of
+// them: all of C for E <= 128, and for E <= 256 one of four panels of two tile columns (the panels
+// repeat the cheap filling of the tiles and split the products, which is what E = 256 is bound by).
+template <int NE>   // experts padded to 32 * NE
+__global__ __launch_bounds__(kCoocThreads) void swap_cooc_kernel(CoocParams p) {
+  constexpr int kPanels = NE * NE > kCoocWaves ? NE * NE / kCoocWaves : 1;   // gridDim.z
+  constexpr int kCols = NE / kPanels;                                         // tile columns of a panel
+  constexpr int kVecs = (2 * 32 * NE + kCoocGroups) * kCoocStride / 16;
+  extern __shared__ __align__(16) uint8_t tiles[];
+  uint8_t *const s_tile = tiles;                                        // [32 NE][stride]  S
+  uint8_t *const a_tile = s_tile + 32 * NE * kCoocStride;               // [32 NE][stride]  A
+  uint8_t *const m_tile = a_tile + 32 * NE * kCoocStride;               // [64][stride]     M
+  __shared__ uint8_t group_of_expert[32 * NE];
+  __shared__ uint16_t staged[kCoocStaged][kCoocThreads];
+
+  const int cut = blockIdx.y, panel = blockIdx.z;
+  const int ng = p.ng[cut], per = p.per[cut];
+  const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+  {
+    i32x4 *z = (i32x4 *)tiles;
+    for (int i = tid; i < kVecs; i += kCoocThreads) z[i] = i32x4{0, 0, 0, 0};
+    if (tid < 32 * NE) {
+      int g = 0;   // an expert with no valid placement is never marked first, so its entry is not read
+      if (tid < p.E) {
+        const int r = p.expert_to_rank[tid];
+        if ((unsigned)r < (unsigned)p.G) g = r / per;
+      }
+      group_of_expert[tid] = (uint8_t)g;
+    }
+  }
+  __syncthreads();
+
+  // A pass: every lane looks at one routing slot, 2^sub_log2 lanes per token.  A tile takes `passes`
+  // passes; kCoocStaged passes are fetched at a time, so that the latency of global memory is paid
+  // once per kCoocStaged passes and not once per tile.
+  const int sub = 1 << p.sub_log2;
+  const int k = min(tid & (sub - 1), p.K - 1);                        // my slot in the token (clamped: see `mine`)
+  const int tp1 = tid >> p.sub_log2;                                  // my token within a pass
+  const int tok_pass = min(kCoocThreads >> p.sub_log2, kCoocTokens);  // tokens one pass covers
+  const int passes = kCoocTokens / tok_pass;
+  const bool mine = tp1 < tok_pass && (tid & (sub - 1)) < p.K;
+  const int alone_bit = 2 << cut;
+  const int64_t t_begin = (int64_t)blockIdx.x * p.tokens_per_chunk;
+  const int64_t t_end = min((int64_t)p.T, t_begin + p.tokens_per_chunk);
+
+  // What this wave accumulates: one tile of C and, counted from the last wave down and dealt round
+  // the panels, at most one tile of CG.
+  const bool has_c = w < NE * kCols;
+  const int c_row = has_c ? w / kCols : 0, c_col = has_c ? panel * kCols + w % kCols : 0;
+  const int ngt = (ng + 31) / 32;
+  const int g_job = (kCoocWaves - 1 - w) * kPanels + panel;
+  const bool has_g = g_job < NE * ngt;
+  const int g_row = has_g ? g_job / ngt : 0, g_col = has_g ? g_job % ngt : 0;
+  const bool counts_base = panel == 0 && w == kCoocWaves / 2;   // lane g: tokens of this chunk that touch group g
+  i32x16 acc, acc_g;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = acc_g[r] = 0;
+  int my_base = 0;
+
+  const int op_at = (lane & 31) * kCoocStride + (lane >> 5) * 16;
+  const uint8_t *const c_a = a_tile + 32 * c_row * kCoocStride + op_at;
+  const uint8_t *const c_b = s_tile + 32 * c_col * kCoocStride + op_at;
+  const uint8_t *const g_a = s_tile + 32 * g_row * kCoocStride + op_at;
+  const uint8_t *const g_b = m_tile + 32 * g_col * kCoocStride + op_at;
+
+  for (int64_t stage0 = t_begin; stage0 < t_end; stage0 += (int64_t)kCoocStaged * tok_pass) {
+    // My slots of the next kCoocStaged passes: expert | bits << 8, 0 for a slot that marks nothing.
+    // The loads are unconditional (clamped to the chunk) so that all of them are in flight at once.
+    // A lane reads back only what it wrote itself, so this needs no barrier.
+    {
+      int id[kCoocStaged], bits[kCoocStaged];
+#pragma unroll
+      for (int j = 0; j < kCoocStaged; ++j) {
+        const int64_t t = min(stage0 + (int64_t)j * tok_pass + tp1, t_end - 1);
+        id[j] = p.ids[t * p.K + k];
+        bits[j] = p.slot_bits[t * p.K + k];
+      }
+#pragma unroll
+      for (int j = 0; j < kCoocStaged; ++j) {
+        const bool in = mine && stage0 + (int64_t)j * tok_pass + tp1 < t_end && (bits[j] & 1);
+        staged[j][tid] = (uint16_t)(in ? ((id[j] & 0xFF) | (bits[j] << 8)) : 0);
+      }
+    }
+    int entry = staged[0][tid];
+    int group_row = group_of_expert[entry & 0xFF] * kCoocStride;
+    for (int tile = 0; tile < kCoocStaged / passes && stage0 + (int64_t)tile * kCoocTokens < t_end; ++tile) {
+      int wrote_s = -1, wrote_a = -1, wrote_m = -1;   // LDS offsets to clear again
+      for (int pass = 0; pass < passes; ++pass) {
+        const int tp = pass * tok_pass + tp1;
+        if (entry) {   // a valid expert with a valid placement, first time in this token
+          wrote_s = (entry & 0xFF) * kCoocStride + tp;
+          wrote_m = group_row + tp;
+          s_tile[wrote_s] = 1;
+          m_tile[wrote_m] = 1;
+          if ((entry >> 8) & alone_bit) {
+            wrote_a = wrote_s;
+            a_tile[wrote_a] = 1;
+          }
+        }
+        // the next pass's entry and its group: fetched here, off the path between the barriers
+        const int next = tile * passes + pass + 1;
+        entry = next < kCoocStaged ? staged[next][tid] : 0;
+        group_row = group_of_expert[entry & 0xFF] * kCoocStride;
+      }
+      __syncthreads();
+
+      {
+        i32x4 a_op[kCoocTokens / 32], b_op[kCoocTokens / 32];
+#pragma unroll
+        for (int step = 0; step < kCoocTokens / 32; ++step) {
+          a_op[step] = *(const i32x4 *)(c_a + 32 * step);
+          b_op[step] = *(const i32x4 *)(c_b + 32 * step);
+        }
+#pragma unroll
+        for (int step = 0; step < kCoocTokens / 32; ++step) acc = mfma_i8(a_op[step], b_op[step], acc);
+      }
+      if (has_g) {
+        i32x4 a_op[kCoocTokens / 32], b_op[kCoocTokens / 32];
+#pragma unroll
+        for (int step = 0; step < kCoocTokens / 32; ++step) {
+          a_op[step] = *(const i32x4 *)(g_a + 32 * step);
+          b_op[step] = *(const i32x4 *)(g_b + 32 * step);
+        }
+#pragma unroll
+        for (int step = 0; step < kCoocTokens / 32; ++step) acc_g = mfma_i8(a_op[step], b_op[step], acc_g);
+      }
+      if (counts_base) {   // bytes are 0 / 1, so a word's population count is its number of tokens
+        const i32x4 *row = (const i32x4 *)(m_tile + lane * kCoocStride);
+#pragma unroll
+        for (int i = 0; i < kCoocTokens / 16; ++i) {
+          const i32x4 v = row[i];
+          my_base += __popc(v[0]) + __popc(v[1]) + __popc(v[2]) + __popc(v[3]);
+        }
+      }
+      __syncthreads();
+
+      // Leave the tiles clean for the next 128 tokens.  A token's column is written by the lanes of
+      // one wave only, so clearing it and filling it again need no barrier in between.
+      if (passes == 1) {
+        if (wrote_s >= 0) {
+          s_tile[wrote_s] = 0;
+          m_tile[wrote_m] = 0;
+          if (wrote_a >= 0) a_tile[wrote_a] = 0;
+        }
+      } else {
+        i32x4 *z = (i32x4 *)tiles;
+        for (int i = tid; i < kVecs; i += kCoocThreads) z[i] = i32x4{0, 0, 0, 0};
+        __syncthreads();
+      }
+    }
+  }
+
+  // Accumulator layout of a 32x32 tile: register r of lane l holds row 8 (r / 4) + 4 (l / 32) + r % 4,
+  // column l % 32.
+  int32_t *const part = p.part[cut] + (int64_t)blockIdx.x * cooc_part_ints(p.E, ng);
+  int32_t *const part_c = part, *const part_cg = part + (int64_t)p.E * p.E, *const part_base = part_cg + (int64_t)p.E * ng;
+  const int col = lane & 31, row_hi = (lane >> 5) * 4;
+  if (has_c) {
+    const int b = 32 * c_col + col;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int a = 32 * c_row + 8 * (r / 4) + row_hi + (r % 4);
+      if (a < p.E && b < p.E) part_c[(int64_t)a * p.E + b] = acc[r];
+    }
+  }
+  if (has_g) {
+    const int g = 32 * g_col + col;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int a = 32 * g_row + 8 * (r / 4) + row_hi + (r % 4);
+      if (a < p.E && g < ng) part_cg[(int64_t)a * ng + g] = acc_g[r];
+    }
+  }
+  if (counts_base) part_base[lane] = my_base;
+}
+
+// Sums the chunks' partial tables into the tables swap_build_kernel reads; blockIdx.y is the cut.
+// L is the diagonal of C and L0[a] the entry of CG in a's own group (every token that selects a
+// selects something there), so neither needs a table of its own upstream.
+__global__ __launch_bounds__(kSwapThreads) void swap_reduce_kernel(SwapParams p, CoocParams cp) {
+  const int cut = blockIdx.y;
+  const int ng = p.ng[cut];
+  const int64_t n = cooc_part_ints(p.E, ng);
+  const int64_t i = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
+  if (i >= n) return;
+  int sum = 0;
+#pragma unroll
+  for (int c = 0; c < kCoocChunksMax; ++c)
+    if (c < cp.chunks) sum += cp.part[cut][c * n + i];
+  const int64_t ee = (int64_t)p.E * p.E;
+  if (i < ee) {
+    p.C[cut][i] = sum;
+    const int a = (int)(i / p.E);
+    if (i % p.E == a) p.L[cut][a] = sum;
+  } else if (i < ee + (int64_t)p.E * ng) {
+    const int64_t j = i - ee;
+    p.CG[cut][j] = sum;
+    if (cut == 0) {
+      const int a = (int)(j / ng), g = (int)(j % ng);
+      const int r = p.expert_to_rank[a];
+      if ((unsigned)r < (unsigned)p.G ? r / p.per[0] == g : g == 0) p.L0[a] = (unsigned)r < (unsigned)p.G ? sum : 0;
+    }
+  } else {
+    p.base[cut][i - ee - (int64_t)p.E * ng] = sum;
+  }
+}
+
 // One lane per element of Z; blockIdx.y is the cut.
 __global__ __launch_bounds__(kSwapThreads) void swap_build_kernel(SwapParams p) {
   const int cut = blockIdx.y;
@@ -343,16 +663,42 @@ static bool swap_factors_lds_ready() {
   return ok;
 }
 
-// Private copies of C: as many as fit 2 MiB per cut, at most kSwapCopiesMax (32 for E <= 128, 8 for
-// E = 256): more copies spread the atomics of popular pairs, but each is cleared and summed again.
+// Private copies of C on the path with atomics: as many as fit 2 MiB per cut, at most
+// kSwapCopiesMax (32 for E <= 128, 8 for E = 256): more copies spread the atomics of popular pairs,
+// but each is cleared and summed again.  The matrix path keeps one summed C.
+static inline bool swap_by_matrices(int64_t E) { return E <= kCoocMaxE; }
 static inline int64_t swap_copies(int64_t E) {
+  if (swap_by_matrices(E)) return 1;
   int64_t n = kSwapCopiesMax;   // a power of two, so that a workgroup finds its copy with a mask
   while (n > 1 && n * E * E > (int64_t)(1 << 19)) n /= 2;
   return n;
 }
 
-// Workspace, in ints: L0 [E], then per cut base [64] | L [E] | CG [E * ng] | C [copies * E * E].
-static inline int64_t swap_cut_ints(int64_t E, int64_t ng) { return 64 + E + E * ng + swap_copies(E) * E * E; }
+// Workspace, in ints: L0 [E], then per cut base [64] | L [E] | CG [E * ng] | C [copies * E * E], and on the
+// matrix path the partial tables of kCoocChunksMax chunks after that.
+static inline int64_t swap_cut_ints(int64_t E, int64_t ng) {
+  return 64 + E + E * ng + swap_copies(E) * E * E + (swap_by_matrices(E) ? kCoocChunksMax * cooc_part_ints(E, ng) : 0);
+}
+// ... and, on the matrix path, one byte per routing slot at the very end.
+static inline int64_t swap_slot_ints(int64_t T, int64_t K, int64_t E) { return swap_by_matrices(E) ? (T * K + 3) / 4 : 0; }
+
+// The matrix kernel for E experts, its dynamic LDS, and whether the device grants that much.
+typedef void (*cooc_kernel_t)(CoocParams);
+static inline cooc_kernel_t cooc_kernel(int E, size_t *lds_bytes) {
+  const int ne = E <= 32 ? 1 : E <= 64 ? 2 : E <= 128 ? 4 : 8;
+  *lds_bytes = (size_t)(2 * 32 * ne + kCoocGroups) * kCoocStride;
+  return ne == 1 ? swap_cooc_kernel<1> : ne == 2 ? swap_cooc_kernel<2> : ne == 4 ? swap_cooc_kernel<4> : swap_cooc_kernel<8>;
+}
+static bool cooc_lds_ready() {
+  static const bool ok = [] {
+    size_t bytes = 0;
+    const cooc_kernel_t k = cooc_kernel(kCoocMaxE, &bytes);   // only the largest needs more than the default
+    const hipError_t e = hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) (void)hipGetLastError();
+    return e == hipSuccess;
+  }();
+  return ok;
+}
 
 static inline bool swap_cuts_ok(int32_t G, int32_t ncuts, const int32_t *ng) {
   if (G < 1 || G > 64 || ncuts < 1 || ncuts > kMaxCuts || !ng) return false;
@@ -400,19 +746,65 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
       p.lds_off[c] = p.lds_off[0];
     }
   }
-  p.ws_ints = at;
-  p.use_lds = (lds_at <= kSwapLds && swap_factors_lds_ready()) ? 1 : 0;
   p.status = status;
-  hipLaunchKernelGGL(swap_clear_kernel, dim3((unsigned)((p.ws_ints + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads),
-                     0, stream, p);
-  if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
-  if (T > 0) {
-    const int64_t tokens_per_block = (int64_t)(kFactorThreads / kWave) * (kWave / p.sub);
-    int64_t blocks = ((int64_t)T + tokens_per_block - 1) / tokens_per_block;
-    if (blocks > 256) blocks = 256;   // one per CU; every block flushes its LDS tables with atomics
-    hipLaunchKernelGGL(swap_factors_kernel, dim3((unsigned)blocks), dim3(kFactorThreads),
-                       p.use_lds ? (size_t)lds_at * sizeof(int32_t) : 0, stream, p);
+  size_t cooc_lds = 0;
+  const cooc_kernel_t cooc = swap_by_matrices(E) ? cooc_kernel(E, &cooc_lds) : nullptr;
+  if (cooc && (cooc_lds <= 65536 || cooc_lds_ready())) {
+    // Every table is written in full by the kernels below: only the status word needs clearing.
+    p.ws_ints = 0;
+    p.use_lds = 0;
+    hipLaunchKernelGGL(swap_clear_kernel, dim3(1), dim3(kSwapThreads), 0, stream, p);
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+    CoocParams cp;
+    cp.ids = topk_ids;
+    cp.expert_to_rank = expert_to_rank;
+    cp.T = T;
+    cp.K = K;
+    cp.E = E;
+    cp.G = G;
+    cp.sub_log2 = 0;
+    while ((1 << cp.sub_log2) < K) ++cp.sub_log2;
+    cp.ncuts = ncuts;
+    cp.slot_bits = (uint8_t *)(p.ws + at);
+    int64_t chunks = ((int64_t)T + kCoocTokensPerChunkMin - 1) / kCoocTokensPerChunkMin;
+    chunks = chunks < 1 ? 1 : chunks > kCoocChunksMax ? kCoocChunksMax : chunks;
+    const int64_t per_chunk = ((int64_t)T + chunks - 1) / chunks;
+    cp.chunks = (int32_t)chunks;
+    cp.tokens_per_chunk = (int32_t)((per_chunk + kCoocTokens - 1) / kCoocTokens * kCoocTokens);
+    if (cp.tokens_per_chunk < kCoocTokens) cp.tokens_per_chunk = kCoocTokens;
+    int64_t max_part = 0;
+    for (int c = 0; c < kMaxCuts; ++c) {
+      cp.ng[c] = p.ng[c];
+      cp.per[c] = p.per[c];
+      cp.part[c] = p.C[c] + (int64_t)E * E;   // behind the summed C of the cut
+      if (c < ncuts && cooc_part_ints(E, ng[c]) > max_part) max_part = cooc_part_ints(E, ng[c]);
+    }
+    cp.status = status;
+    if (T > 0) {
+      const int64_t lanes = (int64_t)T << cp.sub_log2;
+      hipLaunchKernelGGL(swap_slots_kernel, dim3((unsigned)((lanes + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads), 0,
+                         stream, cp);
+      if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+    }
+    hipLaunchKernelGGL(cooc, dim3((unsigned)chunks, (unsigned)ncuts, E > 128 ? 4u : 1u), dim3(kCoocThreads), cooc_lds, stream, cp);
+    if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+    hipLaunchKernelGGL(swap_reduce_kernel, dim3((unsigned)((max_part + kSwapThreads - 1) / kSwapThreads), (unsigned)ncuts),
+                       dim3(kSwapThreads), 0, stream, p, cp);
+    if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+  } else {
+    p.ws_ints = at;
+    p.use_lds = (lds_at <= kSwapLds && swap_factors_lds_ready()) ? 1 : 0;
+    hipLaunchKernelGGL(swap_clear_kernel, dim3((unsigned)((p.ws_ints + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads),
+                       0, stream, p);
+    if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+    if (T > 0) {
+      const int64_t tokens_per_block = (int64_t)(kFactorThreads / kWave) * (kWave / p.sub);
+      int64_t blocks = ((int64_t)T + tokens_per_block - 1) / tokens_per_block;
+      if (blocks > 256) blocks = 256;   // one per CU; every block flushes its LDS tables with atomics
+      hipLaunchKernelGGL(swap_factors_kernel, dim3((unsigned)blocks), dim3(kFactorThreads),
+                         p.use_lds ? (size_t)lds_at * sizeof(int32_t) : 0, stream, p);
+      if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
+    }
   }
   const int64_t total = (int64_t)E * E * max_ng;
   hipLaunchKernelGGL(swap_build_kernel, dim3((unsigned)((total + kSwapThreads - 1) / kSwapThreads), (unsigned)ncuts),
@@ -422,16 +814,16 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
 
 }  // namespace hm
 
-extern "C" size_t hm_swap_multi_workspace_bytes(int32_t E, int32_t G, int32_t ncuts, const int32_t *ng) {
-  if (E < 1 || !hm::swap_cuts_ok(G, ncuts, ng)) return 0;
-  int64_t ints = E;
+extern "C" size_t hm_swap_multi_workspace_bytes(int32_t T, int32_t K, int32_t E, int32_t G, int32_t ncuts, const int32_t *ng) {
+  if (E < 1 || T < 0 || K < 1 || !hm::swap_cuts_ok(G, ncuts, ng)) return 0;
+  int64_t ints = E + hm::swap_slot_ints(T, K, E);
   for (int c = 0; c < ncuts; ++c) ints += hm::swap_cut_ints(E, ng[c]);
   return (size_t)ints * sizeof(int32_t);
 }
 
-extern "C" size_t hm_swap_workspace_bytes(int32_t E, int32_t ng) {
-  if (E < 1 || ng < 1 || ng > 64) return 0;
-  return (size_t)(E + hm::swap_cut_ints(E, ng)) * sizeof(int32_t);
+extern "C" size_t hm_swap_workspace_bytes(int32_t T, int32_t K, int32_t E, int32_t ng) {
+  if (E < 1 || T < 0 || K < 1 || ng < 1 || ng > 64) return 0;
+  return (size_t)(E + hm::swap_cut_ints(E, ng) + hm::swap_slot_ints(T, K, E)) * sizeof(int32_t);
 }
 
 static hm_status swap_counts_checks(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,
@@ -452,7 +844,7 @@ extern "C" hm_status hm_swap_counts(const int32_t *topk_ids, const int32_t *expe
   hm_status st = swap_counts_checks(topk_ids, expert_to_rank, T, K, E, workspace);
   if (st != HM_OK) return st;
   if (!hm::swap_cuts_ok(G, 1, &ng)) return HM_ERR_TOPOLOGY;
-  if (workspace_bytes < hm_swap_workspace_bytes(E, ng)) return HM_ERR_WORKSPACE;
+  if (workspace_bytes < hm_swap_workspace_bytes(T, K, E, ng)) return HM_ERR_WORKSPACE;
   return hm::swap_counts_launch(topk_ids, expert_to_rank, T, K, E, G, 1, &ng, &Z, status, workspace, (hipStream_t)hip_stream);
 }
 
@@ -466,7 +858,7 @@ extern "C" hm_status hm_swap_counts_multi(const int32_t *topk_ids, const int32_t
   if (!hm::swap_cuts_ok(G, ncuts, ng)) return HM_ERR_TOPOLOGY;
   for (int c = 0; c < ncuts; ++c)
     if (!Z[c]) return HM_ERR_NULL;
-  if (workspace_bytes < hm_swap_multi_workspace_bytes(E, G, ncuts, ng)) return HM_ERR_WORKSPACE;
+  if (workspace_bytes < hm_swap_multi_workspace_bytes(T, K, E, G, ncuts, ng)) return HM_ERR_WORKSPACE;
   return hm::swap_counts_launch(topk_ids, expert_to_rank, T, K, E, G, ncuts, ng, Z, status, workspace, (hipStream_t)hip_stream);
 }
 
