@@ -13,7 +13,8 @@
 namespace hm {
 
 constexpr int kSwapThreads = 256;
-constexpr int kSelectThreads = 64;     // Q per pair: fp64 pow-heavy, so many small workgroups to reach every CU
+constexpr int kSelectThreads = 256;    // Q per pair: fp64 pow-heavy, one lane per term of Eq.(8)
+constexpr int kPairLanes = 4, kSelectPairs = kSelectThreads / kPairLanes;
 constexpr int kFactorThreads = 1024;   // the co-occurrence pass: 16 waves share one set of LDS tables
 constexpr int kSwapLds = 30720;   // most ints of LDS for L0 and every cut's L + CG (120 KiB); larger sets stay in global memory
 constexpr int kSwapCopiesMax = 32;   // private copies of C: popular expert pairs would otherwise serialise on one address
@@ -30,12 +31,18 @@ struct SwapParams {
   int32_t use_lds;  // L0 / L / CG of all cuts accumulate in LDS
   int32_t copies;   // private copies of each C
   int32_t ng[kMaxCuts], per[kMaxCuts];
+  uint32_t ng_reciprocal[kMaxCuts];   // ceil(2^32 / ng), for the division by ng in swap_build_kernel (unused when ng = 1)
+  uint32_t per_reciprocal[kMaxCuts];  // ceil(2^32 / per), 0 when per = 1
+  int32_t build_blocks[kMaxCuts];     // column blocks of swap_build_kernel per cut
   int32_t lds_off[kMaxCuts];   // ints: where cut c's [L (E) | CG (E * ng)] starts in LDS; L0 is at 0
   int32_t *L0;                 // [E]                                  (workspace, shared by the cuts)
   int32_t *base[kMaxCuts];     // [64]                                 (workspace, per cut)
   int32_t *L[kMaxCuts];        // [E]
   int32_t *CG[kMaxCuts];       // [E][ng]
   int32_t *C[kMaxCuts];        // [copies][E][E]
+  int32_t *CT[kMaxCuts];       // [E][E]   C transposed   } matrix path only: swap_build_kernel then reads
+  int32_t *CGT[kMaxCuts];      // [ng][E]  CG transposed  } along rows whichever expert of a pair a lane needs
+  int32_t transposed;
   int32_t *Z[kMaxCuts];
   int32_t *ws;                 // start of the workspace and its size in ints (cleared first)
   int64_t ws_ints;
@@ -478,11 +485,13 @@ __global__ __launch_bounds__(kSwapThreads) void swap_reduce_kernel(SwapParams p,
   const int64_t ee = (int64_t)p.E * p.E;
   if (i < ee) {
     p.C[cut][i] = sum;
-    const int a = (int)(i / p.E);
-    if (i % p.E == a) p.L[cut][a] = sum;
+    const int a = (int)(i / p.E), b = (int)(i % p.E);
+    p.CT[cut][(int64_t)b * p.E + a] = sum;
+    if (b == a) p.L[cut][a] = sum;
   } else if (i < ee + (int64_t)p.E * ng) {
     const int64_t j = i - ee;
     p.CG[cut][j] = sum;
+    p.CGT[cut][(j % ng) * p.E + j / ng] = sum;
     if (cut == 0) {
       const int a = (int)(j / ng), g = (int)(j % ng);
       const int r = p.expert_to_rank[a];
@@ -493,32 +502,63 @@ __global__ __launch_bounds__(kSwapThreads) void swap_reduce_kernel(SwapParams p,
   }
 }
 
-// One lane per element of Z; blockIdx.y is the cut.
+// One lane per (c, j) of a cut and kBuildRows row experts r: blockIdx.y is the block of rows and
+// blockIdx.x runs over the column blocks (256 consecutive (c, j)) of all cuts, one cut after the
+// other.  The loads of all rows are issued before the first value is put together, so a lane
+// waits for memory once, and the waves are long enough for the chip not to be bound by starting
+// them.  The two divisions a lane needs are multiplications by rounded-up reciprocals: c = l / ng
+// (exact for l < 2^32 / ng, and l < 64 E < 2^19) and group = rank / per (rank < 64).
+constexpr int kBuildRows = 4;
 __global__ __launch_bounds__(kSwapThreads) void swap_build_kernel(SwapParams p) {
-  const int cut = blockIdx.y;
-  const int ng = p.ng[cut], per = p.per[cut];
-  const int64_t i = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
-  const int64_t total = (int64_t)p.E * p.E * ng;
-  if (i >= total) return;
-  const int j = (int)(i % ng);
-  const int64_t rc = i / ng;
-  const int r = (int)(rc / p.E), c = (int)(rc % p.E);
-  int val = p.base[cut][j];
-  const int rr = p.expert_to_rank[r], rk = p.expert_to_rank[c];
-  const bool valid = (unsigned)rr < (unsigned)p.G && (unsigned)rk < (unsigned)p.G;
-  if (!valid) {
-    if (j == 0) flag(p.status, HM_ERR_BAD_ID);
-  } else {
-    const int gr = rr / per, gc = rk / per;
-    if (gr != gc && (j == gc || j == gr)) {
+  int cut = 0, block = blockIdx.x;
+  while (cut + 1 < p.ncuts && block >= p.build_blocks[cut]) block -= p.build_blocks[cut++];
+  const int ng = p.ng[cut], r0 = blockIdx.y * kBuildRows;
+  const int l = block * kSwapThreads + threadIdx.x;
+  if (l >= p.E * ng) return;
+  const int32_t *__restrict__ const C = p.C[cut];
+  const int32_t *__restrict__ const CT = p.CT[cut];
+  const int32_t *__restrict__ const CG = p.CG[cut];
+  const int32_t *__restrict__ const CGT = p.CGT[cut];
+  const int32_t *__restrict__ const L = p.L[cut];
+  const int32_t *__restrict__ const L0 = p.L0;
+  int32_t *__restrict__ const Z = p.Z[cut];
+  const unsigned per_reciprocal = p.per_reciprocal[cut];
+  const int c = ng == 1 ? l : (int)__umulhi((unsigned)l, p.ng_reciprocal[cut]);
+  const int j = l - c * ng;
+  const int rk = p.expert_to_rank[c];
+  const bool c_ok = (unsigned)rk < (unsigned)p.G;
+  const int gc = !c_ok ? -1 : per_reciprocal ? (int)__umulhi((unsigned)rk, per_reciprocal) : rk;
+  const int base = p.base[cut][j];
+  int add[kBuildRows], sub_[kBuildRows];   // val = base + add - sub
+  bool bad = false;
+#pragma unroll
+  for (int i = 0; i < kBuildRows; ++i) {
+    const int r = min(r0 + i, p.E - 1);
+    const int rr = p.expert_to_rank[r];
+    const bool r_ok = (unsigned)rr < (unsigned)p.G;
+    const int gr = !r_ok ? -1 : per_reciprocal ? (int)__umulhi((unsigned)rr, per_reciprocal) : rr;
+    add[i] = sub_[i] = 0;
+    if (!r_ok || !c_ok) {
+      bad = true;
+    } else if (gr != gc && (j == gc || j == gr)) {
       const int a = j == gc ? r : c, b = j == gc ? c : r;   // group j gains tokens of a, loses tokens of b
-      int cba = 0;
+      int cba = 0, cg;
+      if (p.transposed) {   // every read runs along row r of a table, or along c
+        cba = j == gc ? CT[(int64_t)r * p.E + c] : C[(int64_t)r * p.E + c];
+        cg = j == gc ? CG[(int64_t)r * ng + j] : CGT[(int64_t)j * p.E + c];
+      } else {
 #pragma unroll 8
-      for (int k = 0; k < p.copies; ++k) cba += p.C[cut][((int64_t)k * p.E + b) * p.E + a];
-      val += (p.L0[a] - p.CG[cut][(int64_t)a * ng + j]) - (p.L[cut][b] - cba);
+        for (int k = 0; k < p.copies; ++k) cba += C[((int64_t)k * p.E + b) * p.E + a];
+        cg = CG[(int64_t)a * ng + j];
+      }
+      add[i] = L0[a] - cg;
+      sub_[i] = L[b] - cba;
     }
   }
-  p.Z[cut][i] = val;
+  if (bad && j == 0) flag(p.status, HM_ERR_BAD_ID);
+#pragma unroll
+  for (int i = 0; i < kBuildRows; ++i)
+    if (r0 + i < p.E) Z[((int64_t)(r0 + i) * p.E) * ng + l] = base + (add[i] - sub_[i]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -542,53 +582,98 @@ struct SelectParams {
   double *best_time;
 };
 
+// x[i0 .. i0+16) of a term's counts, 0 beyond n: sixteen loads in flight instead of a wait per
+// entry (counts are >= 0, so the padding changes neither the maximum nor, skipped, the sum).
+__device__ __forceinline__ void load16(const int32_t *x, int n, int i0, int (&v)[16]) {
+  if ((n & 3) == 0) {   // rows of n ints start 16-byte aligned
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      i32x4 w = {0, 0, 0, 0};
+      if (i0 + 4 * j < n) w = *(const i32x4 *)(x + i0 + 4 * j);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[4 * j + e] = w[e];
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = i0 + j < n ? x[i0 + j] : 0;
+  }
+}
+
 __device__ __forceinline__ double smooth_max(const int32_t *x, int n, double gamma) {
   int mi = 0;
-  for (int i = 0; i < n; ++i) mi = max(mi, x[i]);
+  for (int i0 = 0; i0 < n; i0 += 16) {
+    int v[16];
+    load16(x, n, i0, v);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) mi = max(mi, v[j]);
+  }
   const double m = (double)mi;
   if (gamma <= 0.0 || m == 0.0) return m;
   // A small whole gamma (the paper uses 10) needs no pow per entry: square-and-multiply gives the
-  // same power to a few ulp, and a thread is otherwise a serial chain of up to 64 pow calls per level.
+  // same power to a few ulp, and a lane is otherwise a serial chain of up to 64 pow calls.
   const int whole = (gamma <= 64.0 && gamma == (double)(int)gamma) ? (int)gamma : 0;
   const double inv_m = 1.0 / m;
   double sum = 0.0;
-  for (int i = 0; i < n; ++i) {
-    if (whole) {
-      const double ratio = (double)x[i] * inv_m;   // within an ulp of the quotient
-      double acc = 1.0, sq = ratio;
-      for (int e = whole; e; e >>= 1) {
-        if (e & 1) acc *= sq;
-        sq *= sq;
+  if (whole) {
+    for (int i0 = 0; i0 < n; i0 += 16) {
+      int v[16];
+      load16(x, n, i0, v);
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        if (i0 + j < n) {
+          const double ratio = (double)v[j] * inv_m;   // within an ulp of the quotient
+          double acc = 1.0, sq = ratio;
+          for (int e = whole; e; e >>= 1) {
+            if (e & 1) acc *= sq;
+            sq *= sq;
+          }
+          sum += acc;
+        }
       }
-      sum += acc;
-    } else {
-      sum += pow((double)x[i] / m, gamma);
     }
+  } else {
+    for (int i = 0; i < n; ++i) sum += pow((double)x[i] / m, gamma);
   }
   return m * pow(sum, 1.0 / gamma);
 }
 
+// Q of one pair by four lanes: the terms of Eq.(8) (the Inter levels 1 .. d-1, then the Intra
+// level) side by side, one lane each, through one code path (a term is a pointer, a length and
+// four factors).  The terms are then added in the order of the levels, so Q has the bits of a
+// serial evaluation.
 __global__ __launch_bounds__(kSelectThreads) void swap_q_kernel(SelectParams p) {
 #pragma clang fp contract(off)
-  __shared__ double s_val[kSelectThreads];
-  __shared__ int32_t s_arg[kSelectThreads];
-  const int64_t rc = (int64_t)blockIdx.x * kSelectThreads + threadIdx.x;
+  __shared__ double s_val[kSelectPairs];
+  __shared__ int32_t s_arg[kSelectPairs];
+  const int lane = lane_id();
+  const int term = lane & (kPairLanes - 1);
+  const int pair_in_block = threadIdx.x / kPairLanes;
+  const int64_t rc = (int64_t)blockIdx.x * kSelectPairs + pair_in_block;
   const int64_t pairs = (int64_t)p.E * p.E;
-  double q = 0.0;
   const bool live = rc < pairs;
-  if (live) {
-    for (int i = 1; i < p.d; ++i) {
-      const double n = (double)(p.U[i] / p.U[i - 1]) * p.scale_inter[i] * smooth_max(p.z_inter[i] + rc * p.U[i], p.U[i], p.gamma) * p.M * p.v;
-      q = q + (n * p.beta_inter[i] + p.alpha_inter[i]);
-    }
-    const double n = (double)(p.G / p.U[p.d - 1]) * p.scale_intra * smooth_max(p.z_intra + rc * p.G, p.G, p.gamma) * p.M * p.v;
-    q = q + (n * p.beta_intra + p.alpha_intra);
-    p.Q[rc] = q;
+  const int64_t at = live ? rc : 0;
+  double mine = 0.0;
+  if (term < p.d) {
+    const bool intra = term == p.d - 1;
+    const int i = intra ? 0 : term + 1;
+    const int n = intra ? p.G : p.U[i];
+    const int32_t *x = (intra ? p.z_intra : p.z_inter[i]) + at * n;
+    const double fan = intra ? (double)(p.G / p.U[p.d - 1]) : (double)(p.U[i] / p.U[intra ? 0 : i - 1]);
+    const double scale = intra ? p.scale_intra : p.scale_inter[i];
+    const double beta = intra ? p.beta_intra : p.beta_inter[i], alpha = intra ? p.alpha_intra : p.alpha_inter[i];
+    const double volume = fan * scale * smooth_max(x, n, p.gamma) * p.M * p.v;
+    mine = volume * beta + alpha;
   }
-  s_val[threadIdx.x] = q;
-  s_arg[threadIdx.x] = live ? (int32_t)rc : -1;
+  double q = 0.0;
+  const int lane0 = lane & ~(kPairLanes - 1);
+  for (int j = 0; j < p.d; ++j) q = q + __shfl(mine, lane0 + j, kWave);
+  if (term == 0) {
+    if (live) p.Q[rc] = q;
+    s_val[pair_in_block] = q;
+    s_arg[pair_in_block] = live ? (int32_t)rc : -1;
+  }
   __syncthreads();
-  for (int off = kSelectThreads / 2; off > 0; off >>= 1) {
+  for (int off = kSelectPairs / 2; off > 0; off >>= 1) {
     if ((int)threadIdx.x < off) {
       const int o = threadIdx.x + off;
       const bool take = s_arg[o] >= 0 && (s_arg[threadIdx.x] < 0 || s_val[o] < s_val[threadIdx.x] ||
@@ -675,9 +760,9 @@ static inline int64_t swap_copies(int64_t E) {
 }
 
 // Workspace, in ints: L0 [E], then per cut base [64] | L [E] | CG [E * ng] | C [copies * E * E], and on the
-// matrix path the partial tables of kCoocChunksMax chunks after that.
+// matrix path the partial tables of kCoocChunksMax chunks and the transposes of C and CG after that.
 static inline int64_t swap_cut_ints(int64_t E, int64_t ng) {
-  return 64 + E + E * ng + swap_copies(E) * E * E + (swap_by_matrices(E) ? kCoocChunksMax * cooc_part_ints(E, ng) : 0);
+  return 64 + E + E * ng + swap_copies(E) * E * E + (swap_by_matrices(E) ? kCoocChunksMax * cooc_part_ints(E, ng) + E * E + E * ng : 0);
 }
 // ... and, on the matrix path, one byte per routing slot at the very end.
 static inline int64_t swap_slot_ints(int64_t T, int64_t K, int64_t E) { return swap_by_matrices(E) ? (T * K + 3) / 4 : 0; }
@@ -723,11 +808,13 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
   while (p.sub < K) p.sub *= 2;
   p.ws = (int32_t *)workspace;
   p.L0 = p.ws;
-  int64_t at = E, lds_at = E, max_ng = 1;
+  int64_t at = E, lds_at = E;
   for (int c = 0; c < kMaxCuts; ++c) {
     const int cc = c < ncuts ? c : 0;   // unused entries repeat cut 0 so that no pointer is left dangling
     p.ng[c] = ng[cc];
     p.per[c] = G / ng[cc];
+    p.ng_reciprocal[c] = ng[cc] > 1 ? (uint32_t)((0x100000000ull + ng[cc] - 1) / ng[cc]) : 0u;
+    p.per_reciprocal[c] = p.per[c] > 1 ? (uint32_t)((0x100000000ull + p.per[c] - 1) / p.per[c]) : 0u;
     p.Z[c] = Z[cc];
     if (c < ncuts) {
       p.base[c] = p.ws + at;
@@ -737,7 +824,6 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
       at += swap_cut_ints(E, ng[c]);
       p.lds_off[c] = (int32_t)lds_at;
       lds_at += (int64_t)E * (ng[c] + 1);
-      if (ng[c] > max_ng) max_ng = ng[c];
     } else {
       p.base[c] = p.base[0];
       p.L[c] = p.L[0];
@@ -753,6 +839,7 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
     // Every table is written in full by the kernels below: only the status word needs clearing.
     p.ws_ints = 0;
     p.use_lds = 0;
+    p.transposed = 1;
     hipLaunchKernelGGL(swap_clear_kernel, dim3(1), dim3(kSwapThreads), 0, stream, p);
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
     CoocParams cp;
@@ -777,6 +864,8 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
       cp.ng[c] = p.ng[c];
       cp.per[c] = p.per[c];
       cp.part[c] = p.C[c] + (int64_t)E * E;   // behind the summed C of the cut
+      p.CT[c] = cp.part[c] + kCoocChunksMax * cooc_part_ints(E, p.ng[c]);
+      p.CGT[c] = p.CT[c] + (int64_t)E * E;
       if (c < ncuts && cooc_part_ints(E, ng[c]) > max_part) max_part = cooc_part_ints(E, ng[c]);
     }
     cp.status = status;
@@ -792,6 +881,8 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
                        dim3(kSwapThreads), 0, stream, p, cp);
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   } else {
+    p.transposed = 0;
+    for (int c = 0; c < kMaxCuts; ++c) p.CT[c] = p.CGT[c] = nullptr;
     p.ws_ints = at;
     p.use_lds = (lds_at <= kSwapLds && swap_factors_lds_ready()) ? 1 : 0;
     hipLaunchKernelGGL(swap_clear_kernel, dim3((unsigned)((p.ws_ints + kSwapThreads - 1) / kSwapThreads)), dim3(kSwapThreads),
@@ -806,8 +897,12 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
       if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
     }
   }
-  const int64_t total = (int64_t)E * E * max_ng;
-  hipLaunchKernelGGL(swap_build_kernel, dim3((unsigned)((total + kSwapThreads - 1) / kSwapThreads), (unsigned)ncuts),
+  int64_t build_blocks = 0;
+  for (int c = 0; c < kMaxCuts; ++c) {
+    p.build_blocks[c] = c < ncuts ? (int32_t)(((int64_t)E * ng[c] + kSwapThreads - 1) / kSwapThreads) : 0;
+    build_blocks += p.build_blocks[c];
+  }
+  hipLaunchKernelGGL(swap_build_kernel, dim3((unsigned)build_blocks, (unsigned)((E + kBuildRows - 1) / kBuildRows)),
                      dim3(kSwapThreads), 0, stream, p);
   return hm_launch_status();
 }
@@ -864,7 +959,7 @@ extern "C" hm_status hm_swap_counts_multi(const int32_t *topk_ids, const int32_t
 
 extern "C" size_t hm_swap_select_workspace_bytes(int32_t E) {
   if (E < 1) return 0;
-  const int64_t blocks = ((int64_t)E * E + hm::kSelectThreads - 1) / hm::kSelectThreads;
+  const int64_t blocks = ((int64_t)E * E + hm::kSelectPairs - 1) / hm::kSelectPairs;
   return (size_t)blocks * (sizeof(double) + sizeof(int32_t)) + 16;
 }
 
@@ -904,7 +999,7 @@ extern "C" hm_status hm_swap_select(int32_t d, const int32_t *U, int32_t G, int3
   p.alpha_intra = alpha_intra;
   p.beta_intra = beta_intra;
   p.Q = Q;
-  p.nblocks = (int32_t)(((int64_t)E * E + kSelectThreads - 1) / kSelectThreads);
+  p.nblocks = (int32_t)(((int64_t)E * E + kSelectPairs - 1) / kSelectPairs);
   p.block_min = (double *)workspace;
   p.block_arg = (int32_t *)(p.block_min + p.nblocks);
   p.best_pair = best_pair;

@@ -191,7 +191,7 @@ def test_argument_errors_are_reported_before_any_launch(B):
     # expert swap
     # E <= 256: one summed set of tables and 16 chunks' partial tables (C, CG, base); larger E: private copies of C
     part = 256 * 256 + 256 * 32 + 64
-    assert L.hm_swap_workspace_bytes(1000, 6, 256, 32) == (64 + 2 * 256 + 256 * 32 + 256 * 256 + 16 * part + 1500) * 4   # + a byte per slot
+    assert L.hm_swap_workspace_bytes(1000, 6, 256, 32) == (64 + 2 * 256 + 2 * (256 * 256 + 256 * 32) + 16 * part + 1500) * 4   # + transposes, a byte per slot
     assert L.hm_swap_workspace_bytes(1000, 6, 512, 32) == (64 + 2 * 512 + 512 * 32 + 2 * 512 * 512) * 4
     assert L.hm_swap_workspace_bytes(10, 2, 0, 4) == 0 and L.hm_swap_workspace_bytes(-1, 2, 8, 4) == 0
     big = 1 << 30
@@ -206,7 +206,7 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_swap_select(2, i32x(1, 2), 4, 8, 1.0, 1.0, zn, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
     ng2 = i32x(2, 4)
     zz = (ctypes.c_void_p * 2)(fake, fake)
-    assert L.hm_swap_multi_workspace_bytes(7, 3, 16, 4, 2, ng2) == (16 + 6 + sum(64 + 16 + 16 * g + 256 + 16 * (256 + 16 * g + 64) for g in (2, 4))) * 4
+    assert L.hm_swap_multi_workspace_bytes(7, 3, 16, 4, 2, ng2) == (16 + 6 + sum(64 + 16 + 2 * (16 * g + 256) + 16 * (256 + 16 * g + 64) for g in (2, 4))) * 4
     assert L.hm_swap_multi_workspace_bytes(7, 3, 16, 4, 5, ng2) == 0 and L.hm_swap_multi_workspace_bytes(7, 3, 16, 6, 2, ng2) == 0
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 4, 2, ng2, zz, None, fake, 8, None) == B.HM_ERR_WORKSPACE
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 6, 2, ng2, zz, None, fake, big, None) == B.HM_ERR_TOPOLOGY

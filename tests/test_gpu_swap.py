@@ -125,6 +125,30 @@ def test_swap_counts_full_size(hw, oracle, name, placement):
         assert np.array_equal(Z.cpu().numpy(), ref) and st == st_ref == 0, (name, ng)
 
 
+@pytest.mark.parametrize("E,G,K,T,cuts", [(256, 64, 8, 65536, [8, 64]),       # 64 Ki-token layer: four fetch stages per chunk, four panels
+                                          (128, 32, 8, 40000, [4, 32]),       # ragged: the last chunk ends inside a stage
+                                          (96, 16, 3, 20000, [16]),           # four lanes per token: lanes beyond 128 tokens idle
+                                          (200, 8, 24, 9000, [2, 8])])        # 32 lanes per token: four passes per tile
+def test_swap_counts_long_chunks(hw, oracle, E, G, K, T, cuts):
+    """Token counts beyond what one fetch stage of a chunk covers (16 chunks x 1,024 slots-per-lane
+    passes), so the matrix kernel's outer loop, its clamped loads at a ragged end and the
+    multi-pass tiles are all exercised; the four-panel split of E > 128 too."""
+    import torch
+    from paper_2508_09591_amd import binding as B
+    rng = np.random.default_rng(E + T)
+    ids = rng.integers(0, E, (T, K), dtype=np.int32)
+    ids[rng.random((T, K)) < 0.03] = -1
+    ids[T - 1, 0] = ids[T - 1, K - 1]                           # a repeated expert in the very last token
+    e2r = rng.integers(0, G, E).astype(np.int32)
+    Z = [torch.full((E, E, u), -9, dtype=torch.int32, device="cuda") for u in cuts]
+    st = torch.full((1,), 5, dtype=torch.int32, device="cuda")
+    B.hm_swap_counts_multi(hw.dev(ids), hw.dev(e2r), G, cuts, Z, st)
+    assert int(st.item()) == 0
+    for u, z in zip(cuts, Z):
+        ref, _ = oracle.swap_counts(ids, e2r, G, u, "incremental")
+        assert np.array_equal(z.cpu().numpy(), ref), (E, G, K, T, u)
+
+
 def test_swap_select_parity(hw, oracle):
     import torch
     from paper_2508_09591_amd import binding as B
