@@ -784,28 +784,25 @@ def run_planner(args) -> int:
                "sample": "the whole %s batch once (incremental Z update for %d cuts + selection), %.2f s" % (wl.name, len(cuts), dt)}
         log("cpu oracle: %.2f s" % dt)
     swap_ms = kern[names[2]]
-    # What bounds the co-occurrence pass is its read-modify-write updates: per token and cut, one update of the
-    # expert-by-expert table for every (expert alone in its group, other selected expert) pair go to global
-    # memory (popular pairs serialise on one address); everything else accumulates in LDS first.  The rate is
-    # put against what the L2 atomic units could do at best: 8 dies x 16 channels x one update per clock.
-    ids_h = r.topk_ids
-    pair_updates = 0
-    for u in cuts:
-        grp = (e2r[ids_h] // (G // u)).astype(np.int64)                                  # [T, K] group of every selected expert
-        same = (grp[:, :, None] == grp[:, None, :]).sum(2)                              # selected experts sharing my group (top-K ids are distinct)
-        pair_updates += int(((same == 1).sum(1) * (K - 1)).sum())
-    peak_updates = 8 * 16 * 2.4e9
+    # The co-occurrence tables are int8 matrix products over 0/1 indicator tiles (E <= 256): per cut
+    # C = A^T S (E_pad x E_pad x T) and CG = S^T M (E_pad x 32 ceil(ng/32) x T).  Their dense operation count
+    # against the int8 MFMA peak is what the line reports; the products themselves are a small part of the
+    # call (filling the tiles, barriers and LDS latency, and five short launches, set its time).
+    e_pad = 32 * (1 if E <= 32 else 2 if E <= 64 else 4 if E <= 128 else 8)
+    dense_ops = sum(2 * e_pad * (e_pad + 32 * ((u + 31) // 32)) * T for u in cuts) if E <= 256 else 0
+    peak_ops = 5.0e15
     result = {"metric": "planner (counts + d* + swap tensor Z + best pair) tokens/s", "value": round(T / (ms_per_step * 1e-3), 1),
               "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
               "config": {"workload": "%s: T=%d K=%d E=%d G=%d, hierarchy U=%s, gamma=10" % (wl.name, T, K, E, G, U)},
-              "roofline": {"bound": "alu", "kernel": "hm_swap_counts", "achieved": round(pair_updates / (swap_ms * 1e-3) / 1e9, 3),
-                           "peak": round(peak_updates / 1e9, 1),
-                           "unit": "G global read-modify-write updates/s (peak: 8 dies x 16 L2 channels x 1 update per clock at 2.4 GHz)",
-                           "frac": round(pair_updates / (swap_ms * 1e-3) / peak_updates, 5), "traffic": None,
-                           "updates_per_launch": pair_updates,
-                           "note": "seven short launches over a few hundred KiB of input: launch latency and same-address "
-                                   "serialisation of the updates, not arithmetic or bandwidth, set the time"},
+              "roofline": {"bound": "mfma", "kernel": "hm_swap_counts_multi (swap_slots + swap_cooc + swap_reduce + swap_build)",
+                           "achieved": round(dense_ops / (swap_ms * 1e-3) / 1e12, 3), "peak": round(peak_ops / 1e12, 1),
+                           "unit": "int8 TOP/s (dense products of the 0/1 indicator tiles; peak: MI355X int8 MFMA)",
+                           "frac": round(dense_ops / (swap_ms * 1e-3) / peak_ops, 5), "traffic": None,
+                           "dense_ops_per_call": dense_ops,
+                           "note": "latency-bound: ten short launches per planner step over a few hundred KiB of input; in the "
+                                   "matrix kernel the products are about a tenth of the time, filling and clearing the tiles, "
+                                   "barriers and LDS latency the rest"},
               "cpu_baseline": cpu, "kernels": kern, "monitored_counts": monitored}
     print(json.dumps(result), flush=True)
     return 0

@@ -343,10 +343,12 @@ hm_status hm_alltoall_times(int32_t D, const int32_t *U /* host */, int32_t G, d
  *
  * hm_swap_counts -- the swap tensor of Section IV-A: Z[(r*E + c)*ng + j] (device int32) = the
  * duplicate-free number of tokens assigned to group j (the G ranks cut into ng contiguous equal
- * groups) after the positions of experts r and c are exchanged, for every pair.  Computed in
- * O(T K (K + ng)) from per-expert / per-(expert,group) / per-(expert,expert) co-occurrence counts
- * instead of the paper's O(T K E) update: only the two groups involved in a swap can change, and
- * the change is  +#{tokens selecting r, nothing in c's group}  -#{tokens where c is the only
+ * groups) after the positions of experts r and c are exchanged, for every pair.  Computed from
+ * per-expert / per-(expert,group) / per-(expert,expert) co-occurrence counts (for E <= 256 as int8
+ * matrix products over 0/1 indicator tiles on the matrix cores, beyond that with O(T K (K + ng))
+ * atomic updates) instead of the paper's O(T K E) update: only the two groups involved in a swap
+ * can change, and the change is
+ *   +#{tokens selecting r, nothing in c's group}  -#{tokens where c is the only
  * selected expert of its group and r is not selected}  for c's group (and symmetrically).
  * A pair in which either expert's placement entry is outside [0,G) keeps the unswapped counts;
  * invalid slots are ignored; both set *status (optional device int32[1]) to HM_ERR_BAD_ID.

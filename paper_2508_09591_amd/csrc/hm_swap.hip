@@ -2,12 +2,14 @@
 //
 // Z[r][c][:] is the vector of duplicate-free per-group token counts after experts r and c trade
 // places.  A swap can only change the two groups involved, and by how much follows from three
-// small co-occurrence tables gathered in one pass over the tokens (one lane per routing slot):
+// small co-occurrence tables over the tokens:
 //   L0[a]    tokens selecting a                      CG[a][g]  ... that also select something in g
 //   L[a]     tokens where a is alone in its group    C[a][b]   ... that also select b
 // For g_r != g_c:  Z[r][c][g_c] = base[g_c] + (L0[r] - CG[r][g_c]) - (L[c] - C[c][r])   and the same
-// with r and c exchanged for g_r.  This is O(T K (K + ng)) instead of the O(T K E) walk over all
-// unselected experts, with the per-pair work moved into an embarrassingly parallel E^2 ng kernel.
+// with r and c exchanged for g_r: no O(T K E) walk over all unselected experts, and the per-pair
+// work is an embarrassingly parallel E^2 ng kernel.  The tables come from int8 matrix products on
+// the matrix cores for E <= 256 (further down), from O(T K (K + ng)) atomic updates, one lane per
+// routing slot, beyond that.
 #include "hm_device.h"
 
 namespace hm {
