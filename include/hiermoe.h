@@ -25,8 +25,9 @@
  *   - Row and token indices are int32; byte offsets inside the kernels are 64-bit.
  *   - Limits: nodes*ranks_per_node <= 64, nodes <= 32 (bit masks), 1 <= K <= 64,
  *     T*K <= 2^31-1.
- *   - Re-entrant per (plan buffers, workspace, stream); no global state (hm_swap_counts sets one
- *     kernel attribute, its dynamic LDS limit, the first time it runs).
+ *   - Re-entrant per (plan buffers, workspace, stream); the only global state is what is named
+ *     where it is declared: hm_plan_one_launch_limit, the scratch of hm_plan_static, and kernel
+ *     attributes (dynamic LDS limits) that hm_swap_counts sets the first time it runs.
  */
 #ifndef HIERMOE_H
 #define HIERMOE_H
@@ -132,6 +133,20 @@ hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int3
                   int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level,
                   hm_plan_out *out /* host struct */, void *workspace, size_t workspace_bytes,
                   void *hip_stream);
+
+/*
+ * hm_plan_one_launch_limit -- plans of at most `workgroups` workgroups (1,024 routing slots each;
+ * default and maximum 256) run as ONE launch whose workgroups wait for one another's counts, which
+ * needs all of them resident on the GPU together.  One such plan always is (the library checks the
+ * device), and so are two at a time (an MI355X holds 512 of these workgroups).  A caller that
+ * keeps more plans in flight on separate streams, or shares the GPU with kernels that fill it for
+ * longer than about 0.1 s, can end up with several plans each holding part of the machine; their
+ * waits are bounded, so nothing hangs, but such a plan ends with HM_ERR_HIP in its status word
+ * and unwritten maps.  Those callers lower the limit (0: always separate launches, which have no
+ * such need and cost a few microseconds more on small plans).  Process-wide, takes effect for
+ * later calls; returns the previous limit.  The results do not depend on it.
+ */
+int32_t hm_plan_one_launch_limit(int32_t workgroups);
 
 /*
  * hm_plan_status -- waits for `hip_stream`, then returns the plan's device status word and

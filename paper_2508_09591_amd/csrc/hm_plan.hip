@@ -779,12 +779,15 @@ static inline uint64_t next_tag() {
   return e;
 }
 
+// Largest plan, in workgroups, that takes the one-launch kernel (hm_plan_one_launch_limit).
+static std::atomic<int> one_launch_limit{kPlanFusedMaxBlocks};
+
 // One launch when the plan is small enough, else count -> (scan) -> write, on `stream`;
 // p.nblocks, p.Dn and p.counts are set.
 static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
   const bool loads = p.load_expert != nullptr;
   const unsigned hist_bytes = loads && p.E <= kPlanHist ? (unsigned)p.E * sizeof(int32_t) : 0u;
-  if (p.nblocks <= kPlanFusedMaxBlocks && p.nblocks <= fused_capacity()) {
+  if (p.nblocks <= one_launch_limit.load(std::memory_order_relaxed) && p.nblocks <= fused_capacity()) {
     p.scanned = 0;
     const int staged = p.E <= kPlanStagedExperts ? 1 : 0;   // tables (and histogram) in LDS
     const unsigned lds = staged ? ((loads ? (unsigned)p.E * sizeof(int32_t) : 0u) + ((2u * (unsigned)p.E + 15u) & ~15u)) : 0u;
@@ -805,6 +808,11 @@ static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
 }
 
 }  // namespace hm
+
+extern "C" int32_t hm_plan_one_launch_limit(int32_t workgroups) {
+  const int v = workgroups < 0 ? 0 : workgroups > hm::kPlanFusedMaxBlocks ? hm::kPlanFusedMaxBlocks : workgroups;
+  return hm::one_launch_limit.exchange(v, std::memory_order_relaxed);
+}
 
 extern "C" size_t hm_plan_workspace_bytes(int32_t T, int32_t K, int32_t E, hm_topology topo, hm_dedup_level level) {
   if (E < 1 || hm_check_tk(T, K) != HM_OK || hm_check_topology(topo) != HM_OK) return 0;

@@ -23,11 +23,12 @@ def dev(a: np.ndarray) -> torch.Tensor:
 class GpuPlan:
     """hm_plan on the GPU plus host copies of everything it produced."""
 
-    def __init__(self, ids, w, e2r, nodes, rpn, level, row_capacity=None):
+    def __init__(self, ids, w, e2r, nodes, rpn, level, row_capacity=None, loads=False):
         self.ids_d, self.w_d, self.e2r_d = dev(ids), dev(w), dev(e2r)
         T, K = ids.shape
         self.T, self.K = T, K
-        self.plan = B.alloc_plan(T, K, e2r.shape[0], nodes, rpn, level, row_capacity=row_capacity)
+        self.loads = loads
+        self.plan = B.alloc_plan(T, K, e2r.shape[0], nodes, rpn, level, row_capacity=row_capacity, loads=loads)
         # poison the outputs so that unwritten entries are noticed
         for name in ("dest_count", "dest_offset", "row_token", "slot_row"):
             getattr(self.plan, name).fill_(-12345)
@@ -40,7 +41,12 @@ class GpuPlan:
     def host(self):
         p = self.plan
         n = self.total_rows
+        extra = {}
+        if self.loads:   # the load counts hm_plan fills on request
+            extra = dict(load_expert=p.load_expert.cpu().numpy(), load_rank=p.load_rank.cpu().numpy(),
+                         load_node=p.load_node.cpu().numpy())
         return dict(
+            **extra,
             dest_count=p.dest_count[:p.num_dest].cpu().numpy(),
             dest_offset=p.dest_offset[:p.num_dest + 1].cpu().numpy(),
             row_token=p.row_token[:min(n, p.row_capacity)].cpu().numpy(),

@@ -549,6 +549,33 @@ def test_plan_is_deterministic(hw, oracle):
         assert blob == first
 
 
+def test_plan_does_not_depend_on_the_launch_path(hw, oracle):
+    """Small plans run as one launch by default; with the limit at 0 the same plans take the
+    separate count / write launches (which otherwise only plans above 262,144 slots use), and a
+    limit of 2 workgroups splits the cases between the two.  Every field must come out the same,
+    fused load counts included, and equal to the oracle."""
+    from paper_2508_09591_amd import binding as B
+    cases = [("qwen3", 1500, GPU), ("dsv3", 4096, NODE), ("tiny", 1024, NONE), ("skew", 200, GPU)]
+    blobs = {}
+    try:
+        for limit in (256, 0, 2):
+            assert B.hm_plan_one_launch_limit(limit) in (256, 0, 2)
+            for name, T, level in cases:
+                wl = W.WORKLOADS[name]
+                r = W.make_routing(wl, T=T)
+                g = hw.GpuPlan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node, level, loads=True)
+                h = g.host()
+                blob = b"".join(np.ascontiguousarray(h[k]).tobytes() for k in sorted(h))
+                assert blobs.setdefault((name, T, level), blob) == blob, (limit, name)
+                if limit == 0:
+                    hw.assert_plan_equal(g, oracle.plan(r.topk_ids, r.topk_weights, r.expert_to_rank, wl.nodes, wl.ranks_per_node,
+                                                        level), "separate launches: " + name)
+    finally:
+        assert B.hm_plan_one_launch_limit(256) in (256, 0, 2)
+    assert B.hm_plan_one_launch_limit(10 ** 6) == 256 and B.hm_plan_one_launch_limit(-5) == 256      # clamped to [0, 256]
+    assert B.hm_plan_one_launch_limit(256) == 0
+
+
 def test_random_shapes_against_the_oracle(hw, oracle):
     """Seeded sweep over shapes nobody picked by hand: topology, K, E, H (vector and element-wise
     paths), uneven placements, repeated experts, dropped and invalid slots, all three levels."""
