@@ -203,6 +203,7 @@ constexpr int kCoocTokens = 128;     // tokens per tile: four k-steps of the 32x
 constexpr int kCoocStride = 144;     // bytes per tile row: 128 tokens + 16, which spreads 32 rows over all banks
 constexpr int kCoocGroups = 64;      // rows of the group tile
 constexpr int kCoocChunksMax = 16;   // partial tables per cut
+constexpr int kCoocChunkTokensMax = 32640;   // a chunk's counts are stored as 16-bit values
 constexpr int kCoocMaxE = 256;
 constexpr int kCoocStaged = 8;       // passes whose slots are fetched together (16 KiB of LDS)
 constexpr int kCoocTokensPerChunkMin = 512;   // below this a chunk is not worth a workgroup of its own
@@ -220,11 +221,12 @@ struct CoocParams {
   int32_t tokens_per_chunk;    // a multiple of kCoocTokens
   int32_t ng[kMaxCuts], per[kMaxCuts];
   uint8_t *slot_bits;          // [T * K]: bit 0 first valid occurrence, bit 1 + c alone in its group under cut c
-  int32_t *part[kMaxCuts];     // [chunks][E*E + E*ng + 64]: C, CG and base of one chunk
+  uint16_t *part[kMaxCuts];    // [chunks][E*E + E*ng + 64 (+1)]: C, CG and base of one chunk; a chunk has < 2^15 tokens
   int32_t *status;
 };
 
-__host__ __device__ static inline int64_t cooc_part_ints(int64_t E, int64_t ng) { return E * E + E * ng + 64; }
+__host__ __device__ static inline int64_t cooc_part_ints(int64_t E, int64_t ng) { return E * E + E * ng + 64; }   // values per chunk
+__host__ __device__ static inline int64_t cooc_part_words(int64_t E, int64_t ng) { return (cooc_part_ints(E, ng) + 1) / 2; }   // 32-bit words they take
 
 // One lane per routing slot; the K slots of a token sit in 2^sub_log2 consecutive lanes and learn
 // about each other through shuffles, eight in flight at a time.
@@ -449,15 +451,15 @@ __global__ __launch_bounds__(kCoocThreads) void swap_cooc_kernel(CoocParams p) {
 
   // Accumulator layout of a 32x32 tile: register r of lane l holds row 8 (r / 4) + 4 (l / 32) + r % 4,
   // column l % 32.
-  int32_t *const part = p.part[cut] + (int64_t)blockIdx.x * cooc_part_ints(p.E, ng);
-  int32_t *const part_c = part, *const part_cg = part + (int64_t)p.E * p.E, *const part_base = part_cg + (int64_t)p.E * ng;
+  uint16_t *const part = p.part[cut] + (int64_t)blockIdx.x * 2 * cooc_part_words(p.E, ng);
+  uint16_t *const part_c = part, *const part_cg = part + (int64_t)p.E * p.E, *const part_base = part_cg + (int64_t)p.E * ng;
   const int col = lane & 31, row_hi = (lane >> 5) * 4;
   if (has_c) {
     const int b = 32 * c_col + col;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int a = 32 * c_row + 8 * (r / 4) + row_hi + (r % 4);
-      if (a < p.E && b < p.E) part_c[(int64_t)a * p.E + b] = acc[r];
+      if (a < p.E && b < p.E) part_c[(int64_t)a * p.E + b] = (uint16_t)acc[r];
     }
   }
   if (has_g) {
@@ -465,10 +467,10 @@ __global__ __launch_bounds__(kCoocThreads) void swap_cooc_kernel(CoocParams p) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int a = 32 * g_row + 8 * (r / 4) + row_hi + (r % 4);
-      if (a < p.E && g < ng) part_cg[(int64_t)a * ng + g] = acc_g[r];
+      if (a < p.E && g < ng) part_cg[(int64_t)a * ng + g] = (uint16_t)acc_g[r];
     }
   }
-  if (counts_base) part_base[lane] = my_base;
+  if (counts_base) part_base[lane] = (uint16_t)my_base;
 }
 
 // Sums the chunks' partial tables into the tables swap_build_kernel reads; blockIdx.y is the cut.
@@ -477,30 +479,42 @@ __global__ __launch_bounds__(kCoocThreads) void swap_cooc_kernel(CoocParams p) {
 __global__ __launch_bounds__(kSwapThreads) void swap_reduce_kernel(SwapParams p, CoocParams cp) {
   const int cut = blockIdx.y;
   const int ng = p.ng[cut];
-  const int64_t n = cooc_part_ints(p.E, ng);
-  const int64_t i = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;
-  if (i >= n) return;
-  int sum = 0;
+  const int64_t n = cooc_part_ints(p.E, ng), words = cooc_part_words(p.E, ng);
+  const int64_t word = (int64_t)blockIdx.x * kSwapThreads + threadIdx.x;   // two 16-bit values of every chunk
+  if (word >= words) return;
+  const uint32_t *const part = (const uint32_t *)cp.part[cut];
+  int sums[2] = {0, 0};
 #pragma unroll
-  for (int c = 0; c < kCoocChunksMax; ++c)
-    if (c < cp.chunks) sum += cp.part[cut][c * n + i];
-  const int64_t ee = (int64_t)p.E * p.E;
-  if (i < ee) {
-    p.C[cut][i] = sum;
-    const int a = (int)(i / p.E), b = (int)(i % p.E);
-    p.CT[cut][(int64_t)b * p.E + a] = sum;
-    if (b == a) p.L[cut][a] = sum;
-  } else if (i < ee + (int64_t)p.E * ng) {
-    const int64_t j = i - ee;
-    p.CG[cut][j] = sum;
-    p.CGT[cut][(j % ng) * p.E + j / ng] = sum;
-    if (cut == 0) {
-      const int a = (int)(j / ng), g = (int)(j % ng);
-      const int r = p.expert_to_rank[a];
-      if ((unsigned)r < (unsigned)p.G ? r / p.per[0] == g : g == 0) p.L0[a] = (unsigned)r < (unsigned)p.G ? sum : 0;
+  for (int c = 0; c < kCoocChunksMax; ++c) {
+    if (c < cp.chunks) {
+      const uint32_t v = part[c * words + word];
+      sums[0] += (int)(v & 0xFFFFu);
+      sums[1] += (int)(v >> 16);
     }
-  } else {
-    p.base[cut][i - ee - (int64_t)p.E * ng] = sum;
+  }
+  const int64_t ee = (int64_t)p.E * p.E;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int64_t i = 2 * word + h;
+    const int sum = sums[h];
+    if (i >= n) break;
+    if (i < ee) {
+      p.C[cut][i] = sum;
+      const int a = (int)(i / p.E), b = (int)(i % p.E);
+      p.CT[cut][(int64_t)b * p.E + a] = sum;
+      if (b == a) p.L[cut][a] = sum;
+    } else if (i < ee + (int64_t)p.E * ng) {
+      const int64_t j = i - ee;
+      p.CG[cut][j] = sum;
+      p.CGT[cut][(j % ng) * p.E + j / ng] = sum;
+      if (cut == 0) {
+        const int a = (int)(j / ng), g = (int)(j % ng);
+        const int r = p.expert_to_rank[a];
+        if ((unsigned)r < (unsigned)p.G ? r / p.per[0] == g : g == 0) p.L0[a] = (unsigned)r < (unsigned)p.G ? sum : 0;
+      }
+    } else {
+      p.base[cut][i - ee - (int64_t)p.E * ng] = sum;
+    }
   }
 }
 
@@ -753,9 +767,10 @@ static bool swap_factors_lds_ready() {
 // Private copies of C on the path with atomics: as many as fit 2 MiB per cut, at most
 // kSwapCopiesMax (32 for E <= 128, 8 for E = 256): more copies spread the atomics of popular pairs,
 // but each is cleared and summed again.  The matrix path keeps one summed C.
-static inline bool swap_by_matrices(int64_t E) { return E <= kCoocMaxE; }
-static inline int64_t swap_copies(int64_t E) {
-  if (swap_by_matrices(E)) return 1;
+// The matrix path: E <= 256 and chunks short enough for 16-bit counts.
+static inline bool swap_by_matrices(int64_t E, int64_t T) { return E <= kCoocMaxE && T <= (int64_t)kCoocChunksMax * kCoocChunkTokensMax; }
+static inline int64_t swap_copies(int64_t E, int64_t T) {
+  if (swap_by_matrices(E, T)) return 1;
   int64_t n = kSwapCopiesMax;   // a power of two, so that a workgroup finds its copy with a mask
   while (n > 1 && n * E * E > (int64_t)(1 << 19)) n /= 2;
   return n;
@@ -763,11 +778,12 @@ static inline int64_t swap_copies(int64_t E) {
 
 // Workspace, in ints: L0 [E], then per cut base [64] | L [E] | CG [E * ng] | C [copies * E * E], and on the
 // matrix path the partial tables of kCoocChunksMax chunks and the transposes of C and CG after that.
-static inline int64_t swap_cut_ints(int64_t E, int64_t ng) {
-  return 64 + E + E * ng + swap_copies(E) * E * E + (swap_by_matrices(E) ? kCoocChunksMax * cooc_part_ints(E, ng) + E * E + E * ng : 0);
+static inline int64_t swap_cut_ints(int64_t E, int64_t ng, int64_t T) {
+  return 64 + E + E * ng + swap_copies(E, T) * E * E +
+         (swap_by_matrices(E, T) ? kCoocChunksMax * cooc_part_words(E, ng) + E * E + E * ng : 0);
 }
 // ... and, on the matrix path, one byte per routing slot at the very end.
-static inline int64_t swap_slot_ints(int64_t T, int64_t K, int64_t E) { return swap_by_matrices(E) ? (T * K + 3) / 4 : 0; }
+static inline int64_t swap_slot_ints(int64_t T, int64_t K, int64_t E) { return swap_by_matrices(E, T) ? (T * K + 3) / 4 : 0; }
 
 // The matrix kernel for E experts, its dynamic LDS, and whether the device grants that much.
 typedef void (*cooc_kernel_t)(CoocParams);
@@ -805,7 +821,7 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
   p.E = E;
   p.G = G;
   p.ncuts = ncuts;
-  p.copies = (int32_t)swap_copies(E);
+  p.copies = (int32_t)swap_copies(E, T);
   p.sub = 1;
   while (p.sub < K) p.sub *= 2;
   p.ws = (int32_t *)workspace;
@@ -823,7 +839,7 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
       p.L[c] = p.base[c] + 64;
       p.CG[c] = p.L[c] + E;
       p.C[c] = p.CG[c] + (int64_t)E * ng[c];
-      at += swap_cut_ints(E, ng[c]);
+      at += swap_cut_ints(E, ng[c], T);
       p.lds_off[c] = (int32_t)lds_at;
       lds_at += (int64_t)E * (ng[c] + 1);
     } else {
@@ -836,7 +852,7 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
   }
   p.status = status;
   size_t cooc_lds = 0;
-  const cooc_kernel_t cooc = swap_by_matrices(E) ? cooc_kernel(E, &cooc_lds) : nullptr;
+  const cooc_kernel_t cooc = swap_by_matrices(E, T) ? cooc_kernel(E, &cooc_lds) : nullptr;
   if (cooc && (cooc_lds <= 65536 || cooc_lds_ready())) {
     // Every table is written in full by the kernels below: only the status word needs clearing.
     p.ws_ints = 0;
@@ -865,10 +881,10 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
     for (int c = 0; c < kMaxCuts; ++c) {
       cp.ng[c] = p.ng[c];
       cp.per[c] = p.per[c];
-      cp.part[c] = p.C[c] + (int64_t)E * E;   // behind the summed C of the cut
-      p.CT[c] = cp.part[c] + kCoocChunksMax * cooc_part_ints(E, p.ng[c]);
+      cp.part[c] = (uint16_t *)(p.C[c] + (int64_t)E * E);   // behind the summed C of the cut
+      p.CT[c] = p.C[c] + (int64_t)E * E + kCoocChunksMax * cooc_part_words(E, p.ng[c]);
       p.CGT[c] = p.CT[c] + (int64_t)E * E;
-      if (c < ncuts && cooc_part_ints(E, ng[c]) > max_part) max_part = cooc_part_ints(E, ng[c]);
+      if (c < ncuts && cooc_part_words(E, ng[c]) > max_part) max_part = cooc_part_words(E, ng[c]);
     }
     cp.status = status;
     if (T > 0) {
@@ -914,13 +930,13 @@ static hm_status swap_counts_launch(const int32_t *topk_ids, const int32_t *expe
 extern "C" size_t hm_swap_multi_workspace_bytes(int32_t T, int32_t K, int32_t E, int32_t G, int32_t ncuts, const int32_t *ng) {
   if (E < 1 || T < 0 || K < 1 || !hm::swap_cuts_ok(G, ncuts, ng)) return 0;
   int64_t ints = E + hm::swap_slot_ints(T, K, E);
-  for (int c = 0; c < ncuts; ++c) ints += hm::swap_cut_ints(E, ng[c]);
+  for (int c = 0; c < ncuts; ++c) ints += hm::swap_cut_ints(E, ng[c], T);
   return (size_t)ints * sizeof(int32_t);
 }
 
 extern "C" size_t hm_swap_workspace_bytes(int32_t T, int32_t K, int32_t E, int32_t ng) {
   if (E < 1 || T < 0 || K < 1 || ng < 1 || ng > 64) return 0;
-  return (size_t)(E + hm::swap_cut_ints(E, ng) + hm::swap_slot_ints(T, K, E)) * sizeof(int32_t);
+  return (size_t)(E + hm::swap_cut_ints(E, ng, T) + hm::swap_slot_ints(T, K, E)) * sizeof(int32_t);
 }
 
 static hm_status swap_counts_checks(const int32_t *topk_ids, const int32_t *expert_to_rank, int32_t T, int32_t K, int32_t E,

@@ -189,10 +189,13 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_alltoall_times(2, i32x(1, 2), 4, 1.0, 1.0, None, fake, z, z, z, z, fake, fake, None) == B.HM_ERR_NULL
 
     # expert swap
-    # E <= 256: one summed set of tables and 16 chunks' partial tables (C, CG, base); larger E: private copies of C
-    part = 256 * 256 + 256 * 32 + 64
-    assert L.hm_swap_workspace_bytes(1000, 6, 256, 32) == (64 + 2 * 256 + 2 * (256 * 256 + 256 * 32) + 16 * part + 1500) * 4   # + transposes, a byte per slot
+    # E <= 256: one summed set of tables with transposes, 16 chunks' partial tables (C, CG, base as 16-bit
+    # values), a byte per slot; larger E: private copies of C
+    part_words = (256 * 256 + 256 * 32 + 64 + 1) // 2
+    assert L.hm_swap_workspace_bytes(1000, 6, 256, 32) == (64 + 2 * 256 + 2 * (256 * 256 + 256 * 32) + 16 * part_words + 1500) * 4
     assert L.hm_swap_workspace_bytes(1000, 6, 512, 32) == (64 + 2 * 512 + 512 * 32 + 2 * 512 * 512) * 4
+    # more tokens than 16 chunks of 16-bit counts can hold: the path with atomics, 8 private copies of C
+    assert L.hm_swap_workspace_bytes(2000000, 1, 256, 4) == (64 + 2 * 256 + 256 * 4 + 8 * 256 * 256) * 4
     assert L.hm_swap_workspace_bytes(10, 2, 0, 4) == 0 and L.hm_swap_workspace_bytes(-1, 2, 8, 4) == 0
     big = 1 << 30
     assert L.hm_swap_counts(fake, fake, 4, 2, 8, 4, 3, fake, None, fake, big, None) == B.HM_ERR_TOPOLOGY     # 3 does not divide 4
@@ -206,7 +209,7 @@ def test_argument_errors_are_reported_before_any_launch(B):
     assert L.hm_swap_select(2, i32x(1, 2), 4, 8, 1.0, 1.0, zn, fake, z, 1.0, z, z, 0.0, 0.0, 10.0, fake, fake, fake, fake, big, None) == B.HM_ERR_NULL
     ng2 = i32x(2, 4)
     zz = (ctypes.c_void_p * 2)(fake, fake)
-    assert L.hm_swap_multi_workspace_bytes(7, 3, 16, 4, 2, ng2) == (16 + 6 + sum(64 + 16 + 2 * (16 * g + 256) + 16 * (256 + 16 * g + 64) for g in (2, 4))) * 4
+    assert L.hm_swap_multi_workspace_bytes(7, 3, 16, 4, 2, ng2) == (16 + 6 + sum(64 + 16 + 2 * (16 * g + 256) + 16 * ((256 + 16 * g + 64 + 1) // 2) for g in (2, 4))) * 4
     assert L.hm_swap_multi_workspace_bytes(7, 3, 16, 4, 5, ng2) == 0 and L.hm_swap_multi_workspace_bytes(7, 3, 16, 6, 2, ng2) == 0
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 4, 2, ng2, zz, None, fake, 8, None) == B.HM_ERR_WORKSPACE
     assert L.hm_swap_counts_multi(fake, fake, 4, 2, 16, 6, 2, ng2, zz, None, fake, big, None) == B.HM_ERR_TOPOLOGY

@@ -128,7 +128,8 @@ def test_swap_counts_full_size(hw, oracle, name, placement):
 @pytest.mark.parametrize("E,G,K,T,cuts", [(256, 64, 8, 65536, [8, 64]),       # 64 Ki-token layer: four fetch stages per chunk, four panels
                                           (128, 32, 8, 40000, [4, 32]),       # ragged: the last chunk ends inside a stage
                                           (96, 16, 3, 20000, [16]),           # four lanes per token: lanes beyond 128 tokens idle
-                                          (200, 8, 24, 9000, [2, 8])])        # 32 lanes per token: four passes per tile
+                                          (200, 8, 24, 9000, [2, 8]),         # 32 lanes per token: four passes per tile
+                                          (48, 8, 2, 523000, [4])])           # more tokens than 16 chunks of 16-bit counts hold: the path with atomics
 def test_swap_counts_long_chunks(hw, oracle, E, G, K, T, cuts):
     """Token counts beyond what one fetch stage of a chunk covers (16 chunks x 1,024 slots-per-lane
     passes), so the matrix kernel's outer loop, its clamped loads at a ragged end and the
