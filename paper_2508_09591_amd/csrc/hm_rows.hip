@@ -171,12 +171,14 @@ struct RowBf16 {
     return (u + 0x7FFFu + tie_bit) >> 16;
   }
   static __device__ __forceinline__ elem scale(float a, elem g) { return (elem)scale1(a, widen(g)); }
-  // Eight at once: the common path rounds the fp32 products to nearest even and only notes whether
-  // any of them sits on a bf16 tie (1 in 65536); the exact treatment runs for those alone.
+  // Eight at once: the common path rounds the fp32 products to nearest even (add 0x7FFF plus the
+  // kept lsb; the upper halves of two such sums are one output word, picked by a byte permute) and
+  // only notes whether any product is a NaN or sits on a bf16 tie (1 in 65536); the exact
+  // treatment runs for those vectors alone.
   static __device__ __forceinline__ u32x4 scale(float a, u32x4 r) {
     float g[8];
-    uint32_t h[8];
-    bool any_tie = false;
+    uint32_t sum[8];
+    bool special = false;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const uint32_t w = r[e];
@@ -186,16 +188,18 @@ struct RowBf16 {
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float p = a * g[i];
-      h[i] = f32_to_bf16(p);
-      any_tie = any_tie || (__builtin_bit_cast(uint32_t, p) & 0xFFFFu) == 0x8000u;
-    }
-    if (__builtin_expect(any_tie, 0)) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) h[i] = scale1(a, g[i]);
+      const uint32_t u = __builtin_bit_cast(uint32_t, p);
+      sum[i] = u + 0x7FFFu + ((u >> 16) & 1u);
+      special = special || (u & 0xFFFFu) == 0x8000u || __builtin_isnan(p);
     }
     u32x4 o;
+    if (__builtin_expect(special, 0)) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = h[2 * e] | (h[2 * e + 1] << 16);
+      for (int e = 0; e < 4; ++e) o[e] = scale1(a, g[2 * e]) | (scale1(a, g[2 * e + 1]) << 16);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = __builtin_amdgcn_perm(sum[2 * e + 1], sum[2 * e], 0x07060302u);
+    }
     return o;
   }
 };
