@@ -514,6 +514,30 @@ def run_send(args) -> int:
                 % (row["workload"], row["level"], row["T"], row["H"], row["rows_per_token"], row["tokens_per_s"] / 1e6,
                    row["plan_us"], 100 * row["dispatch"]["frac"], 100 * row["combine"]["frac"], 100 * row["pair_frac"]))
 
+    # ---- the rows built beyond the send path (receiver stages, planner, Table IV grid): short runs of
+    # the same code the --path modes run, so that their figures are part of the default record too
+    next_rows = None
+    if not args.no_table:
+        import copy
+        sub = copy.copy(args)
+        sub.steps, sub.warmup, sub.no_cpu_baseline, sub.monitored, sub.separate_cuts = args.table_steps, min(args.warmup, 5), True, False, False
+
+        def brief(res, keep=("metric", "value", "unit", "ms_per_step", "config", "kernels")):
+            out = {k: res[k] for k in keep if k in res}
+            out["roofline"] = {k: res["roofline"][k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac")}
+            return out
+
+        next_rows = {}
+        sub.workload = "dsv3"
+        next_rows["recv"] = brief(run_recv(sub, emit=False))
+        for wname in ("skew", "dsv3"):
+            sub.workload = wname
+            next_rows["planner_" + wname] = brief(run_planner(sub, emit=False, workload=wname))
+        t4 = run_table4(sub, emit=False)
+        next_rows["table4"] = {"metric": t4["metric"], "grid": [
+            {"variant": g["variant"], **{l: {"rows_per_token": g[l]["rows_per_token"], "pair_ms": g[l]["pair_ms"], "frac": g[l]["frac"]}
+                                         for l in ("none", "gpu", "node")}} for g in t4["grid"]]}
+
     result = {
         "metric": "dedup dispatch+combine tokens/s (plan + expert_load + dispatch_pack + combine per step)",
         "expert_load": "separate hm_expert_load call" if args.separate_load else "filled by hm_plan (fused)",
@@ -553,12 +577,13 @@ def run_send(args) -> int:
         "expert_load_ms": None if head["expert_load_ms"] is None else round(head["expert_load_ms"], 5),
         "other_calls": head["extra"] or None,
         "configs": table,
+        "next_rows": next_rows,
     }
     print(json.dumps(result), flush=True)
     return 0
 
 
-def run_recv(args) -> int:
+def run_recv(args, emit=True):
     """Receiver stages of the two-hop exchange (HD2) at the workload's shape, on the rank with local
     index 0 of node 1.  Set-up (untimed) runs the sender path for the 32 source ranks that feed that
     node, so the receiver's inputs have the real size and routing mix:
@@ -685,11 +710,13 @@ def run_recv(args) -> int:
                      "unit": "GB/s", "frac": kern[dominant]["frac"], "traffic": None},
         "cpu_baseline": None, "kernels": kern,
     }
+    if not emit:
+        return result
     print(json.dumps(result), flush=True)
     return 0
 
 
-def run_planner(args) -> int:
+def run_planner(args, emit=True, workload=None):
     """The per-iteration planner work of Sections III-C and IV on the device: per-level counts,
     the time model and d*, the swap tensor Z for every level of a 4-level hierarchy, and the
     selection of the best expert pair (gamma = 10).  Default workload here: skew (config 4)."""
@@ -698,7 +725,7 @@ def run_planner(args) -> int:
     from paper_2508_09591_amd import binding as B
     from paper_2508_09591_amd import workloads as W
 
-    wl = W.WORKLOADS[args.workload if args.workload != "dsv3" or "--workload" in sys.argv else "skew"]
+    wl = W.WORKLOADS[workload or (args.workload if args.workload != "dsv3" or "--workload" in sys.argv else "skew")]
     r = W.make_routing(wl)
     e2r = r.extras.get("expert_to_rank_swapped", r.expert_to_rank)
     T, K, E, G, H = wl.T, wl.K, wl.E, wl.G, wl.H
@@ -804,6 +831,8 @@ def run_planner(args) -> int:
                                    "matrix kernel the products are about a tenth of the time, filling and clearing the tiles, "
                                    "barriers and LDS latency the rest"},
               "cpu_baseline": cpu, "kernels": kern, "monitored_counts": monitored}
+    if not emit:
+        return result
     print(json.dumps(result), flush=True)
     return 0
 
@@ -869,7 +898,7 @@ def monitored_dimension_choice(wl, e2r, ai, bi, aa, ba, stream):
     return out
 
 
-def run_table4(args) -> int:
+def run_table4(args, emit=True):
     """The K / E / G grid of the paper's Table IV on the Qwen3-shaped layer: rows per token at the
     three dedup levels (what the deduplication saves) and the dispatch+combine rate at each."""
     import numpy as np
@@ -930,6 +959,8 @@ def run_table4(args) -> int:
               "roofline": {"bound": "hbm", "kernel": "hm_dispatch_pack+hm_combine", "achieved": ref["node"]["GBps"],
                            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ref["node"]["frac"], "traffic": None},
               "cpu_baseline": None, "grid": table}
+    if not emit:
+        return result
     print(json.dumps(result), flush=True)
     return 0
 
