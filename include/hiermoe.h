@@ -137,16 +137,20 @@ hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int3
 /*
  * hm_plan_one_launch_limit -- plans of at most `workgroups` workgroups (1,024 routing slots each;
  * default and maximum 256) run as ONE launch whose workgroups wait for one another's counts, which
- * needs all of them resident on the GPU together.  One such plan always is (the library checks the
- * device), and so are two at a time (an MI355X holds 512 of these workgroups).  A caller that
- * keeps more plans in flight on separate streams, or shares the GPU with kernels that fill it for
- * longer than about 0.1 s, can end up with several plans each holding part of the machine; their
- * waits are bounded, so nothing hangs, but such a plan ends with HM_ERR_HIP in its status word
- * and unwritten maps.  Those callers lower the limit (0: always separate launches, which have no
- * such need and cost a few microseconds more on small plans).  Process-wide, takes effect for
- * later calls; returns the previous limit.  The results do not depend on it.
+ * needs all of them resident on the GPU together.  One such plan always is (the library checks
+ * hm_plan_one_launch_capacity(), 512 on an MI355X), and so are several in flight on separate
+ * streams as long as together they need no more than that.  Beyond it, or on a GPU that other
+ * kernels fill for longer than about 0.1 s, several plans can each hold part of the machine;
+ * their waits are bounded, so nothing hangs, but such a plan ends with HM_ERR_HIP in its status
+ * word and unwritten maps.  Callers that overlap that many plans lower the limit (0: always
+ * separate launches, which have no such need and cost a few microseconds more on small plans).
+ * Process-wide, takes effect for later calls; returns the previous limit.  The results do not
+ * depend on it.
  */
 int32_t hm_plan_one_launch_limit(int32_t workgroups);
+/* Workgroups of the one-launch plan that the current device holds at once (0 if unknown: then
+ * every plan takes separate launches).  Plans in flight together must not need more. */
+int32_t hm_plan_one_launch_capacity(void);
 
 /*
  * hm_plan_status -- waits for `hip_stream`, then returns the plan's device status word and

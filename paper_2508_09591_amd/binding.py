@@ -27,7 +27,7 @@ EXPORTS = ("hm_plan_workspace_bytes", "hm_plan", "hm_plan_status", "hm_dispatch_
            "hm_plan_mapped_workspace_bytes", "hm_plan_mapped", "hm_combine_mix", "hm_group_counts",
            "hm_alltoall_times", "hm_swap_workspace_bytes", "hm_swap_counts", "hm_swap_select_workspace_bytes",
            "hm_swap_select", "hm_level_dest_map", "hm_combine_f32", "hm_swap_apply",
-           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16", "hm_plan_one_launch_limit",
+           "hm_swap_counts_multi", "hm_swap_multi_workspace_bytes", "hm_combine_transpose_bf16", "hm_plan_one_launch_limit", "hm_plan_one_launch_capacity",
            "hm_plan_static", "hm_plan_static_max_bytes", "hm_combine_launch_shape")
 
 
@@ -73,6 +73,8 @@ def lib():
         L.hm_plan_static_max_bytes.argtypes = []
         L.hm_plan_one_launch_limit.restype = ctypes.c_int32
         L.hm_plan_one_launch_limit.argtypes = [ctypes.c_int32]
+        L.hm_plan_one_launch_capacity.restype = ctypes.c_int32
+        L.hm_plan_one_launch_capacity.argtypes = []
         L.hm_plan_static.restype = ctypes.c_int
         L.hm_plan_static.argtypes = [vp, vp, vp, i32, i32, i32, hm_topology, ctypes.c_int,
                                      ctypes.POINTER(hm_plan_out), vp]

@@ -23,8 +23,9 @@
 //   * larger plans take separate launches: plan_count_kernel (per-workgroup counts ->
 //     workspace), plan_scan_kernel once the matrix has kPlanScanMinEntries entries (one
 //     workgroup per destination turns it into exclusive prefixes plus a row of totals; below
-//     that every workgroup of the write kernel re-reads the small matrix itself), and
-//     plan_write_kernel.  Linear in the number of slots at any size.
+//     that every workgroup re-reads the small matrix itself), and the same kernel as above
+//     instantiated without its grid-wide wait (plan_fused_kernel<false>: the counts are complete
+//     when it starts).  Linear in the number of slots at any size.
 #include "hm_device.h"
 
 #include <unistd.h>
@@ -39,7 +40,6 @@ constexpr int kPlanThreads = 1024;
 constexpr int kPlanWaves = kPlanThreads / kWave;
 constexpr int kPlanHalo = 63;                              // K - 1 <= 63
 constexpr int kPlanStaged = kPlanThreads + 2 * kPlanHalo;
-constexpr int kPlanHist = 8192;                            // experts histogrammed in LDS for the fused loads
 constexpr int64_t kPlanScanMinEntries = 16384;             // count-matrix entries from which the scan launch pays
 constexpr int kPlanFusedMaxBlocks = 256;                   // largest plan (in workgroups) the one-launch kernel takes
 constexpr int kPlanSpinLimit = 1 << 18;                    // polls of the grid barrier before a wave gives up
@@ -78,14 +78,12 @@ struct Slot {
 // slot.  A slot owns its (token, destination) row at level none always, else iff no earlier slot
 // of the token has the same destination: the OR over a group's experts in Eq.(7) leaves one copy
 // per group, and the lowest k keeps it.
-__device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *s_rank, int8_t *s_dest,
-                                                   float *s_weight = nullptr) {
+__device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *s_rank, int8_t *s_dest) {
   const int halo = p.K - 1;
   const int64_t first = (int64_t)blockIdx.x * kPlanThreads;
   for (int i = threadIdx.x; i < kPlanThreads + 2 * halo; i += kPlanThreads) {
     const int64_t s = first - halo + i;
     int r = -1, d = -1;
-    if (s_weight) s_weight[i] = (s >= 0 && s < p.nslots) ? p.weights[s] : 0.0f;   // in flight with the id lookups
     if (s >= 0 && s < p.nslots) {
       if (p.dest_map) {
         const int id = p.ids[s];
@@ -126,7 +124,7 @@ __device__ __forceinline__ Slot stage_and_classify(const PlanParams &p, int8_t *
   return me;
 }
 
-__global__ __launch_bounds__(kPlanThreads) void plan_count_kernel(PlanParams p) {
+__global__ __launch_bounds__(kPlanThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void plan_count_kernel(PlanParams p) {
   __shared__ int8_t s_rank[kPlanStaged];
   __shared__ int8_t s_dest[kPlanStaged];
   __shared__ int32_t wave_cnt[kPlanWaves][kWave];
@@ -186,156 +184,6 @@ __global__ __launch_bounds__(kPlanThreads) void plan_scan_kernel(PlanParams p) {
   if (threadIdx.x == 0) p.counts[(int64_t)p.nblocks * p.Dn + d] = carry;
 }
 
-__global__ __launch_bounds__(kPlanThreads) void plan_write_kernel(PlanParams p) {
-  __shared__ int8_t s_rank[kPlanStaged];
-  __shared__ int8_t s_dest[kPlanStaged];
-  __shared__ int32_t part_tot[kPlanWaves][kWave];
-  __shared__ int32_t part_pre[kPlanWaves][kWave];
-  __shared__ int32_t block_base[kWave];             // first row of this workgroup per destination
-  __shared__ uint64_t ballots[kPlanWaves][kWave];   // [wave][destination] -> lanes that keep a slot
-  __shared__ int32_t wave_base[kPlanWaves][kWave];  // kept slots in earlier waves of the workgroup
-  extern __shared__ int32_t hist[];                 // fused expert load: slots per expert (E entries, only if asked for)
-  __shared__ int32_t blk_rank[kWave], blk_node[kWave];
-  __shared__ float s_weight[kPlanStaged];           // router weights of the staged slots
-  const int lane = lane_id(), wv = (int)(threadIdx.x >> 6);
-  const bool loads = p.load_expert != nullptr;
-  const bool lds_hist = p.E <= kPlanHist;
-  if (loads) {
-    if (lds_hist)
-      for (int e = threadIdx.x; e < p.E; e += kPlanThreads) hist[e] = 0;
-    if (threadIdx.x < kWave) blk_rank[threadIdx.x] = blk_node[threadIdx.x] = 0;
-  }
-
-  // Column sums of the count matrix: over all workgroups (destination total) and over the
-  // earlier ones (this workgroup's base).  Wave wv takes rows wv, wv+16, ...
-  {
-    int tot = 0, pre = 0;
-    if (p.scanned) {
-      if (wv == 0 && lane < p.Dn) {
-        tot = p.counts[(int64_t)p.nblocks * p.Dn + lane];
-        pre = p.counts[(int64_t)blockIdx.x * p.Dn + lane];
-      }
-    } else if (lane < p.Dn) {
-      for (int b = wv; b < p.nblocks; b += kPlanWaves) {
-        const int c = p.counts[(int64_t)b * p.Dn + lane];
-        tot += c;
-        if (b < (int)blockIdx.x) pre += c;
-      }
-    }
-    part_tot[wv][lane] = tot;
-    part_pre[wv][lane] = pre;
-  }
-
-  const int64_t s = (int64_t)blockIdx.x * kPlanThreads + threadIdx.x;
-  int my_id = -1;   // for the expert histogram; fetched now so that it does not cost a round trip later
-  if (loads && s < p.nslots) my_id = p.ids[s];
-  const Slot me = stage_and_classify(p, s_rank, s_dest, s_weight);   // contains a barrier
-  const int kept_dest = me.keep ? me.dest : -1;
-  for (int d = 0; d < p.Dn; ++d) {
-    const uint64_t b = __ballot(kept_dest == d);
-    if (lane == d) ballots[wv][d] = b;
-  }
-  __syncthreads();
-
-  if (lane < p.Dn) {
-    int a = 0;
-    for (int w = 0; w < wv; ++w) a += __popcll(ballots[w][lane]);
-    wave_base[wv][lane] = a;
-  }
-  if (wv == 0) {
-    int tot = 0, pre = 0;
-    if (lane < p.Dn)
-      for (int w = 0; w < kPlanWaves; ++w) {
-        tot += part_tot[w][lane];
-        pre += part_pre[w][lane];
-      }
-    int incl = tot;  // inclusive scan over destinations (lanes >= Dn hold 0)
-    for (int off = 1; off < kWave; off <<= 1) {
-      const int v = __shfl_up(incl, off, kWave);
-      if (lane >= off) incl += v;
-    }
-    const int offset = incl - tot;
-    block_base[lane] = offset + pre;
-    if (blockIdx.x == 0 && lane < p.Dn) {
-      p.dest_count[lane] = tot;
-      p.dest_offset[lane] = offset;
-      if (lane == p.Dn - 1) p.dest_offset[p.Dn] = incl;
-    }
-  }
-  __syncthreads();
-
-  if (me.live) {
-    if (me.dest < 0) {
-      p.slot_row[s] = -1;
-      p.slot_keep[s] = 0;
-      if (me.rank == -1) flag(p.status, HM_ERR_BAD_ID);
-    } else if (!me.keep) {
-      p.slot_keep[s] = 0;  // its slot_row is written by the slot that owns the row
-    } else {
-      const uint64_t b = ballots[wv][me.dest];
-      const int pos = __popcll(b & ((1ull << lane) - 1ull));
-      const int row = block_base[me.dest] + wave_base[wv][me.dest] + pos;
-      p.slot_keep[s] = 1;
-      p.slot_row[s] = row;
-      float wsum = s_weight[me.tok0 + me.k];
-      if (p.level != HM_DEDUP_NONE) {
-        for (int k2 = me.k + 1; k2 < p.K; ++k2) {
-          if (s_dest[me.tok0 + k2] == me.dest) {
-            p.slot_row[s + (k2 - me.k)] = row;
-            wsum = wsum + s_weight[me.tok0 + k2];  // ascending k, fp32
-          }
-        }
-      }
-      if (row < p.row_capacity) {
-        p.row_token[row] = me.t;
-        p.row_weight[row] = wsum;
-      } else {
-        flag(p.status, HM_ERR_CAPACITY);
-      }
-    }
-  }
-  // Per-token masks, owned by the lane of the token's slot 0.
-  uint64_t rm = 0;
-  uint32_t nm = 0;
-  if (me.live && me.k == 0 && (p.rank_mask || p.node_mask || loads)) {
-    for (int k2 = 0; k2 < p.K; ++k2) {
-      const int r2 = s_rank[me.tok0 + k2];
-      if (r2 >= 0) {
-        rm |= 1ull << r2;
-        if (!p.dest_map) nm |= 1u << (r2 / p.R);
-      }
-    }
-    if (p.rank_mask) p.rank_mask[me.t] = rm;
-    if (p.node_mask) p.node_mask[me.t] = nm;
-  }
-  if (!loads) return;
-
-  // Fused hm_expert_load: slots per expert, and tokens per rank / node counted once each from the
-  // masks above (a ballot per group; lane g keeps the count of group g).
-  if (me.live && me.rank >= 0) {
-    if (lds_hist) atomicAdd(&hist[my_id], 1);
-    else atomicAdd(&p.load_expert[my_id], 1);
-  }
-  int my_rank_cnt = 0, my_node_cnt = 0;
-  const int nodes = p.G / p.R;
-  for (int g = 0; g < p.G; ++g) {
-    const uint64_t b = __ballot((rm >> g) & 1ull);
-    if (lane == g) my_rank_cnt = __popcll(b);
-  }
-  for (int n = 0; n < nodes; ++n) {
-    const uint64_t b = __ballot((nm >> n) & 1u);
-    if (lane == n) my_node_cnt = __popcll(b);
-  }
-  if (my_rank_cnt) atomicAdd(&blk_rank[lane], my_rank_cnt);
-  if (my_node_cnt) atomicAdd(&blk_node[lane], my_node_cnt);
-  __syncthreads();
-  if (lds_hist)
-    for (int e = threadIdx.x; e < p.E; e += kPlanThreads)
-      if (hist[e]) atomicAdd(&p.load_expert[e], hist[e]);
-  if ((int)threadIdx.x < p.G && blk_rank[threadIdx.x]) atomicAdd(&p.load_rank[threadIdx.x], blk_rank[threadIdx.x]);
-  if ((int)threadIdx.x < nodes && blk_node[threadIdx.x]) atomicAdd(&p.load_node[threadIdx.x], blk_node[threadIdx.x]);
-}
-
 // ---- one-launch plan ---------------------------------------------------------------------------
 // Words that another workgroup of the same launch reads or writes are accessed with device-scope
 // atomic loads and stores (the workgroups sit on different dies with caches of their own).
@@ -387,7 +235,10 @@ __device__ __forceinline__ int lookup_global(const PlanParams &p, int id) {
 // slots are fetched in the same round as the workgroup's own, and everything that does not need
 // the other workgroups' counts -- slot_keep, the masks, the LDS partials of the load counts --
 // is done while the counts are on their way.
-__global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, uint64_t *matrix, uint64_t *passed,
+// Eight waves per SIMD (two of these workgroups per CU) need at most 96 scalar registers; left alone
+// the compiler takes a few more for the many pointers of PlanParams and halves the occupancy.
+template <bool FUSED>
+__global__ __launch_bounds__(kPlanThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void plan_fused_kernel(PlanParams p, uint64_t *matrix, uint64_t *passed,
                                                                   uint64_t tag, int staged_table) {
   __shared__ int8_t s_rank[kPlanStaged];
   __shared__ int8_t s_node[kPlanStaged];
@@ -445,7 +296,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, 
   }
   if (threadIdx.x < kWave) blk_rank[threadIdx.x] = blk_node[threadIdx.x] = 0;
   if (threadIdx.x == 0) gave_up = 0;
-  if (bid == 0) {   // what the atomics of the other workgroups add to: out before this workgroup's counts are
+  if (FUSED && bid == 0) {   // what the atomics of the other workgroups add to: out before this workgroup's counts are
     if (threadIdx.x == 0) st_device(p.status, 0);
     if (loads) {
       for (int i = threadIdx.x; i < p.E; i += kPlanThreads) st_device(p.load_expert + i, 0);
@@ -522,7 +373,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, 
     int a = 0;
     for (int w1 = 0; w1 < wv; ++w1) a += __popcll(ballots[w1][lane]);
     wave_base[wv][lane] = a;
-    if (wv == kPlanWaves - 1)   // the last wave's base plus its own count is the workgroup's count
+    if (FUSED && wv == kPlanWaves - 1)   // the last wave's base plus its own count is the workgroup's count
       st_device(matrix + (int64_t)bid * p.Dn + lane, (tag << kTagShift) | (uint64_t)(a + __popcll(ballots[wv][lane])));
   }
 
@@ -558,21 +409,28 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, 
   }
   if (loads && me.live && me.rank >= 0 && staged_table) atomicAdd(&hist[id], 1);   // slots per expert, LDS partial
 
-  // ---- the count matrix: wave wv reads rows wv, wv+16, ..., lane = destination, and reads them
-  // again, as a whole wave, until every word carries this launch's tag
-  {
+  // ---- the count matrix: wave wv reads rows wv, wv+16, ..., lane = destination
+  if (FUSED) {   // ... and reads them again, as a whole wave, until every word carries this launch's tag
     int tot = 0, pre = 0;
     bool ready = false;
     for (int spin = 0; spin < kPlanSpinLimit; ++spin) {
       tot = pre = 0;
       bool mine = true;
       if (lane < p.Dn) {
-        for (int b = wv; b < p.nblocks; b += kPlanWaves) {
-          const uint64_t v = ld_device(matrix + (int64_t)b * p.Dn + lane);
-          mine = mine && (v >> kTagShift) == tag;
-          const int c = (int)(v & ((1u << kTagShift) - 1u));
-          tot += c;
-          if (b < bid) pre += c;
+        for (int b0 = wv; b0 < p.nblocks; b0 += 4 * kPlanWaves) {   // four rows in flight
+          uint64_t v[4];
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const int b = b0 + j * kPlanWaves;
+            v[j] = b < p.nblocks ? ld_device(matrix + (int64_t)b * p.Dn + lane) : (tag << kTagShift);
+          }
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            mine = mine && (v[j] >> kTagShift) == tag;
+            const int c = (int)(v[j] & ((1u << kTagShift) - 1u));
+            tot += c;
+            if (b0 + j * kPlanWaves < bid) pre += c;
+          }
         }
       }
       ready = __ballot(!mine) == 0ull;
@@ -582,11 +440,35 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, 
     part_tot[wv][lane] = tot;
     part_pre[wv][lane] = pre;
     if (!ready && lane == 0) gave_up = 1;
+  } else {   // an earlier launch left the counts (or, scanned, their prefixes and a row of totals) in p.counts
+    int tot = 0, pre = 0;
+    if (p.scanned) {
+      if (wv == 0 && lane < p.Dn) {
+        tot = p.counts[(int64_t)p.nblocks * p.Dn + lane];
+        pre = p.counts[(int64_t)bid * p.Dn + lane];
+      }
+    } else if (lane < p.Dn) {
+      for (int b0 = wv; b0 < p.nblocks; b0 += 8 * kPlanWaves) {   // eight rows in flight
+        int c[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int b = b0 + j * kPlanWaves;
+          c[j] = b < p.nblocks ? p.counts[(int64_t)b * p.Dn + lane] : 0;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          tot += c[j];
+          if (b0 + j * kPlanWaves < bid) pre += c[j];
+        }
+      }
+    }
+    part_tot[wv][lane] = tot;
+    part_pre[wv][lane] = pre;
   }
   __syncthreads();
   const bool go = gave_up == 0;   // uniform over the workgroup
   if (go) {
-    if (threadIdx.x == 0) st_device(passed + bid, tag);
+    if (FUSED && threadIdx.x == 0) st_device(passed + bid, tag);
     if (loads) {   // global atomics first: they complete in the shadow of the map stores
       const int nodes = p.G / p.R;
       if (staged_table) {
@@ -648,7 +530,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, 
   }
 
   // ---- workgroup 0 leaves matrix and flags clean (also when a wait gave up: the status word says so)
-  if (bid == 0) {
+  if (FUSED && bid == 0) {
     if (wv == 0 && go) {
       bool ok = true;
       for (int spin = 0; spin < kPlanSpinLimit; ++spin) {
@@ -754,7 +636,7 @@ static inline int fused_capacity() {
     int cus = 0, per_cu = 0;
     v = -1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, plan_fused_kernel, kPlanThreads,
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, plan_fused_kernel<true>, kPlanThreads,
                                                      kPlanStagedExperts * 6) == hipSuccess &&
         cus > 0 && per_cu > 0)
       v = cus * per_cu;
@@ -786,13 +668,12 @@ static std::atomic<int> one_launch_limit{kPlanFusedMaxBlocks};
 // p.nblocks, p.Dn and p.counts are set.
 static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
   const bool loads = p.load_expert != nullptr;
-  const unsigned hist_bytes = loads && p.E <= kPlanHist ? (unsigned)p.E * sizeof(int32_t) : 0u;
+  const int staged = p.E <= kPlanStagedExperts ? 1 : 0;   // tables (and histogram) in LDS
+  const unsigned lds = staged ? ((loads ? (unsigned)p.E * sizeof(int32_t) : 0u) + ((2u * (unsigned)p.E + 15u) & ~15u)) : 0u;
   if (p.nblocks <= one_launch_limit.load(std::memory_order_relaxed) && p.nblocks <= fused_capacity()) {
     p.scanned = 0;
-    const int staged = p.E <= kPlanStagedExperts ? 1 : 0;   // tables (and histogram) in LDS
-    const unsigned lds = staged ? ((loads ? (unsigned)p.E * sizeof(int32_t) : 0u) + ((2u * (unsigned)p.E + 15u) & ~15u)) : 0u;
     uint64_t *matrix = (uint64_t *)((char *)p.counts + plan_counts_bytes(p.nslots, p.Dn));
-    hipLaunchKernelGGL(plan_fused_kernel, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, matrix,
+    hipLaunchKernelGGL(plan_fused_kernel<true>, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, matrix,
                        matrix + (size_t)p.nblocks * p.Dn, next_tag(), staged);
     return hm_launch_status();
   }
@@ -803,11 +684,15 @@ static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
     hipLaunchKernelGGL(plan_scan_kernel, dim3(p.Dn), dim3(kPlanThreads), 0, stream, p);
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   }
-  hipLaunchKernelGGL(plan_write_kernel, dim3(p.nblocks), dim3(kPlanThreads), hist_bytes, stream, p);
+  // the same kernel without its grid-wide wait: the counts are complete
+  hipLaunchKernelGGL(plan_fused_kernel<false>, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, (uint64_t *)nullptr,
+                     (uint64_t *)nullptr, (uint64_t)0, staged);
   return hm_launch_status();
 }
 
 }  // namespace hm
+
+extern "C" int32_t hm_plan_one_launch_capacity(void) { return hm::fused_capacity(); }
 
 extern "C" int32_t hm_plan_one_launch_limit(int32_t workgroups) {
   const int v = workgroups < 0 ? 0 : workgroups > hm::kPlanFusedMaxBlocks ? hm::kPlanFusedMaxBlocks : workgroups;
