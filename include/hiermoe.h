@@ -138,8 +138,8 @@ hm_status hm_plan(const int32_t *topk_ids, const float *topk_weights, const int3
  * hm_plan_one_launch_limit -- plans of at most `workgroups` workgroups (1,024 routing slots each;
  * default and maximum 256) run as ONE launch whose workgroups wait for one another's counts, which
  * needs all of them resident on the GPU together.  One such plan always is (the library checks
- * hm_plan_one_launch_capacity(), 512 on an MI355X), and so are several in flight on separate
- * streams as long as together they need no more than that.  Beyond it, or on a GPU that other
+ * hm_plan_one_launch_capacity(): 256 on an MI355X, one workgroup per CU), and so are several in
+ * flight on separate streams as long as together they need no more than that.  Beyond it, or on a GPU that other
  * kernels fill for longer than about 0.1 s, several plans can each hold part of the machine;
  * their waits are bounded, so nothing hangs, but such a plan ends with HM_ERR_HIP in its status
  * word and unwritten maps.  Callers that overlap that many plans lower the limit (0: always

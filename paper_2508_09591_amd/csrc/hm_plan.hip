@@ -23,9 +23,9 @@
 //   * larger plans take separate launches: plan_count_kernel (per-workgroup counts ->
 //     workspace), plan_scan_kernel once the matrix has kPlanScanMinEntries entries (one
 //     workgroup per destination turns it into exclusive prefixes plus a row of totals; below
-//     that every workgroup re-reads the small matrix itself), and the same kernel as above
-//     instantiated without its grid-wide wait (plan_fused_kernel<false>: the counts are complete
-//     when it starts).  Linear in the number of slots at any size.
+//     that every workgroup re-reads the small matrix itself), and plan_write_kernel: the body of
+//     the one-launch kernel without its grid-wide wait (the counts are complete when it starts).
+//     Linear in the number of slots at any size.
 #include "hm_device.h"
 
 #include <unistd.h>
@@ -235,11 +235,9 @@ __device__ __forceinline__ int lookup_global(const PlanParams &p, int id) {
 // slots are fetched in the same round as the workgroup's own, and everything that does not need
 // the other workgroups' counts -- slot_keep, the masks, the LDS partials of the load counts --
 // is done while the counts are on their way.
-// Eight waves per SIMD (two of these workgroups per CU) need at most 96 scalar registers; left alone
-// the compiler takes a few more for the many pointers of PlanParams and halves the occupancy.
 template <bool FUSED>
-__global__ __launch_bounds__(kPlanThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void plan_fused_kernel(PlanParams p, uint64_t *matrix, uint64_t *passed,
-                                                                  uint64_t tag, int staged_table) {
+__device__ __forceinline__ void plan_body(const PlanParams &p, uint64_t *matrix, uint64_t *passed, uint64_t tag,
+                                          int staged_table) {
   __shared__ int8_t s_rank[kPlanStaged];
   __shared__ int8_t s_node[kPlanStaged];
   __shared__ int8_t s_dest[kPlanStaged];
@@ -547,6 +545,22 @@ __global__ __launch_bounds__(kPlanThreads) __attribute__((amdgpu_waves_per_eu(8,
   }
 }
 
+// The one-launch plan.  It runs one workgroup per CU at the sizes it is used for, so it takes the
+// scalar registers the compiler wants (106: the many pointers of PlanParams).
+__global__ __launch_bounds__(kPlanThreads) void plan_fused_kernel(PlanParams p, uint64_t *matrix, uint64_t *passed,
+                                                                  uint64_t tag, int staged_table) {
+  plan_body<true>(p, matrix, passed, tag, staged_table);
+}
+
+// The last launch of a large plan: the same body without the grid-wide wait.  Held to 96 scalar
+// registers, i.e. eight waves per SIMD, so that two workgroups fit a CU and the 512 workgroups of a
+// 64 Ki-token layer run in one round (thirty-odd scalars then live in vector lanes, which is
+// cheaper than a second round).
+__global__ __launch_bounds__(kPlanThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void plan_write_kernel(PlanParams p,
+                                                                                                      int staged_table) {
+  plan_body<false>(p, nullptr, nullptr, 0, staged_table);
+}
+
 // Table of one hop for a (parent, child) pair of group cuts: purely elementwise.
 __global__ __launch_bounds__(kPlanThreads) void level_dest_map_kernel(const int32_t *__restrict__ expert_to_rank, int E,
                                                                        int G, int my_rank, int ranks_per_parent,
@@ -636,7 +650,7 @@ static inline int fused_capacity() {
     int cus = 0, per_cu = 0;
     v = -1;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, plan_fused_kernel<true>, kPlanThreads,
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, plan_fused_kernel, kPlanThreads,
                                                      kPlanStagedExperts * 6) == hipSuccess &&
         cus > 0 && per_cu > 0)
       v = cus * per_cu;
@@ -673,7 +687,7 @@ static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
   if (p.nblocks <= one_launch_limit.load(std::memory_order_relaxed) && p.nblocks <= fused_capacity()) {
     p.scanned = 0;
     uint64_t *matrix = (uint64_t *)((char *)p.counts + plan_counts_bytes(p.nslots, p.Dn));
-    hipLaunchKernelGGL(plan_fused_kernel<true>, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, matrix,
+    hipLaunchKernelGGL(plan_fused_kernel, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, matrix,
                        matrix + (size_t)p.nblocks * p.Dn, next_tag(), staged);
     return hm_launch_status();
   }
@@ -685,8 +699,7 @@ static inline hm_status launch_plan(PlanParams &p, hipStream_t stream) {
     if (hm_launch_status() != HM_OK) return HM_ERR_HIP;
   }
   // the same kernel without its grid-wide wait: the counts are complete
-  hipLaunchKernelGGL(plan_fused_kernel<false>, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, (uint64_t *)nullptr,
-                     (uint64_t *)nullptr, (uint64_t)0, staged);
+  hipLaunchKernelGGL(plan_write_kernel, dim3(p.nblocks), dim3(kPlanThreads), lds, stream, p, staged);
   return hm_launch_status();
 }
 
